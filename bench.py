@@ -1,0 +1,323 @@
+#!/usr/bin/env python3
+"""Benchmark of the sharded weight-update hot path on one MI355X.
+
+Headline workload (the configuration the metric is quoted on): BERT-large-shaped, 398 float32
+variables, 336 226 108 parameters, LAMB, 8 replicas; this GPU plays replica 0 and owns a packed
+shard of S = 42 028 272 slots.  One step is one pass of the whole path over synthetic inputs
+already resident in HBM:
+
+    shard_format(full gradient tensors -> g[S])                          stage 1
+    shard_update_lamb(w, g, m, v; other replicas' sums given)            stage 2 (3 kernels)
+    unshard_format(gathered[N][S] -> full float32 weight tensors)        stage 3
+
+The cross-replica collectives are not part of the path: the gathered buffer's other rows and the
+other replicas' sums of squares are synthetic inputs.  `value` is the number of real parameters
+in the shard divided by the time of one step.  Per-kernel durations come from HIP events the
+library records on the launch stream (shard_profile_*), in a separate instrumented pass.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+# algorithmic bytes per shard slot (float32 = 4 B), per kernel
+BYTES_PER_SLOT = {
+    "format": 8,       # read 4 + write 4
+    "lamb_p1": 24,     # read g, w, m, v; write m, v
+    "lamb_p2": 16,     # read w, m, v; write w
+    "adam": 28,        # read g, w, m, v; write w, m, v
+    "momentum": 20,    # read g, w, m; write w, m
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="bert_large")
+    ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--replica-id", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=0, help="chunk_elems of the plan (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", default=None, help="also time every config x stage and write a JSON table here")
+    return ap.parse_args()
+
+
+def _device_normal(n, std, gen, torch):
+    return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, std, generator=gen)
+
+
+def _time_region(torch, fn, steps):
+    """Milliseconds per call of fn over `steps` back-to-back calls, bracketed by synchronisation."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(stop) / steps, wall_ms / steps
+
+
+class Workbench:
+    """Device state of one replica of one configuration."""
+
+    def __init__(self, cfg, N, r, chunk, torch, su, want_full=True):
+        self.cfg, self.N, self.r, self.torch, self.su = cfg, N, r, torch, su
+        self.plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8, None, chunk))
+        S = self.plan.S
+        self.S = S
+        self.real = sum(self.plan.real_count(r))
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(cfg.seed)
+        self.gen = gen
+        # the gathered [N][S] buffer; row r is this replica's weight shard, updated in place
+        self.gathered = _device_normal(N * S, cfg.weight_std, gen, torch).view(N, S) if want_full else None
+        self.w = self.gathered[r] if want_full else _device_normal(S, cfg.weight_std, gen, torch)
+        self.g = torch.zeros(S, dtype=torch.float32, device="cuda")
+        self.m = torch.zeros(S, dtype=torch.float32, device="cuda")
+        self.v = torch.zeros(S, dtype=torch.float32, device="cuda")
+        self.w16 = None
+        self.full_g = self.full_w = None
+        if want_full:
+            flat_g = _device_normal(cfg.total, cfg.grad_std, gen, torch)
+            flat_w = torch.empty(cfg.total, dtype=torch.float32, device="cuda")
+            self.full_g, self.full_w, pos = [], [], 0
+            for n in cfg.numel:
+                self.full_g.append(flat_g[pos:pos + n])
+                self.full_w.append(flat_w[pos:pos + n])
+                pos += n
+            # zero the padded slots of row r (other rows' padding is never read by unshard_format)
+            su.shard_format(self.plan, r, self.full_g, self.g)
+        else:
+            self.g.normal_(0.0, cfg.grad_std, generator=gen)
+        self.other = torch.zeros((self.plan.V, 2), dtype=torch.float32, device="cuda")
+        self.local = torch.zeros((self.plan.V, 2), dtype=torch.float32, device="cuda")
+        self.step = 0
+
+    def hp(self):
+        import numpy as np
+        return {k: float(np.float32(v)) for k, v in self.cfg.hyper.items()}
+
+    def free(self):
+        self.plan.free()
+
+
+def headline(args, torch, su, cfgs):
+    cfg = [c for c in cfgs if c.name == args.config][0]
+    N, r = args.replicas, args.replica_id
+    wb = Workbench(cfg, N, r, args.chunk, torch, su)
+    hp = wb.hp()
+    plan = wb.plan
+    if cfg.optimizer != "lamb":
+        raise SystemExit("the headline step is the LAMB configuration; use --table for the others")
+    # clean padding in this replica's weight row, then pre-warm m and v by two steps so no lane
+    # works on all-zero state; the other replicas' sums are (N-1) copies of this replica's
+    wb_full_w_src = [t.clone() for t in wb.full_w]
+    for t, n in zip(wb_full_w_src, cfg.numel):
+        t.normal_(0.0, cfg.weight_std, generator=wb.gen)
+    su.shard_format(plan, r, wb_full_w_src, wb.w)
+    del wb_full_w_src
+    su.shard_update_lamb_partials(plan, r, wb.w, wb.g, wb.m, wb.v, hp, 1, wb.local)
+    wb.m.zero_(); wb.v.zero_()
+    wb.other.copy_(wb.local * float(N - 1))
+    state = {"t": 0}
+
+    def one_step():
+        state["t"] += 1
+        su.shard_format(plan, r, wb.full_g, wb.g)
+        su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, hp, state["t"], other_replicas_sumsq=wb.other)
+        su.unshard_format(plan, wb.gathered, wb.full_w)
+
+    for _ in range(max(args.warmup, 2)):
+        one_step()
+    ms_step, wall_ms = _time_region(torch, one_step, args.steps)
+
+    # instrumented pass: the same K steps with an event pair around every kernel
+    su.shard_profile_reset(plan)
+    su.shard_profile_enable(plan, True)
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    kern = {}
+    for name in ("format", "lamb_p1", "norm_reduce", "lamb_p2", "unshard", "ptr_table"):
+        n, ms = su.shard_profile_read(plan, name)
+        if n:
+            kern[name] = {"launches": n, "avg_us": 1e3 * ms / n}
+    su.shard_profile_enable(plan, False)
+
+    S = wb.S
+    alg_bytes = {
+        "format": BYTES_PER_SLOT["format"] * S,
+        "lamb_p1": BYTES_PER_SLOT["lamb_p1"] * S,
+        "lamb_p2": BYTES_PER_SLOT["lamb_p2"] * S,
+        "unshard": 4 * N * S + 4 * cfg.total,
+    }
+    rooflines = {}
+    for name, b in alg_bytes.items():
+        if name in kern:
+            gbs = b / (kern[name]["avg_us"] * 1e-6) / 1e9
+            rooflines[name] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": round(gbs / HBM_PEAK_GBS, 4), "avg_us": round(kern[name]["avg_us"], 2),
+                               "bytes": b}
+    dominant = max(rooflines, key=lambda k: rooflines[k]["avg_us"])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dominant + "_kernel")
+        except Exception:
+            traffic = None
+    roof = dict(rooflines[dominant])
+    roof["kernel"] = dominant + "_kernel"
+    roof["traffic"] = traffic
+    lamb_us = sum(kern[k]["avg_us"] for k in ("lamb_p1", "norm_reduce", "lamb_p2") if k in kern)
+    update_only = {
+        "kernels_us": round(lamb_us, 2),
+        "params_per_s": wb.real / (lamb_us * 1e-6),
+        "GBps": round(40 * S / (lamb_us * 1e-6) / 1e9, 1),
+        "frac_of_hbm_peak": round(40 * S / (lamb_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    out = {
+        "metric": "shard weight-update params/s (340M LAMB, N=8, one replica's shard)",
+        "value": wb.real / (ms_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s fp32 LAMB N=%d r=%d: shard_format(g) + shard_update_lamb + unshard_format(w)"
+                               % (cfg.name, N, r),
+                   "variables": plan.V, "params": cfg.total, "shard_slots": S, "shard_params": wb.real,
+                   "chunk_elems": args.chunk or 4096},
+        "roofline": roof,
+        "kernels": rooflines,
+        "update_only": update_only,
+        "wall_ms_per_step": round(wall_ms, 5),
+    }
+    wb.free()
+    return out
+
+
+def cpu_baseline(cfg, N, r):
+    """The oracle, as it stands, on one step of the same workload; numpy runs single-threaded."""
+    import numpy as np
+    import oracle
+    from workloads import normal_f32
+    hp = {k: float(np.float32(v)) for k, v in cfg.hyper.items()}
+    plan = oracle.make_plan(cfg.numel, N, 8)
+    gs = [normal_f32(cfg.seed, i, "g", n, cfg.grad_std, 1) for i, n in enumerate(cfg.numel)]
+    gathered = np.zeros((N, plan.S), np.float32)
+    rng = np.random.default_rng(cfg.seed)
+    gathered[r] = oracle.shard_format(plan, r, [normal_f32(cfg.seed, i, "w", n, cfg.weight_std)
+                                                for i, n in enumerate(cfg.numel)])
+    m = np.zeros(plan.S, np.float32); v = np.zeros(plan.S, np.float32)
+    del rng
+    t0 = time.perf_counter()
+    g = oracle.shard_format(plan, r, gs)
+    m, v, u, part = oracle.lamb_shard_partials(plan, r, gathered[r], g, m, v, hp, 1)
+    gathered[r] = oracle.lamb_shard_apply(plan, gathered[r], u, part * N, hp)
+    full = oracle.unshard_format(plan, gathered)
+    dt = time.perf_counter() - t0
+    real = sum(plan.real_count(i, r) for i in range(plan.V))
+    assert len(full) == plan.V
+    return {"value": real / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "1 step of the same workload (%s N=%d r=%d, all %d variables: format g, LAMB on the shard, "
+                      "unformat the whole model), %.1f s" % (cfg.name, N, r, plan.V, dt),
+            "seconds": round(dt, 2)}
+
+
+def table(args, torch, su, cfgs, path):
+    """Every config x stage, kernel time from the library's event pairs; written as JSON."""
+    rows = []
+    for cfg in cfgs:
+        for N in cfg.replicas:
+            r = 0
+            big = cfg.total > 1_000_000_000
+            wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=not (big and N == 1))
+            plan, hp, S = wb.plan, wb.hp(), wb.S
+            if cfg.mixed_bf16:
+                wb.w16 = torch.zeros(S, dtype=torch.bfloat16, device="cuda")
+            stages = []
+            if cfg.optimizer == "adam":
+                stages.append(("adam", lambda t: su.shard_update_adam(plan, r, wb.w, wb.g, wb.m, wb.v, hp, t,
+                                                                      w_bf16_out=wb.w16),
+                               ["adam"], (30 if cfg.mixed_bf16 else 28) * S))
+            elif cfg.optimizer == "momentum":
+                stages.append(("momentum", lambda t: su.shard_update_momentum(plan, r, wb.w, wb.g, wb.m, hp),
+                               ["momentum"], 20 * S))
+            else:
+                stages.append(("lamb", lambda t: su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, hp, t,
+                                                                      other_replicas_sumsq=wb.other),
+                               ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S))
+            if wb.full_g is not None:
+                stages.append(("shard_format", lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S))
+                stages.append(("unshard_format", lambda t: su.unshard_format(plan, wb.gathered, wb.full_w),
+                               ["unshard"], 4 * N * S + 4 * cfg.total))
+            for name, fn, kernels, nbytes in stages:
+                for t in range(1, 6):
+                    fn(t)
+                su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+                iters = 50
+                for t in range(6, 6 + iters):
+                    fn(t)
+                torch.cuda.synchronize()
+                us = 0.0
+                for k in kernels:
+                    n, ms = su.shard_profile_read(plan, k)
+                    us += 1e3 * ms / max(n, 1)
+                su.shard_profile_enable(plan, False)
+                state_bytes = nbytes
+                rows.append({"config": cfg.name, "N": N, "stage": name, "S": S, "kernel_us": round(us, 2),
+                             "params_per_s": wb.real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                             "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                             "cache_resident": state_bytes < 256e6})
+                print("table:", rows[-1], file=sys.stderr, flush=True)
+            wb.free()
+            del wb
+            torch.cuda.empty_cache()
+    with open(path, "w") as f:
+        json.dump(rows, f, indent=1)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one replica's shard on ONE GPU; --gpus %d is not supported "
+              "(the cross-replica collectives are outside this library)" % args.gpus, file=sys.stderr)
+        raise SystemExit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        raise SystemExit(2)
+    import paper_2004_13336_amd as su
+    from workloads import CONFIGS
+    su.lib()
+    out = headline(args, torch, su, CONFIGS)
+    if args.table:
+        table(args, torch, su, CONFIGS, args.table)
+    if not args.no_cpu_baseline:
+        torch.cuda.empty_cache()
+        cfg = [c for c in CONFIGS if c.name == args.config][0]
+        out["cpu_baseline"] = cpu_baseline(cfg, args.replicas, args.replica_id)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,205 @@
+/*
+ * shardupdate: the per-replica hot path of cross-replica weight-update sharding
+ * (Xu et al., "Automatic Cross-Replica Sharding of Weight Update in Data-Parallel
+ * Training"), hand-written for AMD MI355X (gfx950).
+ *
+ * One replica out of N owns 1/N of every variable.  The library
+ *   (1) formats full tensors into that replica's packed shard        (shard_format),
+ *   (2) runs the fused optimizer update on the shard                 (shard_update_*),
+ *   (3) restores full tensors from the N gathered shards             (unshard_format).
+ * The three calls mirror the paper's sharding program / main program / unsharding
+ * program (Section 4.2, "Out-of-loop all-gather placement").  The cross-replica
+ * reduce-scatter, all-gather and scalar all-reduce are NOT part of this library: the
+ * shard gradient is an input, the gathered [N][S] buffer is an input, and LAMB's
+ * per-variable sums of squares are exported / imported as plain device arrays.
+ *
+ * Layout (Section 4.1, "Data formatting"; Section 5.2, "Batched communication operators").
+ * Variable i has n_i elements, taken in row-major order (flattening moves no data).
+ *     L_i   = roundup(ceil(n_i / N), align)         piece length, equal on all replicas
+ *     off_i = L_0 + ... + L_{i-1},   S = sum L_i    one piece of every variable per shard
+ *     shard_r[off_i + k] = (r*L_i + k < n_i) ? var_i[r*L_i + k] : +0.0     0 <= k < L_i
+ *     gathered[r][..]    = shard_r                                          shape [N][S]
+ * Gradient, weight and every auxiliary variable use the same plan (Section 4.1: all
+ * inputs of the update must be sharded the same way).
+ *
+ * Conventions.
+ *  - Every function returns an int status: SHARD_OK (0) or a negative SHARD_E* code.
+ *    Nothing throws, aborts or prints.
+ *  - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *    ordinary process memory.  The library allocates no device memory: every device
+ *    buffer, including the plan's tables (shard_plan_bind), is the caller's.
+ *  - Device buffers of packed shards (w, g, m, v, shard_out, gathered, bf16 outputs,
+ *    sums) must be 16-byte aligned, else SHARD_EALIGN.  Full tensors may have any
+ *    alignment; 16-byte aligned ones (with align_elems a multiple of 8) take the
+ *    128-bit path, others a slower element-wise path with the same results.
+ *  - Kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *    stream) and are asynchronous; errors reported are argument and launch errors.
+ *  - A plan is not thread-safe, and calls that use one plan must be ordered on one
+ *    stream (or otherwise synchronised by the caller): they share the plan's workspace.
+ */
+#ifndef SHARDUPDATE_H
+#define SHARDUPDATE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct shard_plan_s shard_plan_t;   /* opaque host object */
+typedef void* shard_stream_t;             /* hipStream_t */
+
+enum {
+  SHARD_OK = 0,
+  SHARD_EINVAL = -1,   /* bad argument (null pointer, r outside [0,N), step < 1, eps <= 0, ...) */
+  SHARD_ENOMEM = -2,   /* host allocation failed, or workspace too small */
+  SHARD_EALIGN = -3,   /* a packed-shard device pointer is not 16-byte aligned */
+  SHARD_EHIP = -4,     /* the HIP runtime reported an error (no device, launch failure) */
+  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one */
+};
+
+enum { SHARD_F32 = 0, SHARD_BF16 = 1 };   /* element types of formatted buffers */
+
+/* Per-variable flags (LAMB only). */
+enum {
+  SHARD_VAR_NO_DECAY = 1u,   /* weight decay is not applied to this variable */
+  SHARD_VAR_NO_ADAPT = 2u    /* the trust ratio of this variable is fixed at 1 */
+};
+
+/* Kernel ids for shard_profile_read. */
+enum {
+  SHARD_K_FORMAT = 0, SHARD_K_UNSHARD = 1, SHARD_K_ADAM = 2, SHARD_K_MOMENTUM = 3,
+  SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
+  SHARD_K_COUNT = 8
+};
+
+const char* shard_strerror(int status);
+const char* shard_kernel_name(int kernel_id);   /* NULL if out of range */
+
+/* ------------------------------------------------------------------------------------------
+ * shard_plan: the sharding representation (Section 4.1: formatting steps followed by a slice
+ * whose offset is a function of the replica id).  Host only, integer arithmetic.
+ *   V            number of variables (>= 0)
+ *   numel        host array [V], n_i >= 0 (0 is legal and gives L_i = 0)
+ *   N            replica count (>= 1)
+ *   align_elems  power of two >= 1; the piece granule in elements (8 keeps fp32 and bf16
+ *                pieces 16-byte aligned; 1 is the paper's bare ceil(n/N))
+ *   var_flags    host array [V] of SHARD_VAR_* bits, or NULL for all zero
+ *   chunk_elems  work-item size of the table-driven kernels; 0 picks the tuned default,
+ *                otherwise a multiple of 1024 in [1024, 16384]
+ *   out          receives the plan; free with shard_plan_free
+ * Errors: SHARD_EINVAL, SHARD_ENOMEM.
+ */
+int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32_t* var_flags,
+               int chunk_elems, shard_plan_t** out);
+
+/* Sizes of a plan.  Any out pointer may be NULL.
+ *   S                packed shard length in elements
+ *   total            sum of n_i
+ *   n_chunks         entries of the chunk table (a chunk never crosses a variable boundary)
+ *   workspace_bytes  device bytes shard_plan_bind needs
+ */
+int shard_plan_info(const shard_plan_t* plan, int64_t* S, int64_t* total, int64_t* n_chunks,
+                    size_t* workspace_bytes);
+
+/* Copies off_i and L_i into host arrays [V] (either may be NULL). */
+int shard_plan_segments(const shard_plan_t* plan, int64_t* seg_off, int64_t* seg_len);
+
+/* Host array real[V]: how many of replica r's L_i slots hold real (unpadded) elements. */
+int shard_plan_real_count(const shard_plan_t* plan, int r, int64_t* real);
+
+/* Uploads the plan's tables into caller-owned device memory of at least workspace_bytes
+ * (256-byte aligned) and remembers it.  The memory must stay valid, and must not be written
+ * by the caller, until the plan is freed or bound elsewhere.  The copy is enqueued on
+ * `stream`; later calls on the same stream see it. */
+int shard_plan_bind(shard_plan_t* plan, void* device_workspace, size_t bytes, shard_stream_t stream);
+
+void shard_plan_free(shard_plan_t* plan);
+
+/* ------------------------------------------------------------------------------------------
+ * shard_format: replica r's zero-padded piece of every variable, packed (Section 4.1: the pad
+ * is fused into the slice, so only about S elements of the inputs are read).
+ *   full_ptrs  HOST array [V] of DEVICE pointers to the full variables (n_i elements of
+ *              src_dtype each; entries of empty variables may be NULL)
+ *   shard_out  device [S] of dst_dtype
+ * dtype pairs: f32->f32 and bf16->bf16 move bits unchanged (NaN payloads, -0.0 survive);
+ * f32->bf16 rounds to nearest even (NaN stays NaN, sign kept); bf16->f32 widens exactly.
+ * Needs a bound plan.
+ */
+int shard_format(shard_plan_t* plan, int r, const void* const* full_ptrs, int src_dtype,
+                 void* shard_out, int dst_dtype, shard_stream_t stream);
+
+/* unshard_format: the reverse formatting after the all-gather (Section 4.2).  Reads
+ * gathered[N][S] (device, src_dtype) and writes every full variable (device pointers in the
+ * HOST array full_ptrs[V], dst_dtype), dropping the padding.  Same dtype pairs as shard_format
+ * (f32->bf16 is the reduced-precision weight the forward pass needs, Section 4.2). */
+int unshard_format(shard_plan_t* plan, const void* gathered, int src_dtype,
+                   void* const* full_ptrs, int dst_dtype, shard_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Fused optimizer updates on one packed shard (Section 2.2: read gradient, weight and
+ * auxiliaries, write weight and auxiliaries; all float32).  w, m, v are updated in place;
+ * g is only read.  w_bf16_out, if not NULL, receives bf16(w') [S] (Section 4.2, Figure
+ * "all-gather in bfloat16").  Padded slots hold +0.0 and stay +0.0.
+ *
+ * Adam:     g' = g + wd*w;  m = b1*m + (1-b1)*g';  v = b2*v + (1-b2)*g'^2
+ *           w -= lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)           t = step >= 1
+ * Momentum: g' = g + wd*w;  m = mu*m + g';  w -= lr*m
+ * Requirements: 0 <= beta < 1, eps > 0, step >= 1, else SHARD_EINVAL.
+ */
+typedef struct { float lr, beta1, beta2, eps, weight_decay; } shard_adam_hp;
+typedef struct { float lr, mu, weight_decay; } shard_momentum_hp;
+typedef struct { float lr, beta1, beta2, eps, weight_decay; } shard_lamb_hp;
+
+int shard_update_adam(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
+                      void* w_bf16_out, const shard_adam_hp* hp, int64_t step, shard_stream_t stream);
+
+int shard_update_momentum(shard_plan_t* plan, int r, float* w, const float* g, float* m,
+                          void* w_bf16_out, const shard_momentum_hp* hp, shard_stream_t stream);
+
+/* LAMB, a non-elementwise optimizer on a shard (Section 4.1, "Non-elementwise operators":
+ * mask the padding by position, reduce locally, all-reduce the scalars, then apply).
+ *   m, v as Adam (no decay folded in);  u = m_hat/(sqrt(v_hat)+eps) + wd_i*w
+ *   per variable i, over ALL replicas:  ratio_i = ||w_i|| / ||u_i||  (1 if either norm is 0
+ *   or the variable has SHARD_VAR_NO_ADAPT);  w -= lr * ratio_i * u
+ * Sums of squares are exchanged as float32 tables [V][2] = {sum w^2, sum u^2} in device memory.
+ *
+ * shard_update_lamb_partials: phase 1.  Updates m and v, leaves w untouched, and writes this
+ *   replica's sums over its real elements into local_sumsq_out (padding is masked by
+ *   position, whatever the padded slots hold).
+ * shard_update_lamb_apply: phase 2.  global_sumsq is the element-wise sum of all replicas'
+ *   tables (the scalar all-reduce the caller performs).  Must see the m, v that phase 1 wrote
+ *   and the w phase 1 read.
+ * shard_update_lamb: both phases in one call; other_replicas_sumsq (may be NULL = zeros) is
+ *   added to the local table in place of the all-reduce, and local_sumsq_out (may be NULL)
+ *   receives the local table.
+ * All need a bound plan.  The reduction order is fixed: results are run-to-run identical.
+ */
+int shard_update_lamb_partials(shard_plan_t* plan, int r, const float* w, const float* g, float* m, float* v,
+                               const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out,
+                               shard_stream_t stream);
+
+int shard_update_lamb_apply(shard_plan_t* plan, int r, float* w, const float* m, const float* v,
+                            void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
+                            const float* global_sumsq, shard_stream_t stream);
+
+int shard_update_lamb(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
+                      void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
+                      const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Per-kernel timing with HIP events recorded on the launch stream, for benchmarks.
+ * shard_profile_enable(plan, 1) makes every later launch through this plan record an event
+ * pair; shard_profile_read synchronises with the recorded events and returns, for one kernel
+ * id, the number of launches and their summed duration in milliseconds since the last
+ * shard_profile_reset.  Off by default; costs nothing when off.
+ */
+int shard_profile_enable(shard_plan_t* plan, int on);
+int shard_profile_read(shard_plan_t* plan, int kernel_id, int64_t* launches, double* total_ms);
+int shard_profile_reset(shard_plan_t* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHARDUPDATE_H */

@@ -1,0 +1,75 @@
+"""ctypes loader for libshardupdate.so.  There is no fallback: without the HIP library nothing runs."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+from .build import LIB_PATH, build_library
+
+_lib = None
+
+
+class ShardError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = "unknown"
+        try:
+            msg = lib().shard_strerror(status).decode()
+        except Exception:
+            pass
+        super().__init__("%s failed: %s (status %d)" % (where, msg, status))
+
+
+class AdamHP(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
+
+
+class MomentumHP(C.Structure):
+    _fields_ = [("lr", C.c_float), ("mu", C.c_float), ("weight_decay", C.c_float)]
+
+
+class LambHP(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
+
+
+_P = C.c_void_p
+_I64P = C.POINTER(C.c_int64)
+
+# name -> (restype, argtypes); mirrors include/shardupdate.h declaration by declaration
+SIGNATURES = {
+    "shard_strerror": (C.c_char_p, [C.c_int]),
+    "shard_kernel_name": (C.c_char_p, [C.c_int]),
+    "shard_plan": (C.c_int, [C.c_int, _I64P, C.c_int, C.c_int, C.POINTER(C.c_uint32), C.c_int, C.POINTER(_P)]),
+    "shard_plan_info": (C.c_int, [_P, _I64P, _I64P, _I64P, C.POINTER(C.c_size_t)]),
+    "shard_plan_segments": (C.c_int, [_P, _I64P, _I64P]),
+    "shard_plan_real_count": (C.c_int, [_P, C.c_int, _I64P]),
+    "shard_plan_bind": (C.c_int, [_P, _P, C.c_size_t, _P]),
+    "shard_plan_free": (None, [_P]),
+    "shard_format": (C.c_int, [_P, C.c_int, C.POINTER(_P), C.c_int, _P, C.c_int, _P]),
+    "unshard_format": (C.c_int, [_P, _P, C.c_int, C.POINTER(_P), C.c_int, _P]),
+    "shard_update_adam": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(AdamHP), C.c_int64, _P]),
+    "shard_update_momentum": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(MomentumHP), _P]),
+    "shard_update_lamb_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
+    "shard_update_lamb_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
+    "shard_update_lamb": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P, _P]),
+    "shard_profile_enable": (C.c_int, [_P, C.c_int]),
+    "shard_profile_read": (C.c_int, [_P, C.c_int, _I64P, C.POINTER(C.c_double)]),
+    "shard_profile_reset": (C.c_int, [_P]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded library; built in-tree first if no built library is there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            build_library()
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)          # AttributeError if the library lacks a declared symbol
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib

@@ -1,0 +1,211 @@
+"""Thin Python binding of the C-ABI library: argument marshalling and size checks only.
+
+Function names and argument order follow include/shardupdate.h.  Tensors are torch CUDA
+tensors (torch provides device memory and streams, nothing else); every step of the path runs
+in the library's HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, Optional, Sequence, Tuple
+
+import torch
+
+from ._lib import AdamHP, LambHP, MomentumHP, ShardError, lib
+
+SHARD_F32, SHARD_BF16 = 0, 1
+SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
+KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
+              "lamb_p2": 6, "ptr_table": 7}
+
+_DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise ShardError(status, where)
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t: Optional[torch.Tensor], numel: int, dtype, what: str) -> C.c_void_p:
+    """Device pointer of a contiguous CUDA tensor with at least `numel` elements of `dtype`."""
+    if t is None:
+        return C.c_void_p(None)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous CUDA tensor" % what)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must have dtype %s, got %s" % (what, dtype, t.dtype))
+    if t.numel() < numel:
+        raise ValueError("%s holds %d elements, needs %d" % (what, t.numel(), numel))
+    return C.c_void_p(t.data_ptr())
+
+
+class Plan:
+    """Owner of a shard_plan_t handle (and of the workspace tensor, if it allocated one)."""
+
+    def __init__(self, numel: Sequence[int], N: int, align_elems: int = 8,
+                 var_flags: Optional[Sequence[int]] = None, chunk_elems: int = 0):
+        V = len(numel)
+        arr = (C.c_int64 * max(V, 1))(*[int(n) for n in numel])
+        flags = None
+        if var_flags is not None:
+            if len(var_flags) != V:
+                raise ValueError("var_flags must have one entry per variable")
+            flags = (C.c_uint32 * max(V, 1))(*[int(f) for f in var_flags])
+        handle = C.c_void_p()
+        _check(lib().shard_plan(V, arr, int(N), int(align_elems), flags, int(chunk_elems), C.byref(handle)),
+               "shard_plan")
+        self.handle = handle
+        self.V, self.N, self.align = V, int(N), int(align_elems)
+        self.numel = tuple(int(n) for n in numel)
+        S, total, nch, wsb = C.c_int64(), C.c_int64(), C.c_int64(), C.c_size_t()
+        _check(lib().shard_plan_info(handle, C.byref(S), C.byref(total), C.byref(nch), C.byref(wsb)),
+               "shard_plan_info")
+        self.S, self.total, self.n_chunks, self.workspace_bytes = S.value, total.value, nch.value, wsb.value
+        self.workspace: Optional[torch.Tensor] = None
+
+    def segments(self) -> Tuple[Tuple[int, ...], Tuple[int, ...]]:
+        off = (C.c_int64 * max(self.V, 1))()
+        length = (C.c_int64 * max(self.V, 1))()
+        _check(lib().shard_plan_segments(self.handle, off, length), "shard_plan_segments")
+        return tuple(off[: self.V]), tuple(length[: self.V])
+
+    def real_count(self, r: int) -> Tuple[int, ...]:
+        real = (C.c_int64 * max(self.V, 1))()
+        _check(lib().shard_plan_real_count(self.handle, int(r), real), "shard_plan_real_count")
+        return tuple(real[: self.V])
+
+    def free(self) -> None:
+        if self.handle is not None and self.handle.value:
+            lib().shard_plan_free(self.handle)
+        self.handle = None
+        self.workspace = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def shard_plan(numel, N, align_elems=8, var_flags=None, chunk_elems=0) -> Plan:
+    return Plan(numel, N, align_elems, var_flags, chunk_elems)
+
+
+def shard_plan_bind(plan: Plan, workspace: Optional[torch.Tensor] = None, stream=None, device="cuda") -> Plan:
+    """Binds caller memory; with workspace=None a uint8 tensor of the needed size is allocated here."""
+    if workspace is None:
+        workspace = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=device)
+    _check(lib().shard_plan_bind(plan.handle, _dev(workspace, 0, torch.uint8, "workspace"),
+                                 workspace.numel(), _stream(stream)), "shard_plan_bind")
+    plan.workspace = workspace
+    return plan
+
+
+def _full_ptrs(plan: Plan, tensors: Sequence[torch.Tensor], what: str):
+    if len(tensors) != plan.V:
+        raise ValueError("%s: expected %d tensors, got %d" % (what, plan.V, len(tensors)))
+    dtype = None
+    arr = (C.c_void_p * max(plan.V, 1))()
+    for i, t in enumerate(tensors):
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("%s[%d] must be a contiguous CUDA tensor" % (what, i))
+        if t.numel() != plan.numel[i]:
+            raise ValueError("%s[%d] has %d elements, the plan says %d" % (what, i, t.numel(), plan.numel[i]))
+        if t.dtype not in _DTYPES:
+            raise ValueError("%s[%d]: unsupported dtype %s" % (what, i, t.dtype))
+        if dtype is None:
+            dtype = t.dtype
+        elif t.dtype != dtype:
+            raise ValueError("%s: mixed dtypes" % what)
+        arr[i] = t.data_ptr() if t.numel() > 0 else None
+    return arr, (dtype or torch.float32)
+
+
+def shard_format(plan: Plan, r: int, full_tensors: Sequence[torch.Tensor], shard_out: torch.Tensor, stream=None):
+    arr, src = _full_ptrs(plan, full_tensors, "full_tensors")
+    if shard_out.dtype not in _DTYPES:
+        raise ValueError("unsupported shard dtype")
+    _check(lib().shard_format(plan.handle, int(r), arr, _DTYPES[src], _dev(shard_out, plan.S, None, "shard_out"),
+                              _DTYPES[shard_out.dtype], _stream(stream)), "shard_format")
+    return shard_out
+
+
+def unshard_format(plan: Plan, gathered: torch.Tensor, full_tensors: Sequence[torch.Tensor], stream=None):
+    arr, dst = _full_ptrs(plan, full_tensors, "full_tensors")
+    if gathered.dtype not in _DTYPES:
+        raise ValueError("unsupported gathered dtype")
+    _check(lib().unshard_format(plan.handle, _dev(gathered, plan.N * plan.S, None, "gathered"),
+                                _DTYPES[gathered.dtype], arr, _DTYPES[dst], _stream(stream)), "unshard_format")
+    return full_tensors
+
+
+def _hp(cls, hp: Dict[str, float]):
+    return cls(**{name: float(hp.get(name, 0.0)) for name, _ in cls._fields_})
+
+
+def shard_update_adam(plan: Plan, r: int, w, g, m, v, hp: Dict[str, float], step: int, w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_adam(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                   _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                   _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                   C.byref(_hp(AdamHP, hp)), int(step), _stream(stream)), "shard_update_adam")
+
+
+def shard_update_momentum(plan: Plan, r: int, w, g, m, hp: Dict[str, float], w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_momentum(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                       _dev(m, plan.S, f, "m"),
+                                       _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                       C.byref(_hp(MomentumHP, hp)), _stream(stream)), "shard_update_momentum")
+
+
+def shard_update_lamb_partials(plan: Plan, r: int, w, g, m, v, hp, step: int, local_sumsq_out, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lamb_partials(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                            _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                            C.byref(_hp(LambHP, hp)), int(step),
+                                            _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                            _stream(stream)), "shard_update_lamb_partials")
+
+
+def shard_update_lamb_apply(plan: Plan, r: int, w, m, v, hp, step: int, global_sumsq, w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lamb_apply(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(m, plan.S, f, "m"),
+                                         _dev(v, plan.S, f, "v"),
+                                         _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                         C.byref(_hp(LambHP, hp)), int(step),
+                                         _dev(global_sumsq, 2 * plan.V, f, "global_sumsq"),
+                                         _stream(stream)), "shard_update_lamb_apply")
+
+
+def shard_update_lamb(plan: Plan, r: int, w, g, m, v, hp, step: int, other_replicas_sumsq=None,
+                      local_sumsq_out=None, w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lamb(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                   _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                   _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                   C.byref(_hp(LambHP, hp)), int(step),
+                                   _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
+                                   _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                   _stream(stream)), "shard_update_lamb")
+
+
+def shard_profile_enable(plan: Plan, on: bool) -> None:
+    _check(lib().shard_profile_enable(plan.handle, 1 if on else 0), "shard_profile_enable")
+
+
+def shard_profile_read(plan: Plan, kernel: str) -> Tuple[int, float]:
+    """(launches, total milliseconds) of one kernel since the last reset; waits for recorded events."""
+    n, ms = C.c_int64(), C.c_double()
+    _check(lib().shard_profile_read(plan.handle, KERNEL_IDS[kernel], C.byref(n), C.byref(ms)), "shard_profile_read")
+    return n.value, ms.value
+
+
+def shard_profile_reset(plan: Plan) -> None:
+    _check(lib().shard_profile_reset(plan.handle), "shard_profile_reset")

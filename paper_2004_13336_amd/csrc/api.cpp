@@ -1,0 +1,345 @@
+// The C-ABI layer: argument checks, host-side constant folding, pointer-table caching.
+// Every kernel launch lives in kernels.hip; nothing here computes on tensor data.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "internal.hpp"
+
+using namespace su;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline hipStream_t as_stream(shard_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SHARD_OK : SHARD_EHIP; }
+inline bool dtype_ok(int d) { return d == SHARD_F32 || d == SHARD_BF16; }
+inline size_t dtype_size(int d) { return d == SHARD_F32 ? 4 : 2; }
+
+// Folds the hyper-parameters of an Adam-shaped step into float constants.  Powers and
+// reciprocals are taken in double and rounded once.
+int fold_adam(float lr, float beta1, float beta2, float eps, float wd, int64_t step, AdamK* k) {
+  if (step < 1) return SHARD_EINVAL;
+  if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f)) return SHARD_EINVAL;
+  if (!(eps > 0.0f) || !std::isfinite(lr) || !std::isfinite(wd)) return SHARD_EINVAL;
+  const double b1 = beta1, b2 = beta2;
+  k->b1 = beta1;
+  k->b2 = beta2;
+  k->omb1 = (float)(1.0 - b1);
+  k->omb2 = (float)(1.0 - b2);
+  k->rbc1 = (float)(1.0 / (1.0 - std::pow(b1, (double)step)));
+  k->rbc2 = (float)(1.0 / (1.0 - std::pow(b2, (double)step)));
+  k->eps = eps;
+  k->lr = lr;
+  k->wd = wd;
+  return SHARD_OK;
+}
+
+int check_shard_ptr(const void* p) {
+  if (p == nullptr) return SHARD_EINVAL;
+  return aligned16(p) ? SHARD_OK : SHARD_EALIGN;
+}
+
+int check_plan_r(const shard_plan_t* p, int r, bool need_ws) {
+  if (p == nullptr || r < 0 || r >= p->N) return SHARD_EINVAL;
+  if (need_ws && p->ws.base == nullptr) return SHARD_ESTATE;
+  return SHARD_OK;
+}
+
+// Returns the device address of a pointer table holding `ptrs`, uploading it into the least
+// recently used slot unless an identical table is already resident.
+int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t stream, const void*** table) {
+  const size_t bytes = (size_t)p->V * sizeof(void*);
+  int slot = -1;
+  for (int s = 0; s < kPtrSlots; ++s)
+    if (p->slot_valid[s] && (bytes == 0 || std::memcmp(p->slot_ptrs[s].data(), ptrs, bytes) == 0)) slot = s;
+  const void** base = reinterpret_cast<const void**>(p->ws.base + p->ws.ptrs);
+  if (slot < 0) {
+    for (int s = 0; s < kPtrSlots && slot < 0; ++s)
+      if (!p->slot_valid[s]) slot = s;                       // a free slot first
+    if (slot < 0) {
+      slot = 0;                                              // else the least recently used
+      for (int s = 1; s < kPtrSlots; ++s)
+        if (p->slot_age[s] < p->slot_age[slot]) slot = s;
+    }
+    const void** dev = base + (size_t)slot * p->V;
+    if (p->V > 0) {
+      if (launch_ptr_table(p, ptrs, dev, stream) != hipSuccess) {
+        p->slot_valid[slot] = false;
+        return SHARD_EHIP;
+      }
+      std::memcpy(p->slot_ptrs[slot].data(), ptrs, bytes);
+    }
+    p->slot_valid[slot] = true;
+  }
+  p->slot_age[slot] = ++p->clock;
+  *table = base + (size_t)slot * p->V;
+  return SHARD_OK;
+}
+
+// 128-bit path: pieces start on 16-byte boundaries for both element sizes and every tensor does too.
+bool full_tensors_vectorisable(const shard_plan_t* p, const void* const* ptrs) {
+  if (p->align % 8 != 0) return false;
+  for (int i = 0; i < p->V; ++i)
+    if (p->n[i] > 0 && !aligned16(ptrs[i])) return false;
+  return true;
+}
+
+int check_full_ptrs(const shard_plan_t* p, const void* const* ptrs) {
+  if (p->V > 0 && ptrs == nullptr) return SHARD_EINVAL;
+  for (int i = 0; i < p->V; ++i)
+    if (p->n[i] > 0 && ptrs[i] == nullptr) return SHARD_EINVAL;
+  return SHARD_OK;
+}
+
+const char* const kKernelNames[SHARD_K_COUNT] = {
+    "format_kernel", "unshard_kernel", "adam_kernel", "momentum_kernel",
+    "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* shard_strerror(int status) {
+  switch (status) {
+    case SHARD_OK: return "ok";
+    case SHARD_EINVAL: return "invalid argument";
+    case SHARD_ENOMEM: return "out of memory or workspace too small";
+    case SHARD_EALIGN: return "packed-shard pointer not 16-byte aligned";
+    case SHARD_EHIP: return "HIP runtime error";
+    case SHARD_ESTATE: return "plan has no bound workspace";
+    default: return "unknown status";
+  }
+}
+
+const char* shard_kernel_name(int kernel_id) {
+  return (kernel_id >= 0 && kernel_id < SHARD_K_COUNT) ? kKernelNames[kernel_id] : nullptr;
+}
+
+int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32_t* var_flags, int chunk_elems,
+               shard_plan_t** out) {
+  if (out == nullptr) return SHARD_EINVAL;
+  *out = nullptr;
+  shard_plan_t* p = new (std::nothrow) shard_plan_s();
+  if (p == nullptr) return SHARD_ENOMEM;
+  const int rc = plan_build(p, V, numel, N, align_elems, var_flags, chunk_elems);
+  if (rc != SHARD_OK) {
+    delete p;
+    return rc;
+  }
+  *out = p;
+  return SHARD_OK;
+}
+
+int shard_plan_info(const shard_plan_t* p, int64_t* S, int64_t* total, int64_t* n_chunks, size_t* workspace_bytes) {
+  if (p == nullptr) return SHARD_EINVAL;
+  if (S) *S = p->S;
+  if (total) *total = p->total;
+  if (n_chunks) *n_chunks = (int64_t)p->chunks.size();
+  if (workspace_bytes) *workspace_bytes = p->ws_need;
+  return SHARD_OK;
+}
+
+int shard_plan_segments(const shard_plan_t* p, int64_t* seg_off, int64_t* seg_len) {
+  if (p == nullptr) return SHARD_EINVAL;
+  for (int i = 0; i < p->V; ++i) {
+    if (seg_off) seg_off[i] = p->off[i];
+    if (seg_len) seg_len[i] = p->L[i];
+  }
+  return SHARD_OK;
+}
+
+int shard_plan_real_count(const shard_plan_t* p, int r, int64_t* real) {
+  if (p == nullptr || real == nullptr || r < 0 || r >= p->N) return SHARD_EINVAL;
+  for (int i = 0; i < p->V; ++i) {
+    const int64_t rem = p->n[i] - (int64_t)r * p->L[i];
+    real[i] = rem <= 0 ? 0 : (rem < p->L[i] ? rem : p->L[i]);
+  }
+  return SHARD_OK;
+}
+
+int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard_stream_t stream) {
+  if (p == nullptr || device_workspace == nullptr) return SHARD_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(device_workspace) & 255u) != 0) return SHARD_EALIGN;
+  if (bytes < p->ws_need) return SHARD_ENOMEM;
+  Workspace ws;
+  workspace_layout(p, &ws);
+  ws.base = static_cast<char*>(device_workspace);
+  ws.bytes = bytes;
+  hipStream_t s = as_stream(stream);
+  if (!p->vars.empty() &&
+      hipMemcpyAsync(ws.base + ws.vars, p->vars.data(), p->vars.size() * sizeof(VarDesc), hipMemcpyHostToDevice, s) !=
+          hipSuccess)
+    return SHARD_EHIP;
+  if (!p->chunks.empty() && hipMemcpyAsync(ws.base + ws.chunks, p->chunks.data(), p->chunks.size() * sizeof(ChunkDesc),
+                                           hipMemcpyHostToDevice, s) != hipSuccess)
+    return SHARD_EHIP;
+  p->ws = ws;
+  for (int i = 0; i < kPtrSlots; ++i) p->slot_valid[i] = false;
+  return SHARD_OK;
+}
+
+void shard_plan_free(shard_plan_t* p) {
+  if (p == nullptr) return;
+  for (auto& rec : p->prof_live) {
+    (void)hipEventDestroy(rec.start);
+    (void)hipEventDestroy(rec.stop);
+  }
+  for (auto& rec : p->prof_free) {
+    (void)hipEventDestroy(rec.start);
+    (void)hipEventDestroy(rec.stop);
+  }
+  delete p;
+}
+
+int shard_format(shard_plan_t* p, int r, const void* const* full_ptrs, int src_dtype, void* shard_out, int dst_dtype,
+                 shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (!dtype_ok(src_dtype) || !dtype_ok(dst_dtype)) return SHARD_EINVAL;
+  if ((rc = check_full_ptrs(p, full_ptrs)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(shard_out)) != SHARD_OK) return rc;
+  const void** table = nullptr;
+  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
+  return hip_status(launch_format(p, r, table, src_dtype, shard_out, dst_dtype,
+                                  full_tensors_vectorisable(p, full_ptrs), as_stream(stream)));
+}
+
+int unshard_format(shard_plan_t* p, const void* gathered, int src_dtype, void* const* full_ptrs, int dst_dtype,
+                   shard_stream_t stream) {
+  int rc = check_plan_r(p, 0, true);
+  if (rc != SHARD_OK) return rc;
+  if (!dtype_ok(src_dtype) || !dtype_ok(dst_dtype)) return SHARD_EINVAL;
+  if ((rc = check_full_ptrs(p, full_ptrs)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(gathered)) != SHARD_OK) return rc;
+  const void** table = nullptr;
+  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
+  return hip_status(launch_unshard(p, gathered, src_dtype, reinterpret_cast<void* const*>(const_cast<void**>(table)),
+                                   dst_dtype, full_tensors_vectorisable(p, full_ptrs), as_stream(stream)));
+}
+
+int shard_update_adam(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,
+                      const shard_adam_hp* hp, int64_t step, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, false);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+      (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  return hip_status(launch_adam(p, w, g, m, v, w_bf16_out, k, as_stream(stream)));
+}
+
+int shard_update_momentum(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w_bf16_out,
+                          const shard_momentum_hp* hp, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, false);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr || !std::isfinite(hp->lr) || !std::isfinite(hp->mu) || !std::isfinite(hp->weight_decay))
+    return SHARD_EINVAL;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+      (rc = check_shard_ptr(m)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  MomentumK k{hp->mu, hp->lr, hp->weight_decay};
+  return hip_status(launch_momentum(p, w, g, m, w_bf16_out, k, as_stream(stream)));
+}
+
+int shard_update_lamb_partials(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v,
+                               const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
+    return rc;
+  hipError_t e = launch_lamb_p1(p, r, w, g, m, v, k, as_stream(stream));
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, as_stream(stream));
+  return hip_status(e);
+}
+
+int shard_update_lamb_apply(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w_bf16_out,
+                            const shard_lamb_hp* hp, int64_t step, const float* global_sumsq, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
+      (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  return hip_status(launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, global_sumsq, as_stream(stream)));
+}
+
+int shard_update_lamb(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,
+                      const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq,
+                      float* local_sumsq_out, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lamb_p1(p, r, w, g, m, v, k, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
+int shard_profile_enable(shard_plan_t* p, int on) {
+  if (p == nullptr) return SHARD_EINVAL;
+  p->prof = on != 0;
+  return SHARD_OK;
+}
+
+int shard_profile_read(shard_plan_t* p, int kernel_id, int64_t* launches, double* total_ms) {
+  if (p == nullptr || kernel_id < 0 || kernel_id >= SHARD_K_COUNT) return SHARD_EINVAL;
+  int rc = SHARD_OK;
+  for (auto& rec : p->prof_live) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(rec.stop) != hipSuccess || hipEventElapsedTime(&ms, rec.start, rec.stop) != hipSuccess) {
+      rc = SHARD_EHIP;
+    } else {
+      p->prof_count[rec.kernel] += 1;
+      p->prof_ms[rec.kernel] += (double)ms;
+    }
+    p->prof_free.push_back(rec);
+  }
+  p->prof_live.clear();
+  if (launches) *launches = p->prof_count[kernel_id];
+  if (total_ms) *total_ms = p->prof_ms[kernel_id];
+  return rc;
+}
+
+int shard_profile_reset(shard_plan_t* p) {
+  if (p == nullptr) return SHARD_EINVAL;
+  int64_t n;
+  (void)shard_profile_read(p, 0, &n, nullptr);   // drain pending records
+  for (int i = 0; i < SHARD_K_COUNT; ++i) {
+    p->prof_count[i] = 0;
+    p->prof_ms[i] = 0.0;
+  }
+  return SHARD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Internal declarations shared by the host-side plan, the C-ABI layer and the HIP launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "shardupdate.h"
+
+namespace su {
+
+// ---- device-visible tables (uploaded by shard_plan_bind) ------------------------------------
+
+// One variable of the plan.  Section 4.1: the piece of replica r starts at r*L in the flat
+// variable; slots whose flat index reaches n are padding.
+struct VarDesc {
+  int64_t n;            // elements of the full variable
+  int64_t L;            // piece length per replica
+  int64_t off;          // offset of the piece in a packed shard
+  int32_t first_chunk;  // this variable's chunks are [first_chunk, first_chunk + n_chunks)
+  int32_t n_chunks;
+  uint32_t flags;       // SHARD_VAR_*
+  uint32_t reserved;
+};
+static_assert(sizeof(VarDesc) == 40, "VarDesc layout");
+
+// One work item of the table-driven kernels: `len` consecutive slots of one variable's piece,
+// starting k0 slots into the piece.  Never crosses a variable boundary.
+struct ChunkDesc {
+  int64_t k0;
+  int32_t var;
+  int32_t len;
+};
+static_assert(sizeof(ChunkDesc) == 16, "ChunkDesc layout");
+
+constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int kPtrSlots = 4;         // cached device pointer tables per plan
+constexpr int kPtrBatch = 256;       // pointers carried by one table-writing launch
+
+struct PtrBatch {
+  const void* p[kPtrBatch];
+};
+
+// ---- optimizer constants, precomputed on the host in double and rounded once -----------------
+
+struct AdamK {
+  float b1, omb1, b2, omb2, rbc1, rbc2, eps, lr, wd;
+};
+struct MomentumK {
+  float mu, lr, wd;
+};
+
+// ---- the plan --------------------------------------------------------------------------------
+
+struct Workspace {
+  char* base = nullptr;
+  size_t bytes = 0;
+  // byte offsets inside base
+  size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
+};
+
+struct ProfRecord {
+  hipEvent_t start, stop;
+  int kernel;
+};
+
+}  // namespace su
+
+struct shard_plan_s {
+  int V = 0, N = 1, align = 1, chunk = 0;
+  int64_t S = 0, total = 0;
+  std::vector<int64_t> n, L, off;
+  std::vector<uint32_t> flags;
+  std::vector<su::VarDesc> vars;
+  std::vector<su::ChunkDesc> chunks;
+
+  su::Workspace ws;
+  size_t ws_need = 0;
+
+  // cache of uploaded pointer tables: slot -> the V pointers it holds, and an age for LRU
+  std::vector<const void*> slot_ptrs[su::kPtrSlots];
+  uint64_t slot_age[su::kPtrSlots] = {0, 0, 0, 0};
+  bool slot_valid[su::kPtrSlots] = {false, false, false, false};
+  uint64_t clock = 0;
+
+  bool prof = false;
+  std::vector<su::ProfRecord> prof_live;   // recorded, not yet read
+  std::vector<su::ProfRecord> prof_free;   // event pairs ready for reuse
+  int64_t prof_count[SHARD_K_COUNT] = {};
+  double prof_ms[SHARD_K_COUNT] = {};
+};
+
+namespace su {
+
+// plan.cpp (host only)
+int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, const uint32_t* flags, int chunk);
+size_t workspace_layout(const shard_plan_t* p, Workspace* ws);
+
+// kernels.hip: every launcher enqueues on `stream`, returns a hipError_t and never synchronises.
+hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const void** dev_table, hipStream_t stream);
+
+hipError_t launch_format(shard_plan_t* p, int r, const void* const* dev_ptr_table, int src_dtype, void* out,
+                         int dst_dtype, bool vec, hipStream_t stream);
+hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int src_dtype, void* const* dev_ptr_table,
+                          int dst_dtype, bool vec, hipStream_t stream);
+
+hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, float* v, void* w16, const AdamK& k,
+                       hipStream_t stream);
+hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, void* w16, const MomentumK& k,
+                           hipStream_t stream);
+
+hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v, const AdamK& k,
+                          hipStream_t stream);
+// Sums each variable's chunk partials in a fixed order, adds `other` (nullable), writes the totals to
+// `sums_out` (nullable) and `local_out` (nullable, without `other`).
+hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_out, float* local_out,
+                              hipStream_t stream);
+hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w16, const AdamK& k,
+                          const float* sums, hipStream_t stream);
+
+// RAII helper: records an event pair around a launch when profiling is on.
+struct ProfScope {
+  shard_plan_t* p;
+  hipStream_t stream;
+  ProfRecord rec;
+  bool on;
+  ProfScope(shard_plan_t* plan, int kernel, hipStream_t s);
+  ~ProfScope();
+};
+
+}  // namespace su

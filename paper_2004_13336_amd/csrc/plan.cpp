@@ -1,0 +1,97 @@
+// Host-side sharding plan: integer layout arithmetic and the chunk table.
+//
+// Section 4.1 ("Data formatting"): a variable is reshaped (here: fully flattened, which moves no
+// data in linear memory), padded until the shard count divides it, and sliced at an offset
+// computed from the replica id.  Section 5.2 ("Batched communication operators"): a replica's
+// combined shard holds one piece of every variable.
+#include <limits>
+#include <new>
+
+#include "internal.hpp"
+
+namespace su {
+
+namespace {
+constexpr int kDefaultChunk = 4096;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+}  // namespace
+
+int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, const uint32_t* flags, int chunk) {
+  if (V < 0 || N < 1 || align < 1 || (align & (align - 1)) != 0) return SHARD_EINVAL;
+  if (V > 0 && numel == nullptr) return SHARD_EINVAL;
+  if (chunk == 0) chunk = kDefaultChunk;
+  if (chunk < 1024 || chunk > 16384 || chunk % 1024 != 0) return SHARD_EINVAL;
+
+  p->V = V;
+  p->N = N;
+  p->align = align;
+  p->chunk = chunk;
+  try {
+    p->n.assign(numel, numel + V);
+    p->L.resize(V);
+    p->off.resize(V);
+    p->flags.assign(V, 0u);
+    p->vars.resize(V);
+    const int64_t kMax = std::numeric_limits<int64_t>::max() / 16;   // head-room for byte offsets
+    int64_t pos = 0, total = 0;
+    for (int i = 0; i < V; ++i) {
+      const int64_t n = numel[i];
+      if (n < 0 || n > kMax) return SHARD_EINVAL;
+      const int64_t per = (n + N - 1) / N;                 // ceil(n / N)
+      const int64_t len = (per + align - 1) / align * align;
+      if (len > kMax / N || pos > kMax - len) return SHARD_EINVAL;
+      p->L[i] = len;
+      p->off[i] = pos;
+      pos += len;
+      total += n;
+      if (flags) {
+        if (flags[i] & ~(uint32_t)(SHARD_VAR_NO_DECAY | SHARD_VAR_NO_ADAPT)) return SHARD_EINVAL;
+        p->flags[i] = flags[i];
+      }
+    }
+    if (pos > kMax / N) return SHARD_EINVAL;               // N*S must be addressable
+    p->S = pos;
+    p->total = total;
+
+    p->chunks.clear();
+    for (int i = 0; i < V; ++i) {
+      VarDesc& vd = p->vars[i];
+      vd.n = p->n[i];
+      vd.L = p->L[i];
+      vd.off = p->off[i];
+      vd.flags = p->flags[i];
+      vd.reserved = 0;
+      const int64_t count = (p->L[i] + chunk - 1) / chunk;
+      if ((int64_t)p->chunks.size() + count > (int64_t)std::numeric_limits<int32_t>::max() / N) return SHARD_EINVAL;
+      vd.first_chunk = (int32_t)p->chunks.size();
+      vd.n_chunks = (int32_t)count;
+      for (int64_t k0 = 0; k0 < p->L[i]; k0 += chunk) {
+        ChunkDesc cd;
+        cd.k0 = k0;
+        cd.var = i;
+        cd.len = (int32_t)((p->L[i] - k0 < chunk) ? (p->L[i] - k0) : chunk);
+        p->chunks.push_back(cd);
+      }
+    }
+    for (int s = 0; s < kPtrSlots; ++s) p->slot_ptrs[s].assign(V, nullptr);
+  } catch (const std::bad_alloc&) {
+    return SHARD_ENOMEM;
+  }
+  Workspace ws;
+  p->ws_need = workspace_layout(p, &ws);
+  return SHARD_OK;
+}
+
+size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
+  size_t pos = 0;
+  const size_t V = (size_t)p->V, C = p->chunks.size();
+  ws->vars = pos;        pos = align_up(pos + V * sizeof(VarDesc), 256);
+  ws->chunks = pos;      pos = align_up(pos + C * sizeof(ChunkDesc), 256);
+  ws->ptrs = pos;        pos = align_up(pos + (size_t)kPtrSlots * V * sizeof(void*), 256);
+  ws->chunk_sums = pos;  pos = align_up(pos + C * 2 * sizeof(float), 256);
+  ws->var_sums = pos;    pos = align_up(pos + V * 2 * sizeof(float), 256);
+  return pos < 256 ? 256 : pos;
+}
+
+}  // namespace su

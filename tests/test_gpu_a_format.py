@@ -1,0 +1,226 @@
+"""GPU parity of shard_format / unshard_format against the oracle: bit-exact."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2004_13336_amd as su
+from helpers import DEV, same_bits, to_dev, to_host
+from workloads import CONFIGS, random_bits_u32
+
+pytestmark = pytest.mark.gpu
+
+CANARY = 0x5A
+
+
+def _bit_tensors(seed, numel, dtype):
+    """Host arrays of arbitrary bit patterns: float32 (as float32 arrays) or bf16 (uint16)."""
+    out = []
+    for i, n in enumerate(numel):
+        bits = random_bits_u32(seed, i, n)
+        out.append(bits.view(np.float32) if dtype == "f32" else (bits & 0xFFFF).astype(np.uint16))
+    return out
+
+
+def _guarded(nbytes):
+    """A device byte buffer with canary bands before and after the payload."""
+    band = 256
+    buf = torch.full((nbytes + 2 * band,), CANARY, dtype=torch.uint8, device=DEV)
+    return buf, buf[band:band + nbytes], band
+
+
+def _bands_intact(buf, band, nbytes):
+    return bool((buf[:band] == CANARY).all()) and bool((buf[band + nbytes:] == CANARY).all())
+
+
+CASES = [
+    # (numel, N, align)
+    ([1000, 37, 0, 8, 4099, 1], 3, 8),
+    ([5, 6, 7, 64, 1001, 3, 0, 20000], 6, 8),
+    ([2, 1024, 30522, 513], 8, 8),
+    ([64, 64, 9000], 32, 8),                # replicas whose pieces are all padding
+    ([100, 33, 7], 4, 1),                   # element-wise path: pieces not 16-byte aligned
+    ([100, 33, 4097], 5, 4),
+    ([12345, 8], 1, 8),
+    ([70000], 2, 64),
+    ([], 4, 8),
+    ([0, 0], 4, 8),
+]
+
+
+@pytest.mark.parametrize("numel,N,align", CASES)
+@pytest.mark.parametrize("src,dst", [("f32", "f32"), ("bf16", "bf16"), ("f32", "bf16"), ("bf16", "f32")])
+def test_format_and_unshard_match_oracle(numel, N, align, src, dst):
+    print("case", numel, N, align, src, dst, flush=True)
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+    flats = _bit_tensors(11, numel, src)
+    if src == "f32" and dst == "bf16":
+        # NaN payloads are quieted by the conversion on both sides identically; keep them in.
+        pass
+    dev_full = [to_dev(f) for f in flats]
+    tdt = torch.float32 if dst == "f32" else torch.bfloat16
+    esz = 4 if dst == "f32" else 2
+    gathered_ref = np.stack([oracle.shard_format(oplan, r, flats, dst=dst) for r in range(N)]) if oplan.S else None
+    # one guarded, separately allocated (16-byte aligned) output per replica
+    rows = []
+    for r in range(N):
+        buf, payload, band = _guarded(oplan.S * esz)
+        out = payload.view(tdt) if oplan.S else torch.empty(0, dtype=tdt, device=DEV)
+        su.shard_format(plan, r, dev_full, out)
+        torch.cuda.synchronize()
+        assert _bands_intact(buf, band, oplan.S * esz)
+        if oplan.S:
+            assert same_bits(to_host(out), gathered_ref[r]), r
+        rows.append(out)
+    gathered = torch.stack(rows).contiguous()
+    # reverse: restore the full tensors (in dst dtype) and compare with the oracle's unformat
+    if oplan.S:
+        want_full = oracle.unshard_format(oplan, gathered_ref)
+        outs, bufs = [], []
+        for n in numel:
+            b, p, bd = _guarded(n * esz)
+            bufs.append((b, bd, n * esz))
+            outs.append(p.view(tdt))
+        su.unshard_format(plan, gathered, outs)
+        torch.cuda.synchronize()
+        for (b, bd, nb), o, w in zip(bufs, outs, want_full):
+            assert _bands_intact(b, bd, nb)
+            assert same_bits(to_host(o), w)
+    plan.free()
+
+
+def test_unshard_converting_f32_shards_to_bf16_tensors():
+    numel, N = [1000, 37, 4099], 3
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = [np.random.default_rng(i).standard_normal(n).astype(np.float32) for i, n in enumerate(numel)]
+    g32 = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
+    outs = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in numel]
+    su.unshard_format(plan, to_dev(g32), outs)
+    for o, w in zip(outs, oracle.unshard_format(oplan, g32, dst="bf16")):
+        assert same_bits(to_host(o), w)
+
+
+def test_misaligned_full_tensors_take_the_elementwise_path():
+    numel, N = [1000, 4099, 64], 4
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = _bit_tensors(5, numel, "f32")
+    # every tensor starts 4 bytes past a 16-byte boundary
+    backing = [torch.empty(n + 1, dtype=torch.float32, device=DEV) for n in numel]
+    views = [b[1:] for b in backing]
+    for v, f in zip(views, flats):
+        v.copy_(torch.from_numpy(f))
+        assert v.data_ptr() % 16 != 0
+    out = torch.empty(oplan.S, dtype=torch.float32, device=DEV)
+    for r in range(N):
+        su.shard_format(plan, r, views, out)
+        assert same_bits(to_host(out), oracle.shard_format(oplan, r, flats))
+    gathered = to_dev(np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)]))
+    for v in views:
+        v.zero_()
+    su.unshard_format(plan, gathered, views)
+    for v, f in zip(views, flats):
+        assert same_bits(to_host(v), f)
+
+
+def test_pointer_table_cache_survives_alternating_tensor_sets():
+    numel, N = [300, 5000], 2
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    sets = [[to_dev(f) for f in _bit_tensors(s, numel, "f32")] for s in range(6)]   # more sets than cache slots
+    host = [_bit_tensors(s, numel, "f32") for s in range(6)]
+    out = torch.empty(oplan.S, dtype=torch.float32, device=DEV)
+    order = [0, 1, 0, 2, 3, 4, 5, 0, 5, 1, 1, 3]
+    for s in order:
+        su.shard_format(plan, 1, sets[s], out)
+        assert same_bits(to_host(out), oracle.shard_format(oplan, 1, host[s]))
+
+
+def test_runtime_argument_errors():
+    plan = su.shard_plan(([100, 8]), 2)
+    t = [torch.zeros(100, device=DEV), torch.zeros(8, device=DEV)]
+    out = torch.zeros(plan.S, device=DEV)
+    with pytest.raises(su.ShardError) as e:
+        su.shard_format(plan, 0, t, out)           # not bound
+    assert e.value.status == -5
+    su.shard_plan_bind(plan)
+    with pytest.raises(su.ShardError) as e:
+        su.shard_format(plan, 2, t, out)           # replica id out of range
+    assert e.value.status == -1
+    with pytest.raises(ValueError):
+        su.shard_format(plan, 0, t, out[:-1])      # output too small: refused before any launch
+    with pytest.raises(ValueError):
+        su.shard_format(plan, 0, [t[0], t[1][:-1]], out)
+    with pytest.raises(su.ShardError) as e:
+        su.shard_format(plan, 0, t, torch.zeros(plan.S + 1, device=DEV)[1:])   # misaligned shard buffer
+    assert e.value.status == -3
+    small = torch.empty(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(su.ShardError) as e:
+        su.shard_plan_bind(plan, small)
+    assert e.value.status == -2
+
+
+@pytest.mark.parametrize("name,N,replicas", [("bert_large", 8, (0, 7)), ("bert_large", 64, (0, 63, 31)),
+                                             ("resnet50", 32, (0, 31)), ("resnet50", 1, (0,))])
+def test_full_size_format_round_trip(name, N, replicas):
+    """At the benchmark's sizes: sampled replicas bit-exact against the oracle, then the whole
+    gathered buffer unsharded and compared with the inputs."""
+    cfg = [c for c in CONFIGS if c.name == name][0]
+    print("full-size format", name, N, flush=True)
+    numel = cfg.numel
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = _bit_tensors(cfg.seed, numel, "f32")
+    dev_full = [to_dev(f) for f in flats]
+    gathered = torch.empty((N, oplan.S), dtype=torch.float32, device=DEV)
+    for r in range(N):
+        su.shard_format(plan, r, dev_full, gathered[r])
+    for r in replicas:
+        assert same_bits(to_host(gathered[r]), oracle.shard_format(oplan, r, flats)), r
+    outs = [torch.empty(n, dtype=torch.float32, device=DEV) for n in numel]
+    su.unshard_format(plan, gathered, outs)
+    for i, (o, f) in enumerate(zip(outs, flats)):
+        assert same_bits(to_host(o), f), i
+    plan.free()
+
+
+def test_formatting_stress_1p5b_128_replicas_bf16():
+    """771 variables, 128 replicas: [1600]-element variables leave 13 real + 3 padded slots per
+    replica and hundreds of all-padding pieces on the last replicas."""
+    cfg = [c for c in CONFIGS if c.name == "lm_1p5b"][0]
+    N = 128
+    numel = cfg.numel
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(cfg.seed)
+    flat_all = torch.randint(-32768, 32767, (cfg.total,), dtype=torch.int16, device=DEV, generator=gen)
+    pos, dev_full = 0, []
+    for n in numel:
+        dev_full.append(flat_all[pos:pos + n].view(torch.bfloat16))    # offsets are multiples of 8 elements
+        pos += n
+    host_all = flat_all.cpu().numpy().view(np.uint16)
+    pos, flats = 0, []
+    for n in numel:
+        flats.append(host_all[pos:pos + n])
+        pos += n
+    out = torch.empty(oplan.S, dtype=torch.bfloat16, device=DEV)
+    for r in (0, 1, 77, 126, 127):
+        su.shard_format(plan, r, dev_full, out)
+        assert same_bits(to_host(out), oracle.shard_format(oplan, r, flats)), r
+    # whole round trip on the device, checked against the inputs
+    gathered = torch.empty((N, oplan.S), dtype=torch.bfloat16, device=DEV)
+    for r in range(N):
+        su.shard_format(plan, r, dev_full, gathered[r])
+    back = torch.zeros(cfg.total, dtype=torch.int16, device=DEV)
+    pos, outs = 0, []
+    for n in numel:
+        outs.append(back[pos:pos + n].view(torch.bfloat16))
+        pos += n
+    su.unshard_format(plan, gathered, outs)
+    assert torch.equal(back, flat_all)
+    plan.free()

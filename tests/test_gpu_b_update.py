@@ -1,0 +1,391 @@
+"""GPU parity of the fused optimizer updates against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2004_13336_amd as su
+from helpers import (DEV, assert_first_moment_close, assert_second_moment_close, assert_weights_close, f32_hp,
+                     gen_weights_grads, pads_are_zero, same_bits, shards_of, to_dev, to_host)
+from workloads import CONFIGS, normal_f32
+
+pytestmark = pytest.mark.gpu
+
+ADAM = f32_hp({"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8, "weight_decay": 0.0})
+MOM = f32_hp({"lr": 0.1, "mu": 0.9, "weight_decay": 5e-5})
+LAMB = f32_hp({"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-6, "weight_decay": 0.01})
+
+RAGGED = [0, 1, 5, 6, 7, 64, 1001, 3, 4096, 4097, 20011]
+
+
+def dev_rows(a2d):
+    """One separately allocated (hence 16-byte aligned) device tensor per replica."""
+    return [to_dev(a2d[r]) for r in range(a2d.shape[0])]
+
+
+def host_rows(rows):
+    return np.stack([to_host(t) for t in rows])
+
+
+def zeros_like_rows(rows, dtype=None):
+    return [torch.zeros_like(t, dtype=dtype) for t in rows]
+
+
+def _cfg(name):
+    return [c for c in CONFIGS if c.name == name][0]
+
+
+# --------------------------------------------------------------------------------------- Adam
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ragged_align1", "ragged_align2"])
+def test_adam_all_replicas_steps_1_and_10(case):
+    """Config 1: 6 variables, 4 replicas, every replica checked after step 1 and step 10."""
+    if case == "tiny":
+        cfg = _cfg("tiny"); numel, N, seed, align, gstd = cfg.numel, 4, cfg.seed, 8, cfg.grad_std
+    else:
+        numel, N, seed, gstd = RAGGED, 6, 99, 1e-2
+        align = {"ragged": 8, "ragged_align1": 1, "ragged_align2": 2}[case]
+    print("adam", case, flush=True)
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan(numel, N, align)
+    ws, _ = gen_weights_grads(seed, numel, 0.02, gstd)
+    W_ref = shards_of(oplan, ws); M_ref = np.zeros_like(W_ref); V_ref = np.zeros_like(W_ref)
+    W = dev_rows(W_ref); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    for t in range(1, 11):
+        gs = [normal_f32(seed, i, "g", n, gstd, t) for i, n in enumerate(numel)]
+        G_ref = shards_of(oplan, gs)
+        G = dev_rows(G_ref)
+        for r in range(N):
+            su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], ADAM, t)
+            W_ref[r], M_ref[r], V_ref[r] = oracle.adam_step(W_ref[r], G_ref[r], M_ref[r], V_ref[r], ADAM, t)
+        if t in (1, 10):
+            Wh, Mh, Vh = host_rows(W), host_rows(M), host_rows(V)
+            for r in range(N):
+                assert_weights_close(Wh[r], W_ref[r], "w r=%d t=%d" % (r, t))
+                assert_first_moment_close(Mh[r], M_ref[r], gstd, t)
+                assert_second_moment_close(Vh[r], V_ref[r], t)
+                assert pads_are_zero(oplan, r, Wh[r]) and pads_are_zero(oplan, r, Mh[r]) and pads_are_zero(oplan, r, Vh[r])
+    # the shards put back together are the unsharded update (Section 3.1): compare with the oracle run unsharded
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]; uv = [np.zeros_like(w) for w in ws]
+    for t in range(1, 11):
+        gs = [normal_f32(seed, i, "g", n, gstd, t) for i, n in enumerate(numel)]
+        for i in range(len(numel)):
+            uw[i], um[i], uv[i] = oracle.adam_step(uw[i], gs[i], um[i], uv[i], ADAM, t)
+    for a, b in zip(uw, oracle.unshard_format(oplan, host_rows(W))):
+        assert_weights_close(b, a, "unsharded")
+    plan.free()
+
+
+def test_adam_sharded_equals_unsharded_on_the_gpu_bit_for_bit():
+    """The same per-element arithmetic runs whatever the partition: N=4 shards == N=1."""
+    cfg = _cfg("tiny")
+    numel, seed = cfg.numel, cfg.seed
+    ws, gs = gen_weights_grads(seed, numel, 0.02, 1e-2)
+    results = {}
+    for N in (1, 4):
+        oplan = oracle.make_plan(numel, N, 8)
+        plan = su.shard_plan(numel, N, 8)
+        W = to_dev(shards_of(oplan, ws)); G = to_dev(shards_of(oplan, gs))
+        M = torch.zeros_like(W); V = torch.zeros_like(W)
+        for t in (1, 2, 3):
+            for r in range(N):
+                su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], ADAM, t)
+        results[N] = [oracle.unshard_format(oplan, to_host(X)) for X in (W, M, V)]
+        plan.free()
+    for a, b in zip(results[1], results[4]):
+        for x, y in zip(a, b):
+            assert same_bits(x, y)
+
+
+def test_adam_with_weight_decay_and_bf16_side_output():
+    numel, N = RAGGED, 3
+    hp = dict(ADAM, weight_decay=float(np.float32(0.01)))
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan(numel, N, 8)
+    ws, gs = gen_weights_grads(5, numel, 0.02, 1e-3)
+    W_ref = shards_of(oplan, ws); G_ref = shards_of(oplan, gs)
+    W = to_dev(W_ref); G = to_dev(G_ref); M = torch.zeros_like(W); V = torch.zeros_like(W)
+    W16 = torch.full(W.shape, 7.0, dtype=torch.bfloat16, device=DEV)
+    for r in range(N):
+        su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], hp, 1, w_bf16_out=W16[r])
+        wr, mr, vr = oracle.adam_step(W_ref[r], G_ref[r], np.zeros_like(W_ref[r]), np.zeros_like(W_ref[r]), hp, 1)
+        assert_weights_close(to_host(W[r]), wr)
+        assert_first_moment_close(to_host(M[r]), mr, 1e-3)
+        # the bf16 copy is the rounding of the GPU's own float32 result, bit for bit
+        assert same_bits(to_host(W16[r]), oracle.f32_to_bf16_bits(to_host(W[r])))
+    plan.free()
+
+
+# ----------------------------------------------------------------------------------- momentum
+
+@pytest.mark.parametrize("N", [1, 32])
+def test_momentum_resnet_shaped(N):
+    """Config 2: 161 variables, 25.6M parameters, 1 replica and the small-shard regime at 32."""
+    cfg = _cfg("resnet50")
+    print("momentum resnet N=%d" % N, flush=True)
+    numel, seed = cfg.numel, cfg.seed
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan(numel, N, 8)
+    ws, _ = gen_weights_grads(seed, numel, cfg.weight_std, cfg.grad_std)
+    check = sorted({0, N - 1, N // 2})
+    W_ref = shards_of(oplan, ws); M_ref = np.zeros_like(W_ref)
+    W = to_dev(W_ref); M = torch.zeros_like(W)
+    for t in range(1, 4):
+        gs = [normal_f32(seed, i, "g", n, cfg.grad_std, t) for i, n in enumerate(numel)]
+        G_ref = shards_of(oplan, gs); G = to_dev(G_ref)
+        for r in range(N):
+            su.shard_update_momentum(plan, r, W[r], G[r], M[r], MOM)
+        for r in check:
+            W_ref[r], M_ref[r] = oracle.momentum_step(W_ref[r], G_ref[r], M_ref[r], MOM)
+    Wh, Mh = to_host(W), to_host(M)
+    for r in check:
+        assert_weights_close(Wh[r], W_ref[r], "w r=%d" % r)
+        assert_first_moment_close(Mh[r], M_ref[r], cfg.grad_std, 3 * 10)   # mu=0.9 sums ~10 gradients
+        assert pads_are_zero(oplan, r, Wh[r]) and pads_are_zero(oplan, r, Mh[r])
+    plan.free()
+
+
+def test_momentum_scalar_path_and_bf16():
+    numel, N = RAGGED, 5
+    for align in (1, 8):
+        oplan = oracle.make_plan(numel, N, align)
+        plan = su.shard_plan(numel, N, align)
+        ws, gs = gen_weights_grads(6, numel, 0.02, 1e-3)
+        W_ref = shards_of(oplan, ws); G_ref = shards_of(oplan, gs)
+        W = dev_rows(W_ref); G = dev_rows(G_ref); M = zeros_like_rows(W)
+        W16 = zeros_like_rows(W, torch.bfloat16)
+        for r in range(N):
+            su.shard_update_momentum(plan, r, W[r], G[r], M[r], MOM, w_bf16_out=W16[r])
+            wr, mr = oracle.momentum_step(W_ref[r], G_ref[r], np.zeros_like(W_ref[r]), MOM)
+            assert_weights_close(to_host(W[r]), wr)
+            assert_first_moment_close(to_host(M[r]), mr, 1e-3)
+            assert same_bits(to_host(W16[r]), oracle.f32_to_bf16_bits(to_host(W[r])))
+        plan.free()
+
+
+# --------------------------------------------------------------------------------------- LAMB
+
+def _lamb_all_replicas(plan, oplan, W, G, M, V, hp, t, fused_for=None, W16=None):
+    """Runs one LAMB step for every replica on one GPU.  The sum over replicas of the [V][2] tables
+    stands in for the cross-replica all-reduce (Section 4.1)."""
+    N, nv = oplan.N, oplan.V
+    local = torch.zeros((N, ((nv * 2 + 3) // 4) * 4), dtype=torch.float32, device=DEV)          # 16-byte aligned rows
+    for r in range(N):
+        su.shard_update_lamb_partials(plan, r, W[r], G[r], M[r], V[r], hp, t, local[r])
+    local = local[:, :nv * 2].reshape(N, nv, 2).contiguous()
+    total = local.sum(dim=0)
+    for r in range(N):
+        su.shard_update_lamb_apply(plan, r, W[r], M[r], V[r], hp, t, total,
+                                   w_bf16_out=None if W16 is None else W16[r])
+    return local, total
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ragged_align1"])
+def test_lamb_all_replicas_against_unsharded_oracle(case):
+    if case == "tiny":
+        cfg = _cfg("tiny"); numel, N, seed, align = cfg.numel, 4, cfg.seed, 8
+    else:
+        numel, N, seed = RAGGED, 6, 98
+        align = 8 if case == "ragged" else 1
+    print("lamb", case, flush=True)
+    nv = len(numel)
+    flags = [0] * nv
+    flags[2] = su.SHARD_VAR_NO_DECAY
+    flags[-1] = su.SHARD_VAR_NO_ADAPT
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align, flags))
+    ws, _ = gen_weights_grads(seed, numel, 0.02, 1e-3)
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]; uv = [np.zeros_like(w) for w in ws]
+    W = dev_rows(shards_of(oplan, ws)); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    for t in range(1, 4):
+        gs = [normal_f32(seed, i, "g", n, 1e-3, t) for i, n in enumerate(numel)]
+        G = dev_rows(shards_of(oplan, gs))
+        uw, um, uv, usums = oracle.lamb_unsharded_step(uw, gs, um, uv, LAMB, t, flags)
+        local, total = _lamb_all_replicas(plan, oplan, W, G, M, V, LAMB, t)
+        # the all-reduced sums of squares agree with the oracle's whole-variable sums
+        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        Wh = host_rows(W)
+        for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, Wh))):
+            assert_weights_close(b, a, "w var %d t=%d" % (i, t))
+        for a, b in zip(um, oracle.unshard_format(oplan, host_rows(M))):
+            assert_first_moment_close(b, a, 1e-3, t)
+        for a, b in zip(uv, oracle.unshard_format(oplan, host_rows(V))):
+            assert_second_moment_close(b, a, t)
+        for r in range(N):
+            assert pads_are_zero(oplan, r, Wh[r])
+    plan.free()
+
+
+def test_lamb_partials_match_oracle_partials_and_mask_padding_by_position():
+    numel, N = [10, 3, 4100, 64], 4
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    ws, gs = gen_weights_grads(21, numel, 0.02, 1e-3)
+    W_ref = shards_of(oplan, ws); G_ref = shards_of(oplan, gs)
+    for r in range(N):
+        z = np.zeros_like(W_ref[r])
+        _, _, _, want = oracle.lamb_shard_partials(oplan, r, W_ref[r], G_ref[r], z, z, LAMB, 1)
+        # fill the padded slots with garbage: the sums must not move (Section 4.1, mask by position)
+        Wd, Gd = W_ref[r].copy(), G_ref[r].copy()
+        for i in range(oplan.V):
+            real = oplan.real_count(i, r)
+            Wd[oplan.off[i] + real: oplan.off[i] + oplan.L[i]] = 5.0
+            Gd[oplan.off[i] + real: oplan.off[i] + oplan.L[i]] = -3.0
+        for Wx, Gx in ((W_ref[r], G_ref[r]), (Wd, Gd)):
+            out = torch.full((oplan.V, 2), -1.0, dtype=torch.float32, device=DEV)
+            su.shard_update_lamb_partials(plan, r, to_dev(Wx), to_dev(Gx), to_dev(z), to_dev(z), LAMB, 1, out)
+            np.testing.assert_allclose(to_host(out).astype(np.float64), want, rtol=3e-6, atol=1e-30)
+    plan.free()
+
+
+def test_lamb_fused_call_equals_split_calls_and_is_reproducible():
+    cfg = _cfg("tiny")
+    numel, N, seed = cfg.numel, 4, cfg.seed
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    ws, gs = gen_weights_grads(seed, numel, 0.02, 1e-3)
+    W0 = to_dev(shards_of(oplan, ws)); G = to_dev(shards_of(oplan, gs))
+    W = W0.clone(); M = torch.zeros_like(W); V = torch.zeros_like(W)
+    W16 = torch.zeros(W.shape, dtype=torch.bfloat16, device=DEV)
+    local, total = _lamb_all_replicas(plan, oplan, W, G, M, V, LAMB, 1, W16=W16)
+    for rep in range(2):                                    # twice: run-to-run identical bits
+        Wf = W0.clone(); Mf = torch.zeros_like(W); Vf = torch.zeros_like(W)
+        W16f = torch.zeros_like(W16)
+        for r in range(N):
+            others = total - local[r]
+            mine = torch.zeros((oplan.V, 2), dtype=torch.float32, device=DEV)
+            su.shard_update_lamb(plan, r, Wf[r], G[r], Mf[r], Vf[r], LAMB, 1, other_replicas_sumsq=others,
+                                 local_sumsq_out=mine, w_bf16_out=W16f[r])
+            assert torch.equal(mine, local[r])
+        assert torch.equal(Mf, M) and torch.equal(Vf, V)
+        # local + (total - local) differs from total by float32 rounding of the sums only
+        assert_weights_close(to_host(Wf).ravel(), to_host(W).ravel())
+        assert float((Wf - W).abs().max()) <= 1e-9
+        assert same_bits(to_host(W16f), oracle.f32_to_bf16_bits(to_host(Wf).ravel()).reshape(W16f.shape))
+        if rep == 0:
+            first = Wf.clone()
+        else:
+            assert torch.equal(first, Wf)
+    # with a single replica the fused call needs no table from anyone
+    oplan1 = oracle.make_plan(numel, 1, 8)
+    plan1 = su.shard_plan_bind(su.shard_plan(numel, 1, 8))
+    W1 = to_dev(shards_of(oplan1, ws)); G1 = to_dev(shards_of(oplan1, gs))
+    M1 = torch.zeros_like(W1); V1 = torch.zeros_like(W1)
+    su.shard_update_lamb(plan1, 0, W1[0], G1[0], M1[0], V1[0], LAMB, 1)
+    z = [np.zeros_like(w) for w in ws]
+    uw, _, _, _ = oracle.lamb_unsharded_step(ws, gs, z, z, LAMB, 1)
+    for a, b in zip(uw, oracle.unshard_format(oplan1, to_host(W1))):
+        assert_weights_close(b, a)
+    plan.free(); plan1.free()
+
+
+@pytest.fixture(scope="module")
+def bert_reference():
+    """One unsharded oracle LAMB step on the BERT-large-shaped model (config 4), shared by both replica counts."""
+    cfg = _cfg("bert_large")
+    hp = f32_hp(cfg.hyper)
+    ws, gs = gen_weights_grads(cfg.seed, cfg.numel, cfg.weight_std, cfg.grad_std, 1)
+    z = [np.zeros_like(w) for w in ws]
+    print("oracle: unsharded LAMB on 336M parameters", flush=True)
+    uw, um, uv, usums = oracle.lamb_unsharded_step(ws, gs, z, z, hp, 1)
+    return cfg, hp, ws, gs, uw, um, uv, usums
+
+
+@pytest.mark.parametrize("N", [8, 64])
+def test_lamb_bert_large_full_size_all_replicas(bert_reference, N):
+    """Config 4 at full size in the launch configuration the benchmark times: every replica's shard is
+    updated on the one GPU, the tables are summed in place of the all-reduce, and the weights put back
+    together are compared with the oracle's unsharded step, element by element."""
+    cfg, hp, ws, gs, uw, um, uv, usums = bert_reference
+    print("lamb bert N=%d" % N, flush=True)
+    oplan = oracle.make_plan(cfg.numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8))
+    W = to_dev(shards_of(oplan, ws)); G = to_dev(shards_of(oplan, gs))
+    M = torch.zeros_like(W); V = torch.zeros_like(W)
+    local, total = _lamb_all_replicas(plan, oplan, W, G, M, V, hp, 1)
+    np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+    Wh = to_host(W)
+    worst = 0.0
+    for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, Wh))):
+        worst = max(worst, assert_weights_close(b, a, "w var %d" % i))
+    print("max |dw| = %.3g" % worst, flush=True)
+    for a, b in zip(um, oracle.unshard_format(oplan, to_host(M))):
+        assert_first_moment_close(b, a, cfg.grad_std)
+    for a, b in zip(uv, oracle.unshard_format(oplan, to_host(V))):
+        assert_second_moment_close(b, a)
+    for r in (0, N - 1):
+        assert pads_are_zero(oplan, r, Wh[r])
+    plan.free()
+
+
+def test_adam_transformer_big_16_replicas_sampled():
+    """Config 3: 257 variables, 210M parameters, 16 replicas; replicas 0, 15 and 9 checked in full."""
+    cfg = _cfg("transformer_big")
+    N = 16
+    print("adam transformer N=16", flush=True)
+    hp = f32_hp(cfg.hyper)
+    oplan = oracle.make_plan(cfg.numel, N, 8)
+    plan = su.shard_plan(cfg.numel, N, 8)
+    ws, gs = gen_weights_grads(cfg.seed, cfg.numel, cfg.weight_std, cfg.grad_std, 1)
+    for r in (0, 15, 9):
+        w_ref = oracle.shard_format(oplan, r, ws); g_ref = oracle.shard_format(oplan, r, gs)
+        W = to_dev(w_ref); G = to_dev(g_ref); M = torch.zeros_like(W); V = torch.zeros_like(W)
+        m_ref = np.zeros_like(w_ref); v_ref = np.zeros_like(w_ref)
+        for t in (1, 2):
+            su.shard_update_adam(plan, r, W, G, M, V, hp, t)
+            w_ref, m_ref, v_ref = oracle.adam_step(w_ref, g_ref, m_ref, v_ref, hp, t)
+        assert_weights_close(to_host(W), w_ref, "r=%d" % r)
+        assert_first_moment_close(to_host(M), m_ref, cfg.grad_std, 2)
+        assert_second_moment_close(to_host(V), v_ref, 2)
+    plan.free()
+
+
+@pytest.mark.parametrize("N", [1, 128])
+def test_mixed_precision_adam_1p5b_sampled_variables(N):
+    """Config 5: fp32 master weights, m, v and gradient, bf16 copy of the weights written by the update.
+    The update is element-wise, so the sampled variables (embedding slice owner, first and last layer,
+    every [1600] vector of those layers, the final LayerNorm) are generated by the seeded host generator
+    and checked against the oracle; the rest of the shard is filled with device-side noise of the same
+    distribution, and the bf16 copy is checked over the whole shard."""
+    cfg = _cfg("lm_1p5b")
+    print("mixed adam 1.5B N=%d" % N, flush=True)
+    hp = f32_hp(cfg.hyper)
+    oplan = oracle.make_plan(cfg.numel, N, 8)
+    plan = su.shard_plan(cfg.numel, N, 8)
+    r = 0 if N == 1 else 5
+    S = oplan.S
+    gen = torch.Generator(device=DEV); gen.manual_seed(cfg.seed)
+    W = torch.empty(S, dtype=torch.float32, device=DEV).normal_(0.0, cfg.weight_std, generator=gen)
+    G = torch.empty(S, dtype=torch.float32, device=DEV).normal_(0.0, cfg.grad_std, generator=gen)
+    M = torch.zeros(S, dtype=torch.float32, device=DEV); V = torch.zeros(S, dtype=torch.float32, device=DEV)
+    W16 = torch.zeros(S, dtype=torch.bfloat16, device=DEV)
+    nv = len(cfg.numel)
+    sampled = sorted(set(list(range(1, 17)) + list(range(nv - 18, nv)) + ([0] if N > 1 else [])))
+    refs = {}
+    for i in sampled:
+        n = cfg.numel[i]
+        w = normal_f32(cfg.seed, i, "w", n, cfg.weight_std); g = normal_f32(cfg.seed, i, "g", n, cfg.grad_std, 1)
+        start, real = r * oplan.L[i], oplan.real_count(i, r)
+        wp = np.zeros(oplan.L[i], np.float32); gp = np.zeros(oplan.L[i], np.float32)
+        wp[:real] = w[start:start + real]; gp[:real] = g[start:start + real]
+        seg = slice(oplan.off[i], oplan.off[i] + oplan.L[i])
+        W[seg] = torch.from_numpy(wp).to(DEV); G[seg] = torch.from_numpy(gp).to(DEV)
+        refs[i] = (wp, gp, np.zeros_like(wp), np.zeros_like(wp))
+    for t in (1, 2):
+        su.shard_update_adam(plan, r, W, G, M, V, hp, t, w_bf16_out=W16)
+        for i in sampled:
+            wp, gp, mp, vp = refs[i]
+            wp, mp, vp = oracle.adam_step(wp, gp, mp, vp, hp, t)
+            refs[i] = (wp, gp, mp, vp)
+    torch.cuda.synchronize()
+    for i in sampled:
+        seg = slice(oplan.off[i], oplan.off[i] + oplan.L[i])
+        wp, gp, mp, vp = refs[i]
+        assert_weights_close(to_host(W[seg]), wp, "var %d" % i)
+        assert_first_moment_close(to_host(M[seg]), mp, cfg.grad_std, 2)
+        assert_second_moment_close(to_host(V[seg]), vp, 2)
+        assert same_bits(to_host(W16[seg]), oracle.f32_to_bf16_bits(to_host(W[seg])))
+    # bf16 copy over the whole shard: torch's own float32->bfloat16 conversion rounds to nearest even
+    assert torch.equal(W16.view(torch.int16), W.to(torch.bfloat16).view(torch.int16))
+    assert bool(torch.isfinite(W).all())
+    plan.free()

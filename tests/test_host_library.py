@@ -1,0 +1,137 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its
+host-side plan arithmetic agrees with the oracle's independent plan.  No kernel is launched."""
+import ctypes as C
+import os
+import random
+import re
+
+import pytest
+
+import paper_2004_13336_amd as su
+from paper_2004_13336_amd._lib import SIGNATURES, lib
+from oracle import make_plan
+from workloads import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "shardupdate.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(shard_[a-z_0-9]+|unshard_format)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert "shard_plan" in names and "unshard_format" in names and "shard_update_lamb" in names
+    handle = lib()
+    for name in names:
+        assert hasattr(handle, name), name
+    # and the binding knows a signature for each of them
+    assert set(names) == set(SIGNATURES)
+
+
+def test_status_strings():
+    assert lib().shard_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert lib().shard_strerror(code) not in (b"ok", b"unknown status")
+    assert lib().shard_kernel_name(4) == b"lamb_p1_kernel"
+    assert lib().shard_kernel_name(99) is None
+
+
+@pytest.mark.parametrize("align", [1, 4, 8, 64])
+def test_plan_matches_oracle_on_random_lists(align):
+    rnd = random.Random(align)
+    sizes = [0, 1, 2, 3, 7, 8, 9, 63, 64, 65, 127, 128, 129, 1000, 1023, 1024, 1025, 4095, 4096, 4097, 65537, 300001]
+    for _ in range(40):
+        N = rnd.randint(1, 130)
+        numel = [rnd.choice(sizes + [N - 1, N, N + 1]) for _ in range(rnd.randint(0, 14))]
+        want = make_plan(numel, N, align)
+        got = su.shard_plan(numel, N, align)
+        assert (got.S, got.total) == (want.S, sum(numel))
+        off, length = got.segments()
+        assert off == want.off and length == want.L
+        for r in {0, N // 2, N - 1}:
+            assert got.real_count(r) == tuple(want.real_count(i, r) for i in range(len(numel)))
+        got.free()
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_plan_matches_oracle_on_the_benchmark_configs(cfg):
+    for N in cfg.replicas:
+        want = make_plan(cfg.numel, N, 8)
+        got = su.shard_plan(cfg.numel, N, 8)
+        assert got.S == want.S and got.total == cfg.total
+        off, length = got.segments()
+        assert off == want.off and length == want.L
+        # chunk count: every variable is cut into ceil(L / chunk) chunks of the default size
+        assert got.n_chunks == sum(-(-L // 4096) for L in want.L)
+        got.free()
+
+
+def test_shard_sizes_of_the_headline_config():
+    # BERT-large-shaped, 8 replicas: 398 variables, 336 226 108 parameters, 42 028 272 slots per shard.
+    bert = CONFIGS[3]
+    p = su.shard_plan(bert.numel, 8)
+    assert (p.V, p.total, p.S) == (398, 336226108, 42028272)
+    p.free()
+
+
+def test_chunk_sizes():
+    for chunk in (1024, 2048, 8192, 16384):
+        p = su.shard_plan([100000, 5], 3, 8, None, chunk)
+        L = make_plan([100000, 5], 3, 8).L
+        assert p.n_chunks == sum(-(-x // chunk) for x in L)
+        p.free()
+
+
+def _raw_plan(V, numel, N, align, flags=None, chunk=0):
+    arr = (C.c_int64 * max(len(numel), 1))(*numel) if numel is not None else None
+    fl = (C.c_uint32 * max(len(flags), 1))(*flags) if flags is not None else None
+    h = C.c_void_p()
+    rc = lib().shard_plan(V, arr, N, align, fl, chunk, C.byref(h))
+    if rc == 0:
+        lib().shard_plan_free(h)
+    return rc
+
+
+def test_plan_argument_errors():
+    EINVAL = -1
+    assert _raw_plan(1, [4], 0, 8) == EINVAL            # N < 1
+    assert _raw_plan(1, [4], 2, 3) == EINVAL            # align not a power of two
+    assert _raw_plan(1, [4], 2, 0) == EINVAL
+    assert _raw_plan(-1, [4], 2, 8) == EINVAL
+    assert _raw_plan(1, [-4], 2, 8) == EINVAL
+    assert _raw_plan(1, None, 2, 8) == EINVAL
+    assert _raw_plan(1, [4], 2, 8, flags=[8]) == EINVAL  # unknown flag bit
+    assert _raw_plan(1, [4], 2, 8, chunk=1000) == EINVAL
+    assert _raw_plan(1, [4], 2, 8, chunk=32768) == EINVAL
+    assert _raw_plan(1, [2 ** 62], 2, 8) == EINVAL       # would overflow byte offsets
+    assert lib().shard_plan(1, (C.c_int64 * 1)(4), 2, 8, None, 0, None) == EINVAL
+    assert _raw_plan(0, [], 4, 8) == 0                   # an empty model is legal
+    assert _raw_plan(2, [0, 0], 4, 8) == 0
+
+
+def test_calls_that_need_a_workspace_say_so_without_touching_the_gpu():
+    ESTATE, EINVAL = -5, -1
+    p = su.shard_plan([100, 7], 2)
+    hp = su._lib.LambHP(1e-3, 0.9, 0.999, 1e-6, 0.01)
+    fake = C.c_void_p(0x1000)
+    arr = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib().shard_format(p.handle, 0, arr, 0, fake, 0, None) == ESTATE
+    assert lib().unshard_format(p.handle, fake, 0, arr, 0, None) == ESTATE
+    assert lib().shard_update_lamb(p.handle, 0, fake, fake, fake, fake, None, C.byref(hp), 1, None, None, None) == ESTATE
+    # replica id is checked before anything else
+    assert lib().shard_format(p.handle, 2, arr, 0, fake, 0, None) == EINVAL
+    assert lib().shard_format(p.handle, -1, arr, 0, fake, 0, None) == EINVAL
+    ahp = su._lib.AdamHP(1e-3, 0.9, 0.999, 1e-8, 0.0)
+    assert lib().shard_update_adam(p.handle, 0, fake, fake, fake, fake, None, C.byref(ahp), 0, None) == EINVAL  # step 0
+    bad = su._lib.AdamHP(1e-3, 0.9, 0.999, 0.0, 0.0)
+    assert lib().shard_update_adam(p.handle, 0, fake, fake, fake, fake, None, C.byref(bad), 1, None) == EINVAL  # eps 0
+    bad = su._lib.AdamHP(1e-3, 1.0, 0.999, 1e-8, 0.0)
+    assert lib().shard_update_adam(p.handle, 0, fake, fake, fake, fake, None, C.byref(bad), 1, None) == EINVAL  # beta1 = 1
+    assert lib().shard_update_adam(p.handle, 0, None, fake, fake, fake, None, C.byref(ahp), 1, None) == EINVAL  # null w
+    misaligned = C.c_void_p(0x1004)
+    assert lib().shard_update_adam(p.handle, 0, misaligned, fake, fake, fake, None, C.byref(ahp), 1, None) == -3
+    p.free()
