@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--chunk", type=int, default=0, help="chunk_elems of the plan (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", default=None, help="also time every config x stage and write a JSON table here")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run one plain device copy of 1 GiB (2^28 float32), so that a rocprofv3 --pmc run "
+                         "has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -86,7 +89,9 @@ class Workbench:
         gen.manual_seed(cfg.seed)
         self.gen = gen
         # the gathered [N][S] buffer; row r is this replica's weight shard, updated in place
-        self.gathered = _device_normal(N * S, cfg.weight_std, gen, torch).view(N, S) if want_full else None
+        self.gathered = None
+        if want_full:                      # rows on 128-byte boundaries
+            self.gathered = su.gathered_empty(self.plan).normal_(0.0, cfg.weight_std, generator=gen)
         self.w = self.gathered[r] if want_full else _device_normal(S, cfg.weight_std, gen, torch)
         self.g = torch.zeros(S, dtype=torch.float32, device="cuda")
         self.m = torch.zeros(S, dtype=torch.float32, device="cuda")
@@ -101,7 +106,8 @@ class Workbench:
                 self.full_g.append(flat_g[pos:pos + n])
                 self.full_w.append(flat_w[pos:pos + n])
                 pos += n
-            # zero the padded slots of row r (other rows' padding is never read by unshard_format)
+            self.full_g = su.FullTensors(self.plan, self.full_g)      # marshalled once, reused every step
+            self.full_w = su.FullTensors(self.plan, self.full_w)
             su.shard_format(self.plan, r, self.full_g, self.g)
         else:
             self.g.normal_(0.0, cfg.grad_std, generator=gen)
@@ -127,11 +133,9 @@ def headline(args, torch, su, cfgs):
         raise SystemExit("the headline step is the LAMB configuration; use --table for the others")
     # clean padding in this replica's weight row, then pre-warm m and v by two steps so no lane
     # works on all-zero state; the other replicas' sums are (N-1) copies of this replica's
-    wb_full_w_src = [t.clone() for t in wb.full_w]
-    for t, n in zip(wb_full_w_src, cfg.numel):
+    for t in wb.full_w.tensors:
         t.normal_(0.0, cfg.weight_std, generator=wb.gen)
-    su.shard_format(plan, r, wb_full_w_src, wb.w)
-    del wb_full_w_src
+    su.shard_format(plan, r, wb.full_w, wb.w)
     su.shard_update_lamb_partials(plan, r, wb.w, wb.g, wb.m, wb.v, hp, 1, wb.local)
     wb.m.zero_(); wb.v.zero_()
     wb.other.copy_(wb.local * float(N - 1))
@@ -175,13 +179,15 @@ def headline(args, torch, su, cfgs):
                                "frac": round(gbs / HBM_PEAK_GBS, 4), "avg_us": round(kern[name]["avg_us"], 2),
                                "bytes": b}
     dominant = max(rooflines, key=lambda k: rooflines[k]["avg_us"])
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate runs of
+    # this same workload; the summary under profiles/ holds "traffic <kernel> <bytes>" lines
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "bench_%s_lamb_n%d_hbm_traffic.txt" % (cfg.name, N))
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(dominant + "_kernel")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dominant + "_kernel":
+                traffic = int(parts[2])
     roof = dict(rooflines[dominant])
     roof["kernel"] = dominant + "_kernel"
     roof["traffic"] = traffic
@@ -203,7 +209,7 @@ def headline(args, torch, su, cfgs):
         "config": {"workload": "%s fp32 LAMB N=%d r=%d: shard_format(g) + shard_update_lamb + unshard_format(w)"
                                % (cfg.name, N, r),
                    "variables": plan.V, "params": cfg.total, "shard_slots": S, "shard_params": wb.real,
-                   "chunk_elems": args.chunk or 4096},
+                   "chunk_elems": plan.chunk_elems},
         "roofline": roof,
         "kernels": rooflines,
         "update_only": update_only,
@@ -227,17 +233,21 @@ def cpu_baseline(cfg, N, r):
                                                 for i, n in enumerate(cfg.numel)])
     m = np.zeros(plan.S, np.float32); v = np.zeros(plan.S, np.float32)
     del rng
-    t0 = time.perf_counter()
-    g = oracle.shard_format(plan, r, gs)
-    m, v, u, part = oracle.lamb_shard_partials(plan, r, gathered[r], g, m, v, hp, 1)
-    gathered[r] = oracle.lamb_shard_apply(plan, gathered[r], u, part * N, hp)
-    full = oracle.unshard_format(plan, gathered)
-    dt = time.perf_counter() - t0
     real = sum(plan.real_count(i, r) for i in range(plan.V))
-    assert len(full) == plan.V
-    return {"value": real / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "1 step of the same workload (%s N=%d r=%d, all %d variables: format g, LAMB on the shard, "
-                      "unformat the whole model), %.1f s" % (cfg.name, N, r, plan.V, dt),
+    steps, t0 = 0, time.perf_counter()
+    while True:                                   # whole steps until about 12 s of CPU work are done
+        steps += 1
+        g = oracle.shard_format(plan, r, gs)
+        m, v, u, part = oracle.lamb_shard_partials(plan, r, gathered[r], g, m, v, hp, steps)
+        gathered[r] = oracle.lamb_shard_apply(plan, gathered[r], u, part * N, hp)
+        full = oracle.unshard_format(plan, gathered)
+        assert len(full) == plan.V
+        dt = time.perf_counter() - t0
+        if dt >= 12.0 or steps >= 64:
+            break
+    return {"value": real * steps / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "%d steps of the same workload (%s N=%d r=%d, all %d variables: format g, LAMB on the shard, "
+                      "unformat the whole model) in %.1f s" % (steps, cfg.name, N, r, plan.V, dt),
             "seconds": round(dt, 2)}
 
 
@@ -307,6 +317,14 @@ def main():
     import paper_2004_13336_amd as su
     from workloads import CONFIGS
     su.lib()
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     out = headline(args, torch, su, CONFIGS)
     if args.table:
         table(args, torch, su, CONFIGS, args.table)

@@ -18,7 +18,7 @@
  *     L_i   = roundup(ceil(n_i / N), align)         piece length, equal on all replicas
  *     off_i = L_0 + ... + L_{i-1},   S = sum L_i    one piece of every variable per shard
  *     shard_r[off_i + k] = (r*L_i + k < n_i) ? var_i[r*L_i + k] : +0.0     0 <= k < L_i
- *     gathered[r][..]    = shard_r                                          shape [N][S]
+ *     gathered[r][..]    = shard_r                                          shape [N][S] (rows may be strided)
  * Gradient, weight and every auxiliary variable use the same plan (Section 4.1: all
  * inputs of the update must be sharded the same way).
  *
@@ -30,8 +30,8 @@
  *    buffer, including the plan's tables (shard_plan_bind), is the caller's.
  *  - Device buffers of packed shards (w, g, m, v, shard_out, gathered, bf16 outputs,
  *    sums) must be 16-byte aligned, else SHARD_EALIGN.  Full tensors may have any
- *    alignment; 16-byte aligned ones (with align_elems a multiple of 8) take the
- *    128-bit path, others a slower element-wise path with the same results.
+ *    alignment; each 16-byte aligned one (with align_elems a multiple of 8) is moved with
+ *    128-bit accesses, the others element by element, with the same results.
  *  - Kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
  *    stream) and are asynchronous; errors reported are argument and launch errors.
  *  - A plan is not thread-safe, and calls that use one plan must be ordered on one
@@ -98,10 +98,11 @@ int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32
  *   S                packed shard length in elements
  *   total            sum of n_i
  *   n_chunks         entries of the chunk table (a chunk never crosses a variable boundary)
+ *   chunk_elems      the chunk size in use
  *   workspace_bytes  device bytes shard_plan_bind needs
  */
 int shard_plan_info(const shard_plan_t* plan, int64_t* S, int64_t* total, int64_t* n_chunks,
-                    size_t* workspace_bytes);
+                    int* chunk_elems, size_t* workspace_bytes);
 
 /* Copies off_i and L_i into host arrays [V] (either may be NULL). */
 int shard_plan_segments(const shard_plan_t* plan, int64_t* seg_off, int64_t* seg_len);
@@ -130,11 +131,15 @@ void shard_plan_free(shard_plan_t* plan);
 int shard_format(shard_plan_t* plan, int r, const void* const* full_ptrs, int src_dtype,
                  void* shard_out, int dst_dtype, shard_stream_t stream);
 
-/* unshard_format: the reverse formatting after the all-gather (Section 4.2).  Reads
- * gathered[N][S] (device, src_dtype) and writes every full variable (device pointers in the
- * HOST array full_ptrs[V], dst_dtype), dropping the padding.  Same dtype pairs as shard_format
- * (f32->bf16 is the reduced-precision weight the forward pass needs, Section 4.2). */
-int unshard_format(shard_plan_t* plan, const void* gathered, int src_dtype,
+/* unshard_format: the reverse formatting after the all-gather (Section 4.2).  Reads the gathered
+ * shards (device, src_dtype), row r = shard_r starting at element r * row_stride, and writes every
+ * full variable (device pointers in the HOST array full_ptrs[V], dst_dtype), dropping the padding.
+ *   row_stride  distance between rows in elements, >= S; 0 means S (rows back to back).  Rows that
+ *               start on 128-byte boundaries (row_stride a multiple of 32 float32 / 64 bfloat16
+ *               elements) copy fastest; the slots between S and row_stride are never touched.
+ * Same dtype pairs as shard_format (f32->bf16 is the reduced-precision weight the forward pass
+ * needs, Section 4.2). */
+int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride, int src_dtype,
                    void* const* full_ptrs, int dst_dtype, shard_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------

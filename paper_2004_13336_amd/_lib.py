@@ -42,13 +42,13 @@ SIGNATURES = {
     "shard_strerror": (C.c_char_p, [C.c_int]),
     "shard_kernel_name": (C.c_char_p, [C.c_int]),
     "shard_plan": (C.c_int, [C.c_int, _I64P, C.c_int, C.c_int, C.POINTER(C.c_uint32), C.c_int, C.POINTER(_P)]),
-    "shard_plan_info": (C.c_int, [_P, _I64P, _I64P, _I64P, C.POINTER(C.c_size_t)]),
+    "shard_plan_info": (C.c_int, [_P, _I64P, _I64P, _I64P, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]),
     "shard_plan_segments": (C.c_int, [_P, _I64P, _I64P]),
     "shard_plan_real_count": (C.c_int, [_P, C.c_int, _I64P]),
     "shard_plan_bind": (C.c_int, [_P, _P, C.c_size_t, _P]),
     "shard_plan_free": (None, [_P]),
     "shard_format": (C.c_int, [_P, C.c_int, C.POINTER(_P), C.c_int, _P, C.c_int, _P]),
-    "unshard_format": (C.c_int, [_P, _P, C.c_int, C.POINTER(_P), C.c_int, _P]),
+    "unshard_format": (C.c_int, [_P, _P, C.c_int64, C.c_int, C.POINTER(_P), C.c_int, _P]),
     "shard_update_adam": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(AdamHP), C.c_int64, _P]),
     "shard_update_momentum": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(MomentumHP), _P]),
     "shard_update_lamb_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
@@ -64,9 +64,10 @@ def lib() -> C.CDLL:
     """The loaded library; built in-tree first if no built library is there."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("SHARDUPDATE_LIB", LIB_PATH)      # another build of the same library, e.g. a tuning variant
+        if path == LIB_PATH and not os.path.exists(LIB_PATH):
             build_library()
-        handle = C.CDLL(LIB_PATH)
+        handle = C.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(handle, name)          # AttributeError if the library lacks a declared symbol
             fn.restype = res

@@ -63,10 +63,11 @@ class Plan:
         self.handle = handle
         self.V, self.N, self.align = V, int(N), int(align_elems)
         self.numel = tuple(int(n) for n in numel)
-        S, total, nch, wsb = C.c_int64(), C.c_int64(), C.c_int64(), C.c_size_t()
-        _check(lib().shard_plan_info(handle, C.byref(S), C.byref(total), C.byref(nch), C.byref(wsb)),
+        S, total, nch, chunk, wsb = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int(), C.c_size_t()
+        _check(lib().shard_plan_info(handle, C.byref(S), C.byref(total), C.byref(nch), C.byref(chunk), C.byref(wsb)),
                "shard_plan_info")
         self.S, self.total, self.n_chunks, self.workspace_bytes = S.value, total.value, nch.value, wsb.value
+        self.chunk_elems = chunk.value
         self.workspace: Optional[torch.Tensor] = None
 
     def segments(self) -> Tuple[Tuple[int, ...], Tuple[int, ...]]:
@@ -107,7 +108,21 @@ def shard_plan_bind(plan: Plan, workspace: Optional[torch.Tensor] = None, stream
     return plan
 
 
-def _full_ptrs(plan: Plan, tensors: Sequence[torch.Tensor], what: str):
+class FullTensors:
+    """A list of full tensors checked and marshalled once, for callers that pass the same tensors every
+    step (the per-call checks walk all V tensors in Python).  Keeps the tensors alive."""
+
+    def __init__(self, plan: Plan, tensors: Sequence[torch.Tensor], what: str = "full_tensors"):
+        self.tensors = list(tensors)
+        self.V = plan.V
+        self.arr, self.dtype = _full_ptrs(plan, self.tensors, what)
+
+
+def _full_ptrs(plan: Plan, tensors, what: str):
+    if isinstance(tensors, FullTensors):
+        if tensors.V != plan.V:
+            raise ValueError("%s was built for another plan" % what)
+        return tensors.arr, tensors.dtype
     if len(tensors) != plan.V:
         raise ValueError("%s: expected %d tensors, got %d" % (what, plan.V, len(tensors)))
     dtype = None
@@ -136,12 +151,30 @@ def shard_format(plan: Plan, r: int, full_tensors: Sequence[torch.Tensor], shard
     return shard_out
 
 
+def gathered_empty(plan: Plan, dtype=torch.float32, device="cuda") -> torch.Tensor:
+    """An uninitialised [N, S] view whose rows start on 128-byte boundaries (the layout unshard_format likes)."""
+    per_line = 128 // torch.empty((), dtype=dtype).element_size()
+    stride = -(-plan.S // per_line) * per_line
+    return torch.empty((plan.N, stride), dtype=dtype, device=device)[:, : plan.S]
+
+
 def unshard_format(plan: Plan, gathered: torch.Tensor, full_tensors: Sequence[torch.Tensor], stream=None):
+    """gathered: [N, S] (rows may be strided, e.g. from gathered_empty) or a flat tensor of N*S elements."""
     arr, dst = _full_ptrs(plan, full_tensors, "full_tensors")
-    if gathered.dtype not in _DTYPES:
-        raise ValueError("unsupported gathered dtype")
-    _check(lib().unshard_format(plan.handle, _dev(gathered, plan.N * plan.S, None, "gathered"),
-                                _DTYPES[gathered.dtype], arr, _DTYPES[dst], _stream(stream)), "unshard_format")
+    if gathered.dtype not in _DTYPES or not gathered.is_cuda:
+        raise ValueError("gathered must be a float32 or bfloat16 CUDA tensor")
+    if gathered.dim() == 2:
+        if gathered.shape != (plan.N, plan.S) or (plan.S > 0 and gathered.stride(1) != 1):
+            raise ValueError("gathered must have shape [N, S] with unit stride along S")
+        stride = gathered.stride(0) if plan.N > 1 else plan.S
+        if stride < plan.S:
+            raise ValueError("gathered rows overlap")
+        ptr = C.c_void_p(gathered.data_ptr())
+    else:
+        stride = plan.S
+        ptr = _dev(gathered, plan.N * plan.S, None, "gathered")
+    _check(lib().unshard_format(plan.handle, ptr, int(stride), _DTYPES[gathered.dtype], arr, _DTYPES[dst],
+                                _stream(stream)), "unshard_format")
     return full_tensors
 
 

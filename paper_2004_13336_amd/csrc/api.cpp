@@ -77,13 +77,9 @@ int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t str
   return SHARD_OK;
 }
 
-// 128-bit path: pieces start on 16-byte boundaries for both element sizes and every tensor does too.
-bool full_tensors_vectorisable(const shard_plan_t* p, const void* const* ptrs) {
-  if (p->align % 8 != 0) return false;
-  for (int i = 0; i < p->V; ++i)
-    if (p->n[i] > 0 && !aligned16(ptrs[i])) return false;
-  return true;
-}
+// 128-bit path: pieces start on 16-byte boundaries for both element sizes.  (Whether each full
+// tensor does too is checked per variable inside the kernels.)
+bool pieces_vectorisable(const shard_plan_t* p) { return p->align % 8 == 0; }
 
 int check_full_ptrs(const shard_plan_t* p, const void* const* ptrs) {
   if (p->V > 0 && ptrs == nullptr) return SHARD_EINVAL;
@@ -132,11 +128,13 @@ int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32
   return SHARD_OK;
 }
 
-int shard_plan_info(const shard_plan_t* p, int64_t* S, int64_t* total, int64_t* n_chunks, size_t* workspace_bytes) {
+int shard_plan_info(const shard_plan_t* p, int64_t* S, int64_t* total, int64_t* n_chunks, int* chunk_elems,
+                    size_t* workspace_bytes) {
   if (p == nullptr) return SHARD_EINVAL;
   if (S) *S = p->S;
   if (total) *total = p->total;
   if (n_chunks) *n_chunks = (int64_t)p->chunks.size();
+  if (chunk_elems) *chunk_elems = p->chunk;
   if (workspace_bytes) *workspace_bytes = p->ws_need;
   return SHARD_OK;
 }
@@ -204,21 +202,25 @@ int shard_format(shard_plan_t* p, int r, const void* const* full_ptrs, int src_d
   const void** table = nullptr;
   if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
   return hip_status(launch_format(p, r, table, src_dtype, shard_out, dst_dtype,
-                                  full_tensors_vectorisable(p, full_ptrs), as_stream(stream)));
+                                  pieces_vectorisable(p), as_stream(stream)));
 }
 
-int unshard_format(shard_plan_t* p, const void* gathered, int src_dtype, void* const* full_ptrs, int dst_dtype,
-                   shard_stream_t stream) {
+int unshard_format(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* full_ptrs,
+                   int dst_dtype, shard_stream_t stream) {
   int rc = check_plan_r(p, 0, true);
   if (rc != SHARD_OK) return rc;
   if (!dtype_ok(src_dtype) || !dtype_ok(dst_dtype)) return SHARD_EINVAL;
+  if (row_stride == 0) row_stride = p->S;
+  if (row_stride < p->S) return SHARD_EINVAL;
   if ((rc = check_full_ptrs(p, full_ptrs)) != SHARD_OK) return rc;
   if (p->S == 0) return SHARD_OK;
   if ((rc = check_shard_ptr(gathered)) != SHARD_OK) return rc;
   const void** table = nullptr;
   if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
-  return hip_status(launch_unshard(p, gathered, src_dtype, reinterpret_cast<void* const*>(const_cast<void**>(table)),
-                                   dst_dtype, full_tensors_vectorisable(p, full_ptrs), as_stream(stream)));
+  const bool vec = pieces_vectorisable(p) && row_stride % 8 == 0;   // rows stay 16-byte aligned
+  return hip_status(launch_unshard(p, gathered, row_stride, src_dtype,
+                                   reinterpret_cast<void* const*>(const_cast<void**>(table)), dst_dtype, vec,
+                                   as_stream(stream)));
 }
 
 int shard_update_adam(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,

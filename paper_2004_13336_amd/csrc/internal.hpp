@@ -103,7 +103,8 @@ hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const
 
 hipError_t launch_format(shard_plan_t* p, int r, const void* const* dev_ptr_table, int src_dtype, void* out,
                          int dst_dtype, bool vec, hipStream_t stream);
-hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int src_dtype, void* const* dev_ptr_table,
+hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype,
+                          void* const* dev_ptr_table,
                           int dst_dtype, bool vec, hipStream_t stream);
 
 hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, float* v, void* w16, const AdamK& k,

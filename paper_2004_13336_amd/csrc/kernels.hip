@@ -15,16 +15,39 @@
 // The file is compiled with -ffp-contract=off: fused multiply-adds appear only where fmaf() is
 // written, so every kernel (vector path, scalar path, sharded or not) performs bit-identical
 // arithmetic per element.
+#include <type_traits>
+
 #include "internal.hpp"
 
 #ifndef SU_UNROLL
-#define SU_UNROLL 4        // 128-bit accesses per thread per stream in flight
+#define SU_UNROLL 4        // LAMB kernels: 128-bit accesses per thread per stream in flight
 #endif
-#ifndef SU_NT_LOAD
-#define SU_NT_LOAD 0       // 1: mark streaming loads non-temporal
+#ifndef SU_FLAT_UNROLL
+#define SU_FLAT_UNROLL 4   // Adam / momentum kernels: the same
 #endif
-#ifndef SU_NT_STORE
-#define SU_NT_STORE 0      // 1: mark streaming stores non-temporal
+// Cache policy per kernel family, as a 3-bit mask: 4 = non-temporal loads of streams that are only
+// read, 2 = non-temporal loads of streams the same thread writes back in place, 1 = non-temporal
+// stores.  The defaults are the measured best on MI355X for each access pattern.
+#ifndef SU_NT_ADAM
+#define SU_NT_ADAM 6
+#endif
+#ifndef SU_NT_MOMENTUM
+#define SU_NT_MOMENTUM 5
+#endif
+#ifndef SU_NT_LAMB
+#define SU_NT_LAMB 6
+#endif
+#ifndef SU_NT_FORMAT
+#define SU_NT_FORMAT 4
+#endif
+#ifndef SU_NT_UNSHARD
+#define SU_NT_UNSHARD 5
+#endif
+#ifndef SU_P1_REVERSE
+#define SU_P1_REVERSE 0        // 1: LAMB phase 1 walks the chunk table from the end
+#endif
+#ifndef SU_P2_REVERSE
+#define SU_P2_REVERSE 1        // 1: LAMB phase 2 walks it in the opposite direction to phase 1's default
 #endif
 #ifndef SU_GRID_CAP
 #define SU_GRID_CAP 0      // >0: flat kernels launch at most this many workgroups and loop
@@ -38,37 +61,43 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 constexpr int kUnroll = SU_UNROLL;
+constexpr int kFlatUnroll = SU_FLAT_UNROLL;
 
 // Four consecutive floats held in registers; moved with one 128-bit access.
 struct F4 {
   float x, y, z, w;
 };
 
-template <typename T>
-__device__ __forceinline__ T ld(const T* p) {
-#if SU_NT_LOAD
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
-}
-template <typename T>
-__device__ __forceinline__ void st(T* p, T x) {
-#if SU_NT_STORE
-  __builtin_nontemporal_store(x, p);
-#else
-  *p = x;
-#endif
-}
+template <int MASK>
+struct Policy {
+  static constexpr bool RO = (MASK & 4) != 0, RW = (MASK & 2) != 0, ST = (MASK & 1) != 0;
+};
+typedef Policy<SU_NT_ADAM> PolAdam;
+typedef Policy<SU_NT_MOMENTUM> PolMomentum;
+typedef Policy<SU_NT_LAMB> PolLamb;
+typedef Policy<SU_NT_FORMAT> PolFormat;
+typedef Policy<SU_NT_UNSHARD> PolUnshard;
 
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T x) {
+  if constexpr (NT) __builtin_nontemporal_store(x, p);
+  else *p = x;
+}
+template <bool NT>
 __device__ __forceinline__ F4 ld4(const float* p) {
-  const f4 t = ld((const f4*)p);
+  const f4 t = ld<NT>((const f4*)p);
   return F4{t.x, t.y, t.z, t.w};
 }
+template <bool NT>
 __device__ __forceinline__ void st4(float* p, const F4& a) {
   f4 t;
   t.x = a.x; t.y = a.y; t.z = a.z; t.w = a.w;
-  st((f4*)p, t);
+  st<NT>((f4*)p, t);
 }
 
 // ---- bfloat16 ---------------------------------------------------------------------------------
@@ -144,34 +173,50 @@ __global__ __launch_bounds__(kPtrBatch) void ptr_table_kernel(PtrBatch b, const 
 }
 
 // ---- shard_format / unshard_format ----------------------------------------------------------------
-// A unit is 8 elements: two 128-bit accesses of float32 or one of bfloat16.
+// A unit is what one lane moves per access: 4 elements whenever float32 is involved (one 128-bit
+// access on the float32 side, 64 bits on the bfloat16 side), 8 elements for bfloat16 -> bfloat16
+// (128 bits on both sides).  Consecutive lanes take consecutive units, so every wavefront access
+// covers one contiguous span of memory.
 
 template <int DT> struct ElemOf;
 template <> struct ElemOf<SHARD_F32> { typedef uint32_t type; };
 template <> struct ElemOf<SHARD_BF16> { typedef uint16_t type; };
 
-template <int DT>
-__device__ __forceinline__ void load8(const typename ElemOf<DT>::type* p, uint32_t (&x)[8]) {
+template <int SRC, int DST>
+struct UnitOf {
+  static constexpr int n = (SRC == SHARD_BF16 && DST == SHARD_BF16) ? 8 : 4;
+};
+
+template <typename Pol, int DT, int UNIT>
+__device__ __forceinline__ void load_unit(const typename ElemOf<DT>::type* p, uint32_t (&x)[UNIT]) {
   if constexpr (DT == SHARD_F32) {
-    const u4 a = ld((const u4*)p), b = ld((const u4*)p + 1);
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-  } else {
-    const u4 a = ld((const u4*)p);
+    static_assert(UNIT == 4, "float32 units are 4 elements");
+    const u4 a = ld<Pol::RO>((const u4*)p);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+  } else if constexpr (UNIT == 8) {
+    const u4 a = ld<Pol::RO>((const u4*)p);
     x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
     x[4] = a.z & 0xFFFFu; x[5] = a.z >> 16; x[6] = a.w & 0xFFFFu; x[7] = a.w >> 16;
+  } else {
+    const u2 a = ld<Pol::RO>((const u2*)p);
+    x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
   }
 }
-template <int DT>
-__device__ __forceinline__ void store8(typename ElemOf<DT>::type* p, const uint32_t (&x)[8]) {
+template <typename Pol, int DT, int UNIT>
+__device__ __forceinline__ void store_unit(typename ElemOf<DT>::type* p, const uint32_t (&x)[UNIT]) {
   if constexpr (DT == SHARD_F32) {
-    u4 a, b;
-    a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3]; b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
-    st((u4*)p, a);
-    st((u4*)p + 1, b);
-  } else {
+    static_assert(UNIT == 4, "float32 units are 4 elements");
+    u4 a;
+    a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
+    st<Pol::ST>((u4*)p, a);
+  } else if constexpr (UNIT == 8) {
     u4 a;
     a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16); a.z = x[4] | (x[5] << 16); a.w = x[6] | (x[7] << 16);
-    st((u4*)p, a);
+    st<Pol::ST>((u4*)p, a);
+  } else {
+    u2 a;
+    a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16);
+    st<Pol::ST>((u2*)p, a);
   }
 }
 template <int SRC, int DST>
@@ -181,90 +226,117 @@ __device__ __forceinline__ uint32_t convert(uint32_t b) {
   else return b << 16;
 }
 
-// One workgroup per chunk.  VEC: pieces and tensors are 16-byte aligned and len % 8 == 0.
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kBlock) void format_kernel(const VarDesc* __restrict__ vars,
-                                                        const ChunkDesc* __restrict__ chunks,
-                                                        const void* const* __restrict__ ptrs, void* out, int r0,
-                                                        int64_t S, int n_chunks) {
-  typedef typename ElemOf<SRC>::type SrcT;
+// Work items of the two formatting kernels are (replica, chunk, tile) triples: a chunk is cut into
+// tiles of kBlock units and every tile is one short-lived workgroup.  Many small workgroups,
+// dispatched in address order, keep the set of DRAM pages in flight compact, which measures
+// faster on MI355X than fewer workgroups that each loop over more data.  The table look-ups
+// (chunk -> variable -> pointer) of the tiles of one chunk hit the same cache lines.
+// VEC: pieces (and gathered rows) are 16-byte aligned and every chunk length is a multiple of 8;
+// whether a variable's full tensor is aligned too is tested per item.
+
+// One tile of a copy: consecutive lanes on consecutive units.
+// ALL: every unit of the tile holds real elements only; the tile moves without a branch.
+// Otherwise units that end at or before `whole` are moved whole, and (shard_format only) units
+// that start at or after `zero_from` and before `len` are written as zeros.  The one unit that
+// straddles the end of the variable, if any, is left to copy_tile's caller.
+template <int SRC, int DST, bool ALL, bool UNSHARD>
+__device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src, typename ElemOf<DST>::type* dst,
+                                           int whole, int zero_from, int len) {
+  constexpr int UNIT = UnitOf<SRC, DST>::n;
+  typedef typename std::conditional<UNSHARD, PolUnshard, PolFormat>::type Pol;
+  uint32_t x[UNIT];
+  const int e = (int)threadIdx.x * UNIT;
+  if (ALL || e + UNIT <= whole) {
+    load_unit<Pol, SRC, UNIT>(src + e, x);
+#pragma unroll
+    for (int j = 0; j < UNIT; ++j) x[j] = convert<SRC, DST>(x[j]);
+    store_unit<Pol, DST, UNIT>(dst + e, x);
+  } else if (!UNSHARD && e >= zero_from && e < len) {
+#pragma unroll
+    for (int j = 0; j < UNIT; ++j) x[j] = 0u;
+    store_unit<Pol, DST, UNIT>(dst + e, x);
+  }
+}
+
+// Moves tile `t` of a chunk.  shard_format: zero-padded piece of the flat variable -> packed shard
+// (all `len` slots written).  unshard_format: the `valid` real elements of a gathered piece -> flat
+// variable (padding dropped).  src and dst point at the chunk's first slot.
+template <int SRC, int DST, bool VEC, bool UNSHARD>
+__device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const typename ElemOf<SRC>::type* src,
+                                          typename ElemOf<DST>::type* dst) {
   typedef typename ElemOf<DST>::type DstT;
-  // blockIdx.y walks replicas for the all-replica form; r0 is the single replica otherwise
-  const int r = r0 + blockIdx.y;
-  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, r);
-  const SrcT* src = (const SrcT*)ptrs[cv.var] + cv.flat0;      // never dereferenced when valid == 0
-  DstT* dst = (DstT*)out + (int64_t)blockIdx.y * S + cv.shard0;
-  (void)n_chunks;
+  constexpr int UNIT = UnitOf<SRC, DST>::n;
+  constexpr int TILE = kBlock * UNIT;
+  const int base = t * TILE;
+  if (base >= (UNSHARD ? cv.valid : cv.len)) return;
   if constexpr (VEC) {
-    const int units = cv.len >> 3;
-    for (int u0 = threadIdx.x; u0 < units; u0 += kBlock * kUnroll) {
-      uint32_t x[kUnroll][8];
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const int e = (u0 + k * kBlock) << 3;
-        if (e + 8 <= cv.valid) {
-          load8<SRC>(src + e, x[k]);
-        } else if (e < cv.len) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[k][j] = (e + j < cv.valid) ? (uint32_t)src[e + j] : 0u;
-        }
-      }
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const int e = (u0 + k * kBlock) << 3;
-        if (e < cv.len) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[k][j] = convert<SRC, DST>(x[k][j]);
-          store8<DST>(dst + e, x[k]);
-        }
-      }
+    if (base + TILE <= cv.valid) {
+      copy_units<SRC, DST, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
+      return;
+    }
+    const int whole = cv.valid / UNIT * UNIT;                  // slots covered by fully real units
+    const int zero_from = (cv.valid + UNIT - 1) / UNIT * UNIT; // first unit that is all padding
+    copy_units<SRC, DST, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
+    // the unit that straddles the end of the variable: real elements, then (shard_format) zeros
+    if (whole != cv.valid && whole >= base && whole < base + TILE && (int)threadIdx.x < UNIT) {
+      const int e = whole + threadIdx.x;
+      if (e < cv.valid) dst[e] = (DstT)convert<SRC, DST>((uint32_t)src[e]);
+      else if (!UNSHARD) dst[e] = (DstT)0;
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock)
+    const int end = (UNSHARD ? cv.valid : cv.len) < base + TILE ? (UNSHARD ? cv.valid : cv.len) : base + TILE;
+    for (int e = base + threadIdx.x; e < end; e += kBlock)
       dst[e] = (DstT)((e < cv.valid) ? convert<SRC, DST>((uint32_t)src[e]) : 0u);
   }
 }
 
-// One workgroup per (chunk, replica): copies the real elements of gathered[r][chunk] back into
-// the flat variable and drops the padding.
+// UNSHARD = false: shard_format; `packed` is the output, shard r0 + replica goes to row `replica`.
+// UNSHARD = true : unshard_format; `packed` is the gathered buffer, r0 = 0.
+// blockIdx.x = (replica * n_chunks + chunk) * tiles_per_chunk + tile.
+template <int SRC, int DST, bool VEC, bool UNSHARD>
+__device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
+                                              const void* const* __restrict__ ptrs, void* packed, int r0,
+                                              int64_t row_stride, int n_chunks, int tiles_per_chunk) {
+  typedef typename ElemOf<SRC>::type SrcT;
+  typedef typename ElemOf<DST>::type DstT;
+  const int item = blockIdx.x / tiles_per_chunk;
+  const int tile = blockIdx.x - item * tiles_per_chunk;
+  const int replica = item / n_chunks;
+  const ChunkView cv = chunk_view(vars, chunks, item - replica * n_chunks, r0 + replica);
+  // skip the pointer look-up for tiles with nothing to do (beyond a short chunk, or all padding)
+  constexpr int TILE = kBlock * UnitOf<SRC, DST>::n;
+  if (tile * TILE >= (UNSHARD ? cv.valid : cv.len)) return;
+  const void* ptr = ptrs[cv.var];
+  // 128-bit accesses need this variable's tensor on a 16-byte boundary (VEC already says the
+  // pieces are); a tensor that is not takes the element-wise path, the others are unaffected
+  const bool vec = VEC && (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0;
+  if constexpr (UNSHARD) {
+    const SrcT* src = (const SrcT*)packed + (int64_t)replica * row_stride + cv.shard0;
+    DstT* dst = (DstT*)const_cast<void*>(ptr) + cv.flat0;
+    if (vec) copy_tile<SRC, DST, true, true>(cv, tile, src, dst);
+    else copy_tile<SRC, DST, false, true>(cv, tile, src, dst);
+  } else {
+    const SrcT* src = (const SrcT*)ptr + cv.flat0;      // not dereferenced where there is no real element
+    DstT* dst = (DstT*)packed + (int64_t)replica * row_stride + cv.shard0;
+    if (vec) copy_tile<SRC, DST, true, false>(cv, tile, src, dst);
+    else copy_tile<SRC, DST, false, false>(cv, tile, src, dst);
+  }
+}
+
+template <int SRC, int DST, bool VEC>
+__global__ __launch_bounds__(kBlock) void format_kernel(const VarDesc* __restrict__ vars,
+                                                        const ChunkDesc* __restrict__ chunks,
+                                                        const void* const* __restrict__ ptrs, void* out, int r0,
+                                                        int64_t row_stride, int n_chunks, int tiles_per_chunk) {
+  reformat_body<SRC, DST, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
+}
+
 template <int SRC, int DST, bool VEC>
 __global__ __launch_bounds__(kBlock) void unshard_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
-                                                         void* const* __restrict__ ptrs, const void* gathered,
-                                                         int64_t S) {
-  typedef typename ElemOf<SRC>::type SrcT;
-  typedef typename ElemOf<DST>::type DstT;
-  const int r = blockIdx.y;
-  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, r);
-  if (cv.valid == 0) return;
-  const SrcT* src = (const SrcT*)gathered + (int64_t)r * S + cv.shard0;
-  DstT* dst = (DstT*)ptrs[cv.var] + cv.flat0;
-  if constexpr (VEC) {
-    const int units = (cv.valid + 7) >> 3;
-    for (int u0 = threadIdx.x; u0 < units; u0 += kBlock * kUnroll) {
-      uint32_t x[kUnroll][8];
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const int e = (u0 + k * kBlock) << 3;
-        if (e < cv.valid) load8<SRC>(src + e, x[k]);          // the piece itself is always whole in the shard
-      }
-#pragma unroll
-      for (int k = 0; k < kUnroll; ++k) {
-        const int e = (u0 + k * kBlock) << 3;
-        if (e + 8 <= cv.valid) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[k][j] = convert<SRC, DST>(x[k][j]);
-          store8<DST>(dst + e, x[k]);
-        } else if (e < cv.valid) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (e + j < cv.valid) dst[e + j] = (DstT)convert<SRC, DST>(x[k][j]);
-        }
-      }
-    }
-  } else {
-    for (int e = threadIdx.x; e < cv.valid; e += kBlock) dst[e] = (DstT)convert<SRC, DST>((uint32_t)src[e]);
-  }
+                                                         const void* const* __restrict__ ptrs, void* gathered,
+                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk) {
+  reformat_body<SRC, DST, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 // ---- element-wise optimizer arithmetic ------------------------------------------------------------
@@ -297,49 +369,67 @@ __device__ __forceinline__ float lamb_dir(float w, float m, float v, float wd, c
   return fmaf(wd, w, (m * k.rbc1) * __builtin_amdgcn_rcpf(denom));
 }
 
+template <bool NT>
 __device__ __forceinline__ void store_bf16x4(uint16_t* p, const F4& w) {
   u2 o;
   o.x = bf16_of(w.x) | (bf16_of(w.y) << 16);
   o.y = bf16_of(w.z) | (bf16_of(w.w) << 16);
-  st((u2*)p, o);
+  st<NT>((u2*)p, o);
 }
 
 // ---- flat kernels: Adam and momentum ---------------------------------------------------------------
 // Padded slots are a fixed point of both updates (0 in, +0.0 out), so the packed shard is
 // processed as one flat array: no table, no masks.
 
+// One tile = kBlock * kFlatUnroll 128-bit accesses per stream.  FULL tiles (all but possibly the last)
+// run without a single branch: every load of the tile is issued before the first use.
+constexpr int kFlatTileElems = kBlock * kFlatUnroll * 4;   // float32 elements per tile and stream
+constexpr int kTileElems = kBlock * kUnroll * 4;           // the same for the LAMB kernels
+
+template <bool FULL, bool BF16>
+__device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g, float* m, float* v,
+                                          uint16_t* __restrict__ w16, int lim4, const AdamK& k) {
+  // w, g, m, v, w16 point at the tile; lim4 = 128-bit units of the tile that exist (FULL: all)
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kFlatUnroll], rg[kFlatUnroll], rm[kFlatUnroll], rv[kFlatUnroll];
+#pragma unroll
+  for (int i = 0; i < kFlatUnroll; ++i) {
+    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
+      const int o = i * kBlock * 4 + t4;
+      rg[i] = ld4<PolAdam::RO>(g + o);
+      rw[i] = ld4<PolAdam::RW>(w + o);
+      rm[i] = ld4<PolAdam::RW>(m + o);
+      rv[i] = ld4<PolAdam::RW>(v + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kFlatUnroll; ++i) {
+    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
+      const int o = i * kBlock * 4 + t4;
+      adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
+      adam_elem(rw[i].y, rg[i].y, rm[i].y, rv[i].y, k);
+      adam_elem(rw[i].z, rg[i].z, rm[i].z, rv[i].z, k);
+      adam_elem(rw[i].w, rg[i].w, rm[i].w, rv[i].w, k);
+      st4<PolAdam::ST>(w + o, rw[i]);
+      st4<PolAdam::ST>(m + o, rm[i]);
+      st4<PolAdam::ST>(v + o, rv[i]);
+      if constexpr (BF16) store_bf16x4<PolAdam::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void adam_kernel(float* w, const float* __restrict__ g, float* m, float* v,
                                                       uint16_t* __restrict__ w16, int64_t n4, int tail, AdamK k) {
-  const int64_t tile = (int64_t)kBlock * kUnroll;
-  const int64_t tiles = (n4 + tile - 1) / tile;
+  const int64_t tile4 = (int64_t)kBlock * kFlatUnroll;
+  const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t u0 = t * tile + threadIdx.x;
-    F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
-#pragma unroll
-    for (int i = 0; i < kUnroll; ++i) {
-      const int64_t u = u0 + (int64_t)i * kBlock;
-      if (u < n4) {
-        rg[i] = ld4(g + 4 * u);
-        rw[i] = ld4(w + 4 * u);
-        rm[i] = ld4(m + 4 * u);
-        rv[i] = ld4(v + 4 * u);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kUnroll; ++i) {
-      const int64_t u = u0 + (int64_t)i * kBlock;
-      if (u < n4) {
-        adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
-        adam_elem(rw[i].y, rg[i].y, rm[i].y, rv[i].y, k);
-        adam_elem(rw[i].z, rg[i].z, rm[i].z, rv[i].z, k);
-        adam_elem(rw[i].w, rg[i].w, rm[i].w, rv[i].w, k);
-        st4(w + 4 * u, rw[i]);
-        st4(m + 4 * u, rm[i]);
-        st4(v + 4 * u, rv[i]);
-        if constexpr (BF16) store_bf16x4(w16 + 4 * u, rw[i]);
-      }
-    }
+    const int64_t e0 = t * kFlatTileElems;
+    const int64_t left4 = n4 - t * tile4;
+    if (left4 >= tile4)
+      adam_tile<true, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)tile4, k);
+    else
+      adam_tile<false, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)left4, k);
   }
   if (blockIdx.x == 0 && (int)threadIdx.x < tail) {        // S % 4 leftover elements (align < 4 only)
     const int64_t e = 4 * n4 + threadIdx.x;
@@ -350,37 +440,48 @@ __global__ __launch_bounds__(kBlock) void adam_kernel(float* w, const float* __r
   }
 }
 
+template <bool FULL, bool BF16>
+__device__ __forceinline__ void momentum_tile(float* w, const float* __restrict__ g, float* m,
+                                              uint16_t* __restrict__ w16, int lim4, const MomentumK& k) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kFlatUnroll], rg[kFlatUnroll], rm[kFlatUnroll];
+#pragma unroll
+  for (int i = 0; i < kFlatUnroll; ++i) {
+    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
+      const int o = i * kBlock * 4 + t4;
+      rg[i] = ld4<PolMomentum::RO>(g + o);
+      rw[i] = ld4<PolMomentum::RW>(w + o);
+      rm[i] = ld4<PolMomentum::RW>(m + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kFlatUnroll; ++i) {
+    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
+      const int o = i * kBlock * 4 + t4;
+      momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
+      momentum_elem(rw[i].y, rg[i].y, rm[i].y, k);
+      momentum_elem(rw[i].z, rg[i].z, rm[i].z, k);
+      momentum_elem(rw[i].w, rg[i].w, rm[i].w, k);
+      st4<PolMomentum::ST>(w + o, rw[i]);
+      st4<PolMomentum::ST>(m + o, rm[i]);
+      if constexpr (BF16) store_bf16x4<PolMomentum::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float* __restrict__ g, float* m,
                                                           uint16_t* __restrict__ w16, int64_t n4, int tail,
                                                           MomentumK k) {
-  const int64_t tile = (int64_t)kBlock * kUnroll;
-  const int64_t tiles = (n4 + tile - 1) / tile;
+  const int64_t tile4 = (int64_t)kBlock * kFlatUnroll;
+  const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t u0 = t * tile + threadIdx.x;
-    F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
-#pragma unroll
-    for (int i = 0; i < kUnroll; ++i) {
-      const int64_t u = u0 + (int64_t)i * kBlock;
-      if (u < n4) {
-        rg[i] = ld4(g + 4 * u);
-        rw[i] = ld4(w + 4 * u);
-        rm[i] = ld4(m + 4 * u);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kUnroll; ++i) {
-      const int64_t u = u0 + (int64_t)i * kBlock;
-      if (u < n4) {
-        momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
-        momentum_elem(rw[i].y, rg[i].y, rm[i].y, k);
-        momentum_elem(rw[i].z, rg[i].z, rm[i].z, k);
-        momentum_elem(rw[i].w, rg[i].w, rm[i].w, k);
-        st4(w + 4 * u, rw[i]);
-        st4(m + 4 * u, rm[i]);
-        if constexpr (BF16) store_bf16x4(w16 + 4 * u, rw[i]);
-      }
-    }
+    const int64_t e0 = t * kFlatTileElems;
+    const int64_t left4 = n4 - t * tile4;
+    if (left4 >= tile4)
+      momentum_tile<true, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)tile4, k);
+    else
+      momentum_tile<false, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)left4, k);
   }
   if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
     const int64_t e = 4 * n4 + threadIdx.x;
@@ -396,55 +497,65 @@ __global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float*
 // w^2 and u^2 (Section 4.1: padded slots contribute the identity of the reduce; they are found
 // by position, not by value).
 
+// One tile of phase 1: `lim` = slots of the tile that exist, `valid` = leading slots that hold real
+// elements (may be negative or exceed the tile).  FULL tiles run without branches; the mask on the
+// sums is a select.
+template <bool FULL>
+__device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const float* __restrict__ g, float* m,
+                                             float* v, int lim, int valid, float wd, const AdamK& k, float& sw,
+                                             float& su) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rg[i] = ld4<PolLamb::RO>(g + o);
+      rw[i] = ld4<PolLamb::RO>(w + o);
+      rm[i] = ld4<PolLamb::RW>(m + o);
+      rv[i] = ld4<PolLamb::RW>(v + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      float d, wm;
+#define SU_LAMB_P1_LANE(c, j)                       \
+  lamb_moments(rg[i].c, rm[i].c, rv[i].c, k);       \
+  d = lamb_dir(rw[i].c, rm[i].c, rv[i].c, wd, k);   \
+  d = (o + j < valid) ? d : 0.0f;                   \
+  wm = (o + j < valid) ? rw[i].c : 0.0f;            \
+  sw = fmaf(wm, wm, sw);                            \
+  su = fmaf(d, d, su);
+      SU_LAMB_P1_LANE(x, 0)
+      SU_LAMB_P1_LANE(y, 1)
+      SU_LAMB_P1_LANE(z, 2)
+      SU_LAMB_P1_LANE(w, 3)
+#undef SU_LAMB_P1_LANE
+      st4<PolLamb::ST>(m + o, rm[i]);
+      st4<PolLamb::ST>(v + o, rv[i]);
+    }
+  }
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const float* __restrict__ w, const float* __restrict__ g,
                                                          float* m, float* v, float* __restrict__ chunk_sums, int r,
                                                          AdamK k) {
-  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, r);
+  const int c = SU_P1_REVERSE ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const ChunkView cv = chunk_view(vars, chunks, c, r);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
   float sw = 0.0f, su = 0.0f;
   if constexpr (VEC) {
-    const float* w4 = w + cv.shard0;
-    const float* g4 = g + cv.shard0;
-    float* m4 = m + cv.shard0;
-    float* v4 = v + cv.shard0;
-    const int units = cv.len >> 2;
-    for (int u0 = threadIdx.x; u0 < units; u0 += kBlock * kUnroll) {
-      F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
-#pragma unroll
-      for (int i = 0; i < kUnroll; ++i) {
-        const int u = u0 + i * kBlock;
-        if (u < units) {
-          rg[i] = ld4(g4 + 4 * u);
-          rw[i] = ld4(w4 + 4 * u);
-          rm[i] = ld4(m4 + 4 * u);
-          rv[i] = ld4(v4 + 4 * u);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < kUnroll; ++i) {
-        const int u = u0 + i * kBlock;
-        if (u < units) {
-          const int e = u << 2;
-          float d;
-#define SU_LAMB_P1_LANE(c, j)                                  \
-  lamb_moments(rg[i].c, rm[i].c, rv[i].c, k);                  \
-  d = lamb_dir(rw[i].c, rm[i].c, rv[i].c, wd, k);              \
-  if (e + j < cv.valid) {                                      \
-    sw = fmaf(rw[i].c, rw[i].c, sw);                           \
-    su = fmaf(d, d, su);                                       \
-  }
-          SU_LAMB_P1_LANE(x, 0)
-          SU_LAMB_P1_LANE(y, 1)
-          SU_LAMB_P1_LANE(z, 2)
-          SU_LAMB_P1_LANE(w, 3)
-#undef SU_LAMB_P1_LANE
-          st4(m4 + 4 * u, rm[i]);
-          st4(v4 + 4 * u, rv[i]);
-        }
-      }
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      if (base + kTileElems <= cv.len)
+        lamb_p1_tile<true>(w + s0, g + s0, m + s0, v + s0, kTileElems, cv.valid - base, wd, k, sw, su);
+      else
+        lamb_p1_tile<false>(w + s0, g + s0, m + s0, v + s0, cv.len - base, cv.valid - base, wd, k, sw, su);
     }
   } else {
     for (int e = threadIdx.x; e < cv.len; e += kBlock) {
@@ -452,19 +563,19 @@ __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restri
       float mm = m[s], vv = v[s];
       const float ww = w[s];
       lamb_moments(g[s], mm, vv, k);
-      const float d = lamb_dir(ww, mm, vv, wd, k);
-      if (e < cv.valid) {
-        sw = fmaf(ww, ww, sw);
-        su = fmaf(d, d, su);
-      }
+      float d = lamb_dir(ww, mm, vv, wd, k);
+      d = (e < cv.valid) ? d : 0.0f;
+      const float wm = (e < cv.valid) ? ww : 0.0f;
+      sw = fmaf(wm, wm, sw);
+      su = fmaf(d, d, su);
       m[s] = mm;
       v[s] = vv;
     }
   }
   block_sum2(sw, su);
   if (threadIdx.x == 0) {
-    chunk_sums[2 * blockIdx.x] = sw;
-    chunk_sums[2 * blockIdx.x + 1] = su;
+    chunk_sums[2 * c] = sw;
+    chunk_sums[2 * c + 1] = su;
   }
 }
 
@@ -503,13 +614,43 @@ __global__ __launch_bounds__(kBlock) void norm_reduce_kernel(const VarDesc* __re
 
 // Phase 2, one workgroup per chunk: trust ratio of the chunk's variable from the all-reduced
 // sums, then w -= lr * ratio * u with u re-created from (old w, new m, new v).
+template <bool FULL, bool BF16>
+__device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__ m, const float* __restrict__ v,
+                                             uint16_t* __restrict__ w16, int lim, float wd, float step,
+                                             const AdamK& k) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rm[kUnroll], rv[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rw[i] = ld4<PolLamb::RW>(w + o);
+      rm[i] = ld4<PolLamb::RO>(m + o);
+      rv[i] = ld4<PolLamb::RO>(v + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rw[i].x = fmaf(-step, lamb_dir(rw[i].x, rm[i].x, rv[i].x, wd, k), rw[i].x);
+      rw[i].y = fmaf(-step, lamb_dir(rw[i].y, rm[i].y, rv[i].y, wd, k), rw[i].y);
+      rw[i].z = fmaf(-step, lamb_dir(rw[i].z, rm[i].z, rv[i].z, wd, k), rw[i].z);
+      rw[i].w = fmaf(-step, lamb_dir(rw[i].w, rm[i].w, rv[i].w, wd, k), rw[i].w);
+      st4<PolLamb::ST>(w + o, rw[i]);
+      if constexpr (BF16) store_bf16x4<PolLamb::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
 template <bool VEC, bool BF16>
 __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks, float* w,
                                                          const float* __restrict__ m, const float* __restrict__ v,
                                                          uint16_t* __restrict__ w16, const float* __restrict__ sums,
                                                          AdamK k) {
-  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, 0);
+  const int c = SU_P2_REVERSE ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const ChunkView cv = chunk_view(vars, chunks, c, 0);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
   float ratio = 1.0f;
   if (!(cv.flags & SHARD_VAR_NO_ADAPT)) {
@@ -518,33 +659,12 @@ __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restri
   }
   const float step = k.lr * ratio;
   if constexpr (VEC) {
-    float* w4 = w + cv.shard0;
-    const float* m4 = m + cv.shard0;
-    const float* v4 = v + cv.shard0;
-    const int units = cv.len >> 2;
-    for (int u0 = threadIdx.x; u0 < units; u0 += kBlock * kUnroll) {
-      F4 rw[kUnroll], rm[kUnroll], rv[kUnroll];
-#pragma unroll
-      for (int i = 0; i < kUnroll; ++i) {
-        const int u = u0 + i * kBlock;
-        if (u < units) {
-          rw[i] = ld4(w4 + 4 * u);
-          rm[i] = ld4(m4 + 4 * u);
-          rv[i] = ld4(v4 + 4 * u);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < kUnroll; ++i) {
-        const int u = u0 + i * kBlock;
-        if (u < units) {
-          rw[i].x = fmaf(-step, lamb_dir(rw[i].x, rm[i].x, rv[i].x, wd, k), rw[i].x);
-          rw[i].y = fmaf(-step, lamb_dir(rw[i].y, rm[i].y, rv[i].y, wd, k), rw[i].y);
-          rw[i].z = fmaf(-step, lamb_dir(rw[i].z, rm[i].z, rv[i].z, wd, k), rw[i].z);
-          rw[i].w = fmaf(-step, lamb_dir(rw[i].w, rm[i].w, rv[i].w, wd, k), rw[i].w);
-          st4(w4 + 4 * u, rw[i]);
-          if constexpr (BF16) store_bf16x4(w16 + cv.shard0 + 4 * u, rw[i]);
-        }
-      }
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      if (base + kTileElems <= cv.len)
+        lamb_p2_tile<true, BF16>(w + s0, m + s0, v + s0, w16 + s0, kTileElems, wd, step, k);
+      else
+        lamb_p2_tile<false, BF16>(w + s0, m + s0, v + s0, w16 + s0, cv.len - base, wd, step, k);
     }
   } else {
     for (int e = threadIdx.x; e < cv.len; e += kBlock) {
@@ -558,7 +678,7 @@ __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restri
 }
 
 inline unsigned flat_grid(int64_t n4) {
-  const int64_t tile = (int64_t)kBlock * kUnroll;
+  const int64_t tile = (int64_t)kBlock * kFlatUnroll;
   int64_t tiles = (n4 + tile - 1) / tile;
   if (tiles < 1) tiles = 1;
 #if SU_GRID_CAP > 0
@@ -610,30 +730,45 @@ hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const
 }
 
 namespace {
-template <int SRC, int DST>
-void format_dispatch(shard_plan_t* p, int r, int replicas, const void* const* tab, void* out, bool vec,
-                     hipStream_t stream) {
-  const dim3 grid((unsigned)p->chunks.size(), (unsigned)replicas);
+
+template <int SRC, int DST, bool UNSHARD>
+void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
+                       bool vec, hipStream_t stream) {
+  const int n_chunks = (int)p->chunks.size();
+  constexpr int TILE = kBlock * UnitOf<SRC, DST>::n;
+  const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
+  // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31
+  const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  if (vec)
-    hipLaunchKernelGGL((format_kernel<SRC, DST, true>), grid, dim3(kBlock), 0, stream, vars, chunks, tab, out, r, p->S,
-                       (int)p->chunks.size());
-  else
-    hipLaunchKernelGGL((format_kernel<SRC, DST, false>), grid, dim3(kBlock), 0, stream, vars, chunks, tab, out, r,
-                       p->S, (int)p->chunks.size());
+  if constexpr (UNSHARD) {
+    if (vec)
+      hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride, n_chunks,
+                         tiles_per_chunk);
+    else
+      hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+                         n_chunks, tiles_per_chunk);
+  } else {
+    if (vec)
+      hipLaunchKernelGGL((format_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
+                         n_chunks, tiles_per_chunk);
+    else
+      hipLaunchKernelGGL((format_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
+                         n_chunks, tiles_per_chunk);
+  }
 }
-template <int SRC, int DST>
-void unshard_dispatch(shard_plan_t* p, const void* gathered, void* const* tab, bool vec, hipStream_t stream) {
-  const dim3 grid((unsigned)p->chunks.size(), (unsigned)p->N);
-  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
-  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  if (vec)
-    hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), grid, dim3(kBlock), 0, stream, vars, chunks, tab, gathered,
-                       p->S);
+
+template <bool UNSHARD>
+void reformat_any(shard_plan_t* p, int r0, int replicas, const void* const* tab, int src_dtype, void* packed,
+                  int64_t stride, int dst_dtype, bool vec, hipStream_t stream) {
+  if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32)
+    reformat_dispatch<SHARD_F32, SHARD_F32, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+  else if (src_dtype == SHARD_F32)
+    reformat_dispatch<SHARD_F32, SHARD_BF16, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+  else if (dst_dtype == SHARD_F32)
+    reformat_dispatch<SHARD_BF16, SHARD_F32, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
   else
-    hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), grid, dim3(kBlock), 0, stream, vars, chunks, tab, gathered,
-                       p->S);
+    reformat_dispatch<SHARD_BF16, SHARD_BF16, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
 }
 }  // namespace
 
@@ -641,21 +776,16 @@ hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src
                          bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_FORMAT, stream);
-  if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32) format_dispatch<SHARD_F32, SHARD_F32>(p, r, 1, tab, out, vec, stream);
-  else if (src_dtype == SHARD_F32) format_dispatch<SHARD_F32, SHARD_BF16>(p, r, 1, tab, out, vec, stream);
-  else if (dst_dtype == SHARD_F32) format_dispatch<SHARD_BF16, SHARD_F32>(p, r, 1, tab, out, vec, stream);
-  else format_dispatch<SHARD_BF16, SHARD_BF16>(p, r, 1, tab, out, vec, stream);
+  reformat_any<false>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, stream);
   return hipGetLastError();
 }
 
-hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int src_dtype, void* const* tab, int dst_dtype,
-                          bool vec, hipStream_t stream) {
+hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* tab,
+                          int dst_dtype, bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_UNSHARD, stream);
-  if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32) unshard_dispatch<SHARD_F32, SHARD_F32>(p, gathered, tab, vec, stream);
-  else if (src_dtype == SHARD_F32) unshard_dispatch<SHARD_F32, SHARD_BF16>(p, gathered, tab, vec, stream);
-  else if (dst_dtype == SHARD_F32) unshard_dispatch<SHARD_BF16, SHARD_F32>(p, gathered, tab, vec, stream);
-  else unshard_dispatch<SHARD_BF16, SHARD_BF16>(p, gathered, tab, vec, stream);
+  reformat_any<true>(p, 0, p->N, reinterpret_cast<const void* const*>(tab), src_dtype, const_cast<void*>(gathered),
+                     row_stride, dst_dtype, vec, stream);
   return hipGetLastError();
 }
 

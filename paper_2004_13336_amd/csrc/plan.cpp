@@ -12,7 +12,7 @@
 namespace su {
 
 namespace {
-constexpr int kDefaultChunk = 4096;
+constexpr int kDefaultChunk = 2048;   // measured best on MI355X for the formatting kernels
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 }  // namespace
@@ -63,7 +63,9 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, c
       vd.flags = p->flags[i];
       vd.reserved = 0;
       const int64_t count = (p->L[i] + chunk - 1) / chunk;
-      if ((int64_t)p->chunks.size() + count > (int64_t)std::numeric_limits<int32_t>::max() / N) return SHARD_EINVAL;
+      // the formatting kernels launch one workgroup per (replica, chunk, 1024-slot tile)
+      if (((int64_t)p->chunks.size() + count) * (chunk / 1024) > (int64_t)std::numeric_limits<int32_t>::max() / N)
+        return SHARD_EINVAL;
       vd.first_chunk = (int32_t)p->chunks.size();
       vd.n_chunks = (int32_t)count;
       for (int64_t k0 = 0; k0 < p->L[i]; k0 += chunk) {

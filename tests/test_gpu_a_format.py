@@ -104,17 +104,49 @@ def test_unshard_converting_f32_shards_to_bf16_tensors():
         assert same_bits(to_host(o), w)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unshard_reads_strided_rows(dtype):
+    """Rows of the gathered buffer may be spaced further apart than S (128-byte aligned rows)."""
+    numel, N = [1000, 37, 4099, 20011], 5
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = _bit_tensors(17, numel, dtype)
+    ref = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    for stride in (oplan.S + 8, oplan.S + 9, None):          # vector path, element-wise path, gathered_empty
+        if stride is None:
+            gathered = su.gathered_empty(plan, tdt)
+            assert gathered.data_ptr() % 128 == 0 and (gathered.stride(0) * gathered.element_size()) % 128 == 0
+        else:
+            gathered = torch.zeros((N, stride), dtype=tdt, device=DEV)[:, :oplan.S]
+        gathered.copy_(to_dev(ref))
+        outs = [torch.zeros(n, dtype=tdt, device=DEV) for n in numel]
+        su.unshard_format(plan, gathered, outs)
+        for o, f in zip(outs, flats):
+            assert same_bits(to_host(o), f)
+    # rows closer together than S are refused
+    import ctypes as C
+    arr = (C.c_void_p * len(numel))(*[o.data_ptr() for o in outs])
+    assert su.lib().unshard_format(plan.handle, C.c_void_p(gathered.data_ptr()), oplan.S - 8, 0, arr, 0, None) == -1
+    plan.free()
+
+
 def test_misaligned_full_tensors_take_the_elementwise_path():
     numel, N = [1000, 4099, 64], 4
     oplan = oracle.make_plan(numel, N, 8)
     plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
     flats = _bit_tensors(5, numel, "f32")
-    # every tensor starts 4 bytes past a 16-byte boundary
-    backing = [torch.empty(n + 1, dtype=torch.float32, device=DEV) for n in numel]
-    views = [b[1:] for b in backing]
-    for v, f in zip(views, flats):
+    _check_with_shifted_tensors(numel, N, oplan, plan, flats, shifted=(0, 1, 2))     # every tensor misaligned
+    _check_with_shifted_tensors(numel, N, oplan, plan, flats, shifted=(1,))          # only the middle one
+
+
+def _check_with_shifted_tensors(numel, N, oplan, plan, flats, shifted):
+    # a shifted tensor starts 4 bytes past a 16-byte boundary
+    backing = [torch.empty(n + 4, dtype=torch.float32, device=DEV) for n in numel]
+    views = [b[1:1 + n] if i in shifted else b[:n] for i, (b, n) in enumerate(zip(backing, numel))]
+    for i, (v, f) in enumerate(zip(views, flats)):
         v.copy_(torch.from_numpy(f))
-        assert v.data_ptr() % 16 != 0
+        assert (v.data_ptr() % 16 != 0) == (i in shifted)
     out = torch.empty(oplan.S, dtype=torch.float32, device=DEV)
     for r in range(N):
         su.shard_format(plan, r, views, out)

@@ -66,7 +66,8 @@ def test_plan_matches_oracle_on_the_benchmark_configs(cfg):
         off, length = got.segments()
         assert off == want.off and length == want.L
         # chunk count: every variable is cut into ceil(L / chunk) chunks of the default size
-        assert got.n_chunks == sum(-(-L // 4096) for L in want.L)
+        assert got.n_chunks == sum(-(-L // got.chunk_elems) for L in want.L)
+        assert got.chunk_elems in (1024, 2048, 4096, 8192, 16384)
         got.free()
 
 
@@ -82,7 +83,7 @@ def test_chunk_sizes():
     for chunk in (1024, 2048, 8192, 16384):
         p = su.shard_plan([100000, 5], 3, 8, None, chunk)
         L = make_plan([100000, 5], 3, 8).L
-        assert p.n_chunks == sum(-(-x // chunk) for x in L)
+        assert p.n_chunks == sum(-(-x // chunk) for x in L) and p.chunk_elems == chunk
         p.free()
 
 
@@ -120,7 +121,7 @@ def test_calls_that_need_a_workspace_say_so_without_touching_the_gpu():
     fake = C.c_void_p(0x1000)
     arr = (C.c_void_p * 2)(0x1000, 0x2000)
     assert lib().shard_format(p.handle, 0, arr, 0, fake, 0, None) == ESTATE
-    assert lib().unshard_format(p.handle, fake, 0, arr, 0, None) == ESTATE
+    assert lib().unshard_format(p.handle, fake, 0, 0, arr, 0, None) == ESTATE
     assert lib().shard_update_lamb(p.handle, 0, fake, fake, fake, fake, None, C.byref(hp), 1, None, None, None) == ESTATE
     # replica id is checked before anything else
     assert lib().shard_format(p.handle, 2, arr, 0, fake, 0, None) == EINVAL
