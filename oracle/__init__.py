@@ -2,7 +2,7 @@
 
 A plain, slow, numpy implementation of what the HIP library computes, written
 from the paper's description (Sections 2.2, 4.1, 5.2) and from the published
-definitions of Adam, momentum SGD and LAMB.  It shares no code with the HIP
+definitions of Adam, momentum SGD, LAMB and LARS.  It shares no code with the HIP
 path and must never be imported by it: only tests, the smoke check and the
 benchmark's cpu_baseline leg may use it.
 
@@ -19,5 +19,6 @@ from .plan import Plan, make_plan  # noqa: F401
 from .formatting import shard_format, unshard_format, f32_to_bf16_bits, bf16_bits_to_f32  # noqa: F401
 from .optim import (  # noqa: F401
     adam_step, momentum_step, lamb_unsharded_step, lamb_shard_partials, lamb_shard_apply,
+    lars_unsharded_step, lars_shard_partials, lars_shard_apply,
     VAR_NO_DECAY, VAR_NO_ADAPT,
 )

@@ -143,3 +143,66 @@ def lamb_shard_apply(plan: Plan, w, u, global_sums, hp, flags: Sequence[int] = N
         ratio = _trust_ratio(global_sums[i][0], global_sums[i][1], adapt=not (fl & VAR_NO_ADAPT))
         out[seg] = (w64[seg] - lr * ratio * u64[seg]).astype(_f32)
     return out
+
+
+# --------------------------------------------------------------------------- LARS
+# The paper's ResNet-50 runs use LARS (Section 6, Table 1), its example of an optimizer with a
+# reduce over the variable (Section 4.1).  Definition (You, Gitman & Ginsburg): per variable
+#     local_lr = trust_coeff * ||w|| / (||g|| + wd * ||w|| + eps)
+#     m <- mu * m + lr * local_lr * (g + wd * w) ;   w <- w - m
+# with local_lr = 1 when either norm is zero or the variable is flagged VAR_NO_ADAPT.
+
+def _lars_local_lr(sum_w2: float, sum_g2: float, wd: float, hp, adapt: bool) -> float:
+    if not adapt:
+        return 1.0
+    wn, gn = np.sqrt(_f64(sum_w2)), np.sqrt(_f64(sum_g2))
+    if not (wn > 0.0 and gn > 0.0):
+        return 1.0
+    return float(_f64(hp["trust_coeff"]) * wn / (gn + wd * wn + _f64(hp.get("eps", 0.0))))
+
+
+def _lars_apply(w, g, m, local_lr: float, wd: float, hp):
+    lr, mu = _f64(hp["lr"]), _f64(hp["mu"])
+    m = mu * m + lr * local_lr * (g + wd * w)
+    return w - m, m
+
+
+def lars_unsharded_step(ws: Sequence, gs: Sequence, ms: Sequence, hp, flags: Sequence[int] = None):
+    """One LARS step on whole variables.  Returns (ws', ms', sums) with sums[i] = (sum w^2, sum g^2)."""
+    out_w, out_m, sums = [], [], []
+    for i in range(len(ws)):
+        fl = 0 if flags is None else int(flags[i])
+        wd = _f64(0.0) if (fl & VAR_NO_DECAY) else _f64(hp.get("weight_decay", 0.0))
+        w, g, m = _up(ws[i], gs[i], ms[i])
+        s_w, s_g = float(np.sum(w * w)), float(np.sum(g * g))
+        w, m = _lars_apply(w, g, m, _lars_local_lr(s_w, s_g, wd, hp, not (fl & VAR_NO_ADAPT)), wd, hp)
+        out_w.append(w.astype(_f32)); out_m.append(m.astype(_f32)); sums.append((s_w, s_g))
+    return out_w, out_m, np.array(sums, dtype=_f64).reshape(len(ws), 2)
+
+
+def lars_shard_partials(plan: Plan, r: int, w, g):
+    """Phase 1 on replica r's packed shard: per-variable (sum w^2, sum g^2) over real slots only."""
+    assert 0 <= r < plan.N
+    w64, g64 = _up(w, g)
+    partial = np.zeros((plan.V, 2), _f64)
+    for i in range(plan.V):
+        seg = slice(plan.off[i], plan.off[i] + plan.L[i])
+        position = r * plan.L[i] + np.arange(plan.L[i], dtype=np.int64)
+        real = position < plan.numel[i]
+        partial[i, 0] = np.sum(np.where(real, w64[seg] * w64[seg], 0.0))
+        partial[i, 1] = np.sum(np.where(real, g64[seg] * g64[seg], 0.0))
+    return partial
+
+
+def lars_shard_apply(plan: Plan, w, g, m, global_sums, hp, flags: Sequence[int] = None):
+    """Phase 2 on a packed shard with the all-reduced sums [V, 2]; returns (w', m') float32 [S]."""
+    w64, g64, m64 = _up(w, g, m)
+    out_w = np.empty(plan.S, _f32); out_m = np.empty(plan.S, _f32)
+    for i in range(plan.V):
+        fl = 0 if flags is None else int(flags[i])
+        wd = _f64(0.0) if (fl & VAR_NO_DECAY) else _f64(hp.get("weight_decay", 0.0))
+        seg = slice(plan.off[i], plan.off[i] + plan.L[i])
+        local_lr = _lars_local_lr(global_sums[i][0], global_sums[i][1], wd, hp, not (fl & VAR_NO_ADAPT))
+        wi, mi = _lars_apply(w64[seg], g64[seg], m64[seg], local_lr, wd, hp)
+        out_w[seg] = wi.astype(_f32); out_m[seg] = mi.astype(_f32)
+    return out_w, out_m

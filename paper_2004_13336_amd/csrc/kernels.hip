@@ -29,10 +29,10 @@
 // read, 2 = non-temporal loads of streams the same thread writes back in place, 1 = non-temporal
 // stores.  The defaults are the measured best on MI355X for each access pattern.
 #ifndef SU_NT_ADAM
-#define SU_NT_ADAM 6
+#define SU_NT_ADAM 3
 #endif
 #ifndef SU_NT_MOMENTUM
-#define SU_NT_MOMENTUM 5
+#define SU_NT_MOMENTUM 3
 #endif
 #ifndef SU_NT_LAMB
 #define SU_NT_LAMB 6
