@@ -61,7 +61,7 @@ enum {
 
 enum { SHARD_F32 = 0, SHARD_BF16 = 1 };   /* element types of formatted buffers */
 
-/* Per-variable flags (LAMB only). */
+/* Per-variable flags (LAMB and LARS only). */
 enum {
   SHARD_VAR_NO_DECAY = 1u,   /* weight decay is not applied to this variable */
   SHARD_VAR_NO_ADAPT = 2u    /* the trust ratio of this variable is fixed at 1 */
@@ -71,7 +71,8 @@ enum {
 enum {
   SHARD_K_FORMAT = 0, SHARD_K_UNSHARD = 1, SHARD_K_ADAM = 2, SHARD_K_MOMENTUM = 3,
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
-  SHARD_K_COUNT = 8
+  SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9,
+  SHARD_K_COUNT = 10
 };
 
 const char* shard_strerror(int status);
@@ -131,6 +132,13 @@ void shard_plan_free(shard_plan_t* plan);
 int shard_format(shard_plan_t* plan, int r, const void* const* full_ptrs, int src_dtype,
                  void* shard_out, int dst_dtype, shard_stream_t stream);
 
+/* shard_format_all: all N pieces in one pass, row r of `out` = shard_r, rows row_stride elements
+ * apart (>= S; 0 means S): the buffer a reduce-scatter over N equal contiguous rows consumes
+ * (Section 5.1: the piece boundaries of the collective equal the sharding format and the padding
+ * is written in place while the pieces are prepared).  Reads every input element once. */
+int shard_format_all(shard_plan_t* plan, const void* const* full_ptrs, int src_dtype, void* out,
+                     int64_t row_stride, int dst_dtype, shard_stream_t stream);
+
 /* unshard_format: the reverse formatting after the all-gather (Section 4.2).  Reads the gathered
  * shards (device, src_dtype), row r = shard_r starting at element r * row_stride, and writes every
  * full variable (device pointers in the HOST array full_ptrs[V], dst_dtype), dropping the padding.
@@ -156,6 +164,7 @@ int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride,
 typedef struct { float lr, beta1, beta2, eps, weight_decay; } shard_adam_hp;
 typedef struct { float lr, mu, weight_decay; } shard_momentum_hp;
 typedef struct { float lr, beta1, beta2, eps, weight_decay; } shard_lamb_hp;
+typedef struct { float lr, mu, weight_decay, trust_coeff, eps; } shard_lars_hp;
 
 int shard_update_adam(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
                       void* w_bf16_out, const shard_adam_hp* hp, int64_t step, shard_stream_t stream);
@@ -192,6 +201,29 @@ int shard_update_lamb_apply(shard_plan_t* plan, int r, float* w, const float* m,
 int shard_update_lamb(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
                       void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
                       const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream);
+
+/* LARS, the optimizer of the paper's ResNet-50 runs (Section 6, Table 1) and its example of a
+ * reduce inside the weight update (Section 4.1); same two-phase shape as LAMB.
+ *   per variable i over ALL replicas:
+ *     local_lr_i = trust_coeff * ||w_i|| / (||g_i|| + wd_i*||w_i|| + eps)
+ *     (1 if either norm is 0 or the variable has SHARD_VAR_NO_ADAPT; wd_i = 0 with SHARD_VAR_NO_DECAY)
+ *   m = mu*m + lr*local_lr_i*(g + wd_i*w);   w -= m
+ * Tables are float32 [V][2] = {sum w^2, sum g^2} in device memory.
+ * shard_update_lars_partials reads w and g only; shard_update_lars_apply updates w and m in place
+ * from the all-reduced table; shard_update_lars does both, adding other_replicas_sumsq (may be
+ * NULL) in place of the all-reduce.  trust_coeff, lr, mu, weight_decay, eps must be finite,
+ * eps >= 0.  All need a bound plan.
+ */
+int shard_update_lars_partials(shard_plan_t* plan, int r, const float* w, const float* g,
+                               float* local_sumsq_out, shard_stream_t stream);
+
+int shard_update_lars_apply(shard_plan_t* plan, int r, float* w, const float* g, float* m,
+                            void* w_bf16_out, const shard_lars_hp* hp, const float* global_sumsq,
+                            shard_stream_t stream);
+
+int shard_update_lars(shard_plan_t* plan, int r, float* w, const float* g, float* m,
+                      void* w_bf16_out, const shard_lars_hp* hp, const float* other_replicas_sumsq,
+                      float* local_sumsq_out, shard_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events recorded on the launch stream, for benchmarks.

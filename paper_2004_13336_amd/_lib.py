@@ -34,6 +34,11 @@ class LambHP(C.Structure):
                 ("weight_decay", C.c_float)]
 
 
+class LarsHP(C.Structure):
+    _fields_ = [("lr", C.c_float), ("mu", C.c_float), ("weight_decay", C.c_float), ("trust_coeff", C.c_float),
+                ("eps", C.c_float)]
+
+
 _P = C.c_void_p
 _I64P = C.POINTER(C.c_int64)
 
@@ -54,6 +59,10 @@ SIGNATURES = {
     "shard_update_lamb_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
     "shard_update_lamb_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
     "shard_update_lamb": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P, _P]),
+    "shard_format_all": (C.c_int, [_P, C.POINTER(_P), C.c_int, _P, C.c_int64, C.c_int, _P]),
+    "shard_update_lars_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P]),
+    "shard_update_lars_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P]),
+    "shard_update_lars": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P, _P]),
     "shard_profile_enable": (C.c_int, [_P, C.c_int]),
     "shard_profile_read": (C.c_int, [_P, C.c_int, _I64P, C.POINTER(C.c_double)]),
     "shard_profile_reset": (C.c_int, [_P]),

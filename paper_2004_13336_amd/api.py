@@ -11,12 +11,12 @@ from typing import Dict, Optional, Sequence, Tuple
 
 import torch
 
-from ._lib import AdamHP, LambHP, MomentumHP, ShardError, lib
+from ._lib import AdamHP, LambHP, LarsHP, MomentumHP, ShardError, lib
 
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
-              "lamb_p2": 6, "ptr_table": 7}
+              "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -151,6 +151,29 @@ def shard_format(plan: Plan, r: int, full_tensors: Sequence[torch.Tensor], shard
     return shard_out
 
 
+def _rows(plan: Plan, t: torch.Tensor, what: str):
+    """(pointer, row stride) of an [N, S] tensor with unit stride along S, or of a flat N*S tensor."""
+    if t.dtype not in _DTYPES or not t.is_cuda:
+        raise ValueError("%s must be a float32 or bfloat16 CUDA tensor" % what)
+    if t.dim() == 2:
+        if t.shape != (plan.N, plan.S) or (plan.S > 0 and t.stride(1) != 1):
+            raise ValueError("%s must have shape [N, S] with unit stride along S" % what)
+        stride = t.stride(0) if plan.N > 1 else plan.S
+        if stride < plan.S:
+            raise ValueError("%s rows overlap" % what)
+        return C.c_void_p(t.data_ptr()), stride
+    return _dev(t, plan.N * plan.S, None, what), plan.S
+
+
+def shard_format_all(plan: Plan, full_tensors, out: torch.Tensor, stream=None):
+    """out: [N, S] (rows may be strided, e.g. from gathered_empty) or flat N*S; row r receives shard_r."""
+    arr, src = _full_ptrs(plan, full_tensors, "full_tensors")
+    ptr, stride = _rows(plan, out, "out")
+    _check(lib().shard_format_all(plan.handle, arr, _DTYPES[src], ptr, int(stride), _DTYPES[out.dtype],
+                                  _stream(stream)), "shard_format_all")
+    return out
+
+
 def gathered_empty(plan: Plan, dtype=torch.float32, device="cuda") -> torch.Tensor:
     """An uninitialised [N, S] view whose rows start on 128-byte boundaries (the layout unshard_format likes)."""
     per_line = 128 // torch.empty((), dtype=dtype).element_size()
@@ -161,18 +184,7 @@ def gathered_empty(plan: Plan, dtype=torch.float32, device="cuda") -> torch.Tens
 def unshard_format(plan: Plan, gathered: torch.Tensor, full_tensors: Sequence[torch.Tensor], stream=None):
     """gathered: [N, S] (rows may be strided, e.g. from gathered_empty) or a flat tensor of N*S elements."""
     arr, dst = _full_ptrs(plan, full_tensors, "full_tensors")
-    if gathered.dtype not in _DTYPES or not gathered.is_cuda:
-        raise ValueError("gathered must be a float32 or bfloat16 CUDA tensor")
-    if gathered.dim() == 2:
-        if gathered.shape != (plan.N, plan.S) or (plan.S > 0 and gathered.stride(1) != 1):
-            raise ValueError("gathered must have shape [N, S] with unit stride along S")
-        stride = gathered.stride(0) if plan.N > 1 else plan.S
-        if stride < plan.S:
-            raise ValueError("gathered rows overlap")
-        ptr = C.c_void_p(gathered.data_ptr())
-    else:
-        stride = plan.S
-        ptr = _dev(gathered, plan.N * plan.S, None, "gathered")
+    ptr, stride = _rows(plan, gathered, "gathered")
     _check(lib().unshard_format(plan.handle, ptr, int(stride), _DTYPES[gathered.dtype], arr, _DTYPES[dst],
                                 _stream(stream)), "unshard_format")
     return full_tensors
@@ -227,6 +239,35 @@ def shard_update_lamb(plan: Plan, r: int, w, g, m, v, hp, step: int, other_repli
                                    _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
                                    _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
                                    _stream(stream)), "shard_update_lamb")
+
+
+def shard_update_lars_partials(plan: Plan, r: int, w, g, local_sumsq_out, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lars_partials(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                            _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                            _stream(stream)), "shard_update_lars_partials")
+
+
+def shard_update_lars_apply(plan: Plan, r: int, w, g, m, hp, global_sumsq, w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lars_apply(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                         _dev(m, plan.S, f, "m"),
+                                         _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                         C.byref(_hp(LarsHP, hp)),
+                                         _dev(global_sumsq, 2 * plan.V, f, "global_sumsq"),
+                                         _stream(stream)), "shard_update_lars_apply")
+
+
+def shard_update_lars(plan: Plan, r: int, w, g, m, hp, other_replicas_sumsq=None, local_sumsq_out=None,
+                      w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_lars(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                   _dev(m, plan.S, f, "m"),
+                                   _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                   C.byref(_hp(LarsHP, hp)),
+                                   _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
+                                   _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                   _stream(stream)), "shard_update_lars")
 
 
 def shard_profile_enable(plan: Plan, on: bool) -> None:

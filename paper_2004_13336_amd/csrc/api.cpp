@@ -91,7 +91,21 @@ int check_full_ptrs(const shard_plan_t* p, const void* const* ptrs) {
 const char* const kKernelNames[SHARD_K_COUNT] = {
     "format_kernel", "unshard_kernel", "adam_kernel", "momentum_kernel",
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
+    "lars_p1_kernel", "lars_p2_kernel",
 };
+
+int fold_lars(const shard_lars_hp* hp, LarsK* k) {
+  if (hp == nullptr) return SHARD_EINVAL;
+  if (!std::isfinite(hp->lr) || !std::isfinite(hp->mu) || !std::isfinite(hp->weight_decay) ||
+      !std::isfinite(hp->trust_coeff) || !std::isfinite(hp->eps) || hp->eps < 0.0f)
+    return SHARD_EINVAL;
+  k->mu = hp->mu;
+  k->lr = hp->lr;
+  k->wd = hp->weight_decay;
+  k->trust = hp->trust_coeff;
+  k->eps = hp->eps;
+  return SHARD_OK;
+}
 
 }  // namespace
 
@@ -205,6 +219,22 @@ int shard_format(shard_plan_t* p, int r, const void* const* full_ptrs, int src_d
                                   pieces_vectorisable(p), as_stream(stream)));
 }
 
+int shard_format_all(shard_plan_t* p, const void* const* full_ptrs, int src_dtype, void* out, int64_t row_stride,
+                     int dst_dtype, shard_stream_t stream) {
+  int rc = check_plan_r(p, 0, true);
+  if (rc != SHARD_OK) return rc;
+  if (!dtype_ok(src_dtype) || !dtype_ok(dst_dtype)) return SHARD_EINVAL;
+  if (row_stride == 0) row_stride = p->S;
+  if (row_stride < p->S) return SHARD_EINVAL;
+  if ((rc = check_full_ptrs(p, full_ptrs)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(out)) != SHARD_OK) return rc;
+  const void** table = nullptr;
+  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
+  const bool vec = pieces_vectorisable(p) && row_stride % 8 == 0;
+  return hip_status(launch_format_all(p, table, src_dtype, out, row_stride, dst_dtype, vec, as_stream(stream)));
+}
+
 int unshard_format(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* full_ptrs,
                    int dst_dtype, shard_stream_t stream) {
   int rc = check_plan_r(p, 0, true);
@@ -305,6 +335,54 @@ int shard_update_lamb(shard_plan_t* p, int r, float* w, const float* g, float* m
   hipError_t e = launch_lamb_p1(p, r, w, g, m, v, k, s);
   if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
   if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
+int shard_update_lars_partials(shard_plan_t* p, int r, const float* w, const float* g, float* local_sumsq_out,
+                               shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK)) return rc;
+  hipError_t e = launch_lars_p1(p, r, w, g, as_stream(stream));
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, as_stream(stream));
+  return hip_status(e);
+}
+
+int shard_update_lars_apply(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w_bf16_out,
+                            const shard_lars_hp* hp, const float* global_sumsq, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
+      (rc = check_shard_ptr(g)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  return hip_status(launch_lars_p2(p, r, w, g, m, w_bf16_out, k, global_sumsq, as_stream(stream)));
+}
+
+int shard_update_lars(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w_bf16_out,
+                      const shard_lars_hp* hp, const float* other_replicas_sumsq, float* local_sumsq_out,
+                      shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lars_p1(p, r, w, g, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lars_p2(p, r, w, g, m, w_bf16_out, k, sums, s);
   return hip_status(e);
 }
 

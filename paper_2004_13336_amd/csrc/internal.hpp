@@ -51,6 +51,9 @@ struct AdamK {
 struct MomentumK {
   float mu, lr, wd;
 };
+struct LarsK {
+  float mu, lr, wd, trust, eps;
+};
 
 // ---- the plan --------------------------------------------------------------------------------
 
@@ -119,6 +122,12 @@ hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g
 hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_out, float* local_out,
                               hipStream_t stream);
 hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w16, const AdamK& k,
+                          const float* sums, hipStream_t stream);
+
+hipError_t launch_format_all(shard_plan_t* p, const void* const* dev_ptr_table, int src_dtype, void* out,
+                             int64_t row_stride, int dst_dtype, bool vec, hipStream_t stream);
+hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, hipStream_t stream);
+hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w16, const LarsK& k,
                           const float* sums, hipStream_t stream);
 
 // RAII helper: records an event pair around a launch when profiling is on.

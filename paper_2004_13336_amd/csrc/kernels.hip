@@ -37,6 +37,9 @@
 #ifndef SU_NT_LAMB
 #define SU_NT_LAMB 6
 #endif
+#ifndef SU_NT_LARS
+#define SU_NT_LARS 6
+#endif
 #ifndef SU_NT_FORMAT
 #define SU_NT_FORMAT 4
 #endif
@@ -75,6 +78,7 @@ struct Policy {
 typedef Policy<SU_NT_ADAM> PolAdam;
 typedef Policy<SU_NT_MOMENTUM> PolMomentum;
 typedef Policy<SU_NT_LAMB> PolLamb;
+typedef Policy<SU_NT_LARS> PolLars;
 typedef Policy<SU_NT_FORMAT> PolFormat;
 typedef Policy<SU_NT_UNSHARD> PolUnshard;
 
@@ -677,6 +681,139 @@ __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restri
   }
 }
 
+// ---- LARS ------------------------------------------------------------------------------------------
+// Phase 1 only reads: masked sums of w^2 and g^2 per chunk.  Phase 2 is the momentum update with a
+// per-variable learning-rate scale.
+
+template <bool FULL>
+__device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const float* __restrict__ g, int lim,
+                                             int valid, float& sw, float& sg) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rg[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rg[i] = ld4<PolLars::RO>(g + o);
+      rw[i] = ld4<PolLars::RO>(w + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      float a, b;
+#define SU_LARS_P1_LANE(c, j)                 \
+  a = (o + j < valid) ? rw[i].c : 0.0f;       \
+  b = (o + j < valid) ? rg[i].c : 0.0f;       \
+  sw = fmaf(a, a, sw);                        \
+  sg = fmaf(b, b, sg);
+      SU_LARS_P1_LANE(x, 0)
+      SU_LARS_P1_LANE(y, 1)
+      SU_LARS_P1_LANE(z, 2)
+      SU_LARS_P1_LANE(w, 3)
+#undef SU_LARS_P1_LANE
+    }
+  }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void lars_p1_kernel(const VarDesc* __restrict__ vars,
+                                                         const ChunkDesc* __restrict__ chunks,
+                                                         const float* __restrict__ w, const float* __restrict__ g,
+                                                         float* __restrict__ chunk_sums, int r) {
+  const int c = blockIdx.x;
+  const ChunkView cv = chunk_view(vars, chunks, c, r);
+  float sw = 0.0f, sg = 0.0f;
+  if constexpr (VEC) {
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      if (base + kTileElems <= cv.len) lars_p1_tile<true>(w + s0, g + s0, kTileElems, cv.valid - base, sw, sg);
+      else lars_p1_tile<false>(w + s0, g + s0, cv.len - base, cv.valid - base, sw, sg);
+    }
+  } else {
+    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+      const float a = (e < cv.valid) ? w[cv.shard0 + e] : 0.0f;
+      const float b = (e < cv.valid) ? g[cv.shard0 + e] : 0.0f;
+      sw = fmaf(a, a, sw);
+      sg = fmaf(b, b, sg);
+    }
+  }
+  block_sum2(sw, sg);
+  if (threadIdx.x == 0) {
+    chunk_sums[2 * c] = sw;
+    chunk_sums[2 * c + 1] = sg;
+  }
+}
+
+__device__ __forceinline__ void lars_elem(float& w, float g, float& m, float wd, float scale, float mu) {
+  g = fmaf(wd, w, g);
+  m = fmaf(mu, m, scale * g);
+  w = w - m;
+}
+
+template <bool FULL, bool BF16>
+__device__ __forceinline__ void lars_p2_tile(float* w, const float* __restrict__ g, float* m,
+                                             uint16_t* __restrict__ w16, int lim, float wd, float scale, float mu) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rg[i] = ld4<PolLars::RO>(g + o);
+      rw[i] = ld4<PolLars::RW>(w + o);
+      rm[i] = ld4<PolLars::RW>(m + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      lars_elem(rw[i].x, rg[i].x, rm[i].x, wd, scale, mu);
+      lars_elem(rw[i].y, rg[i].y, rm[i].y, wd, scale, mu);
+      lars_elem(rw[i].z, rg[i].z, rm[i].z, wd, scale, mu);
+      lars_elem(rw[i].w, rg[i].w, rm[i].w, wd, scale, mu);
+      st4<PolLars::ST>(w + o, rw[i]);
+      st4<PolLars::ST>(m + o, rm[i]);
+      if constexpr (BF16) store_bf16x4<PolLars::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
+template <bool VEC, bool BF16>
+__global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restrict__ vars,
+                                                         const ChunkDesc* __restrict__ chunks, float* w,
+                                                         const float* __restrict__ g, float* m,
+                                                         uint16_t* __restrict__ w16, const float* __restrict__ sums,
+                                                         LarsK k) {
+  const int c = (int)(gridDim.x - 1 - blockIdx.x);          // opposite direction to phase 1
+  const ChunkView cv = chunk_view(vars, chunks, c, 0);
+  const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
+  float local_lr = 1.0f;
+  if (!(cv.flags & SHARD_VAR_NO_ADAPT)) {
+    const float wn = sqrtf(sums[2 * cv.var]), gn = sqrtf(sums[2 * cv.var + 1]);
+    if (wn > 0.0f && gn > 0.0f) local_lr = k.trust * wn / (gn + wd * wn + k.eps);
+  }
+  const float scale = k.lr * local_lr;
+  if constexpr (VEC) {
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      if (base + kTileElems <= cv.len) lars_p2_tile<true, BF16>(w + s0, g + s0, m + s0, w16 + s0, kTileElems, wd, scale, k.mu);
+      else lars_p2_tile<false, BF16>(w + s0, g + s0, m + s0, w16 + s0, cv.len - base, wd, scale, k.mu);
+    }
+  } else {
+    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+      const int64_t s = cv.shard0 + e;
+      float ww = w[s], mm = m[s];
+      lars_elem(ww, g[s], mm, wd, scale, k.mu);
+      w[s] = ww;
+      m[s] = mm;
+      if constexpr (BF16) w16[s] = (uint16_t)bf16_of(ww);
+    }
+  }
+}
+
 inline unsigned flat_grid(int64_t n4) {
   const int64_t tile = (int64_t)kBlock * kFlatUnroll;
   int64_t tiles = (n4 + tile - 1) / tile;
@@ -780,6 +917,14 @@ hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src
   return hipGetLastError();
 }
 
+hipError_t launch_format_all(shard_plan_t* p, const void* const* tab, int src_dtype, void* out, int64_t row_stride,
+                             int dst_dtype, bool vec, hipStream_t stream) {
+  if (p->chunks.empty()) return hipSuccess;
+  ProfScope ps(p, SHARD_K_FORMAT, stream);
+  reformat_any<false>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, stream);
+  return hipGetLastError();
+}
+
 hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* tab,
                           int dst_dtype, bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
@@ -859,6 +1004,37 @@ hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, cons
   else if (vec) hipLaunchKernelGGL((lamb_p2_kernel<true, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
   else if (o) hipLaunchKernelGGL((lamb_p2_kernel<false, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
   else hipLaunchKernelGGL((lamb_p2_kernel<false, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
+  return hipGetLastError();
+}
+
+hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, hipStream_t stream) {
+  if (p->chunks.empty()) return hipSuccess;
+  ProfScope ps(p, SHARD_K_LARS_P1, stream);
+  const dim3 grid((unsigned)p->chunks.size());
+  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
+  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
+  float* cs = ws_at<float>(p, p->ws.chunk_sums);
+  if (p->align % 4 == 0)
+    hipLaunchKernelGGL((lars_p1_kernel<true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, cs, r);
+  else
+    hipLaunchKernelGGL((lars_p1_kernel<false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, cs, r);
+  return hipGetLastError();
+}
+
+hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w16, const LarsK& k,
+                          const float* sums, hipStream_t stream) {
+  (void)r;
+  if (p->chunks.empty()) return hipSuccess;
+  ProfScope ps(p, SHARD_K_LARS_P2, stream);
+  const dim3 grid((unsigned)p->chunks.size());
+  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
+  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
+  const bool vec = p->align % 4 == 0;
+  uint16_t* o = (uint16_t*)w16;
+  if (vec && o) hipLaunchKernelGGL((lars_p2_kernel<true, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
+  else if (vec) hipLaunchKernelGGL((lars_p2_kernel<true, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
+  else if (o) hipLaunchKernelGGL((lars_p2_kernel<false, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
+  else hipLaunchKernelGGL((lars_p2_kernel<false, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
   return hipGetLastError();
 }
 

@@ -256,3 +256,49 @@ def test_formatting_stress_1p5b_128_replicas_bf16():
     su.unshard_format(plan, gathered, outs)
     assert torch.equal(back, flat_all)
     plan.free()
+
+
+@pytest.mark.parametrize("numel,N,align", [([1000, 37, 0, 8, 4099, 1], 3, 8), ([64, 64, 9000], 32, 8), ([100, 33, 7], 4, 1),
+                                          ([2, 1024, 30522, 513], 8, 8)])
+@pytest.mark.parametrize("src,dst", [("f32", "f32"), ("f32", "bf16"), ("bf16", "bf16")])
+def test_format_all_replicas_in_one_pass(numel, N, align, src, dst):
+    """Row r of the output is shard_r, for all r at once (the reduce-scatter input layout)."""
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+    flats = _bit_tensors(23, numel, src)
+    dev_full = [to_dev(f) for f in flats]
+    tdt = torch.float32 if dst == "f32" else torch.bfloat16
+    esz = 4 if dst == "f32" else 2
+    ref = np.stack([oracle.shard_format(oplan, r, flats, dst=dst) for r in range(N)])
+    # back-to-back rows, with canaries around the whole buffer
+    buf, payload, band = _guarded(N * oplan.S * esz)
+    out = payload.view(tdt).view(N, oplan.S)
+    su.shard_format_all(plan, dev_full, out)
+    torch.cuda.synchronize()
+    assert _bands_intact(buf, band, N * oplan.S * esz)
+    assert same_bits(to_host(out), ref)
+    # strided rows: the slots between S and the stride keep their contents
+    stride = oplan.S + 24
+    wide = torch.full((N, stride), 3.0, dtype=tdt, device=DEV)
+    su.shard_format_all(plan, dev_full, wide[:, :oplan.S])
+    assert same_bits(to_host(wide[:, :oplan.S].contiguous()), ref)
+    assert bool((wide[:, oplan.S:] == 3.0).all())
+    plan.free()
+
+
+def test_format_all_full_size_transformer():
+    cfg = [c for c in CONFIGS if c.name == "transformer_big"][0]
+    N = 16
+    oplan = oracle.make_plan(cfg.numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8))
+    flats = _bit_tensors(cfg.seed, cfg.numel, "f32")
+    dev_full = su.FullTensors(plan, [to_dev(f) for f in flats])
+    out = su.gathered_empty(plan)
+    su.shard_format_all(plan, dev_full, out)
+    for r in (0, 7, 15):
+        assert same_bits(to_host(out[r]), oracle.shard_format(oplan, r, flats)), r
+    back = [torch.empty(n, dtype=torch.float32, device=DEV) for n in cfg.numel]
+    su.unshard_format(plan, out, back)
+    for o, f in zip(back, flats):
+        assert same_bits(to_host(o), f)
+    plan.free()

@@ -389,3 +389,87 @@ def test_mixed_precision_adam_1p5b_sampled_variables(N):
     assert torch.equal(W16.view(torch.int16), W.to(torch.bfloat16).view(torch.int16))
     assert bool(torch.isfinite(W).all())
     plan.free()
+
+
+# --------------------------------------------------------------------------------------- LARS
+
+LARS = f32_hp({"lr": 0.1, "mu": 0.9, "weight_decay": 5e-5, "trust_coeff": 0.001, "eps": 0.0})
+
+
+def _lars_all_replicas(plan, oplan, W, G, M, hp, W16=None):
+    N, nv = oplan.N, oplan.V
+    local = torch.zeros((N, ((nv * 2 + 3) // 4) * 4), dtype=torch.float32, device=DEV)
+    for r in range(N):
+        su.shard_update_lars_partials(plan, r, W[r], G[r], local[r])
+    local = local[:, :nv * 2].reshape(N, nv, 2).contiguous()
+    total = local.sum(dim=0)
+    for r in range(N):
+        su.shard_update_lars_apply(plan, r, W[r], G[r], M[r], hp, total, w_bf16_out=None if W16 is None else W16[r])
+    return local, total
+
+
+@pytest.mark.parametrize("case", ["ragged", "ragged_align1", "resnet50_N32", "resnet50_N1"])
+def test_lars_all_replicas_against_unsharded_oracle(case):
+    """The paper's ResNet-50 optimizer on the ResNet-50-shaped variable list (config 2) and on ragged lists."""
+    if case.startswith("resnet50"):
+        cfg = _cfg("resnet50"); numel, seed, align = cfg.numel, cfg.seed, 8
+        N = 32 if case.endswith("N32") else 1
+        flags = [0 if len(s) == 4 or len(s) == 2 else (su.SHARD_VAR_NO_DECAY | su.SHARD_VAR_NO_ADAPT) for s in cfg.shapes]
+        steps = 2
+    else:
+        numel, N, seed = RAGGED, 6, 97
+        align = 8 if case == "ragged" else 1
+        flags = [0] * len(numel); flags[2] = su.SHARD_VAR_NO_DECAY; flags[-1] = su.SHARD_VAR_NO_ADAPT
+        steps = 3
+    print("lars", case, flush=True)
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align, flags))
+    ws, _ = gen_weights_grads(seed, numel, 0.02, 1e-3)
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]
+    W = dev_rows(shards_of(oplan, ws)); M = zeros_like_rows(W)
+    W16 = zeros_like_rows(W, torch.bfloat16)
+    for t in range(1, steps + 1):
+        gs = [normal_f32(seed, i, "g", n, 1e-3, t) for i, n in enumerate(numel)]
+        G = dev_rows(shards_of(oplan, gs))
+        uw, um, usums = oracle.lars_unsharded_step(uw, gs, um, LARS, flags)
+        local, total = _lars_all_replicas(plan, oplan, W, G, M, LARS, W16)
+        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        Wh, Mh = host_rows(W), host_rows(M)
+        for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, Wh))):
+            assert_weights_close(b, a, "w var %d t=%d" % (i, t))
+        for a, b in zip(um, oracle.unshard_format(oplan, Mh)):
+            # m = mu m + lr*local_lr*(g + wd w): magnitudes of lr*g for unadapted variables
+            assert_first_moment_close(b, a, LARS["lr"] * 1e-3, 10 * t)
+        for r in range(N):
+            assert pads_are_zero(oplan, r, Wh[r]) and pads_are_zero(oplan, r, Mh[r])
+            assert same_bits(to_host(W16[r]), oracle.f32_to_bf16_bits(Wh[r]))
+    plan.free()
+
+
+def test_lars_fused_call_and_partials():
+    numel, N = [10, 3, 4100, 64, 20011], 4
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    ws, gs = gen_weights_grads(31, numel, 0.02, 1e-3)
+    W_ref = shards_of(oplan, ws); G_ref = shards_of(oplan, gs)
+    W = dev_rows(W_ref); G = dev_rows(G_ref); M = zeros_like_rows(W)
+    # partial sums against the oracle's, with garbage in the padded slots of the inputs
+    for r in range(N):
+        want = oracle.lars_shard_partials(oplan, r, W_ref[r], G_ref[r])
+        Wd, Gd = W_ref[r].copy(), G_ref[r].copy()
+        for i in range(oplan.V):
+            real = oplan.real_count(i, r)
+            Wd[oplan.off[i] + real: oplan.off[i] + oplan.L[i]] = 5.0
+            Gd[oplan.off[i] + real: oplan.off[i] + oplan.L[i]] = -3.0
+        out = torch.full((oplan.V, 2), -1.0, dtype=torch.float32, device=DEV)
+        su.shard_update_lars_partials(plan, r, to_dev(Wd), to_dev(Gd), out)
+        np.testing.assert_allclose(to_host(out).astype(np.float64), want, rtol=3e-6, atol=1e-30)
+    local, total = _lars_all_replicas(plan, oplan, W, G, M, LARS)
+    Wf = dev_rows(W_ref); Mf = zeros_like_rows(Wf)
+    for r in range(N):
+        mine = torch.zeros((oplan.V, 2), dtype=torch.float32, device=DEV)
+        su.shard_update_lars(plan, r, Wf[r], G[r], Mf[r], LARS, other_replicas_sumsq=total - local[r],
+                             local_sumsq_out=mine)
+        assert torch.equal(mine, local[r])
+        assert float((Wf[r] - W[r]).abs().max()) <= 1e-9
+    plan.free()
