@@ -270,6 +270,10 @@ def table(args, torch, su, cfgs, path):
             elif cfg.optimizer == "momentum":
                 stages.append(("momentum", lambda t: su.shard_update_momentum(plan, r, wb.w, wb.g, wb.m, hp),
                                ["momentum"], 20 * S))
+                lars_hp = dict(hp, trust_coeff=0.001, eps=0.0)     # the paper's optimizer for this model
+                stages.append(("lars", lambda t: su.shard_update_lars(plan, r, wb.w, wb.g, wb.m, lars_hp,
+                                                                      other_replicas_sumsq=wb.other),
+                               ["lars_p1", "norm_reduce", "lars_p2"], 28 * S))
             else:
                 stages.append(("lamb", lambda t: su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, hp, t,
                                                                       other_replicas_sumsq=wb.other),
@@ -278,6 +282,8 @@ def table(args, torch, su, cfgs, path):
                 stages.append(("shard_format", lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S))
                 stages.append(("unshard_format", lambda t: su.unshard_format(plan, wb.gathered, wb.full_w),
                                ["unshard"], 4 * N * S + 4 * cfg.total))
+                stages.append(("shard_format_all", lambda t: su.shard_format_all(plan, wb.full_g, wb.gathered),
+                               ["format"], 4 * N * S + 4 * cfg.total))
             for name, fn, kernels, nbytes in stages:
                 for t in range(1, 6):
                     fn(t)

@@ -43,6 +43,9 @@
 #ifndef SU_NT_FORMAT
 #define SU_NT_FORMAT 4
 #endif
+#ifndef SU_NT_FORMAT_ALL
+#define SU_NT_FORMAT_ALL 5    // all-replica formatting: the output goes to a collective, not to the next kernel
+#endif
 #ifndef SU_NT_UNSHARD
 #define SU_NT_UNSHARD 5
 #endif
@@ -81,6 +84,7 @@ typedef Policy<SU_NT_LAMB> PolLamb;
 typedef Policy<SU_NT_LARS> PolLars;
 typedef Policy<SU_NT_FORMAT> PolFormat;
 typedef Policy<SU_NT_UNSHARD> PolUnshard;
+typedef Policy<SU_NT_FORMAT_ALL> PolFormatAll;
 
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T* p) {
@@ -243,11 +247,10 @@ __device__ __forceinline__ uint32_t convert(uint32_t b) {
 // Otherwise units that end at or before `whole` are moved whole, and (shard_format only) units
 // that start at or after `zero_from` and before `len` are written as zeros.  The one unit that
 // straddles the end of the variable, if any, is left to copy_tile's caller.
-template <int SRC, int DST, bool ALL, bool UNSHARD>
+template <typename Pol, int SRC, int DST, bool ALL, bool UNSHARD>
 __device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src, typename ElemOf<DST>::type* dst,
                                            int whole, int zero_from, int len) {
   constexpr int UNIT = UnitOf<SRC, DST>::n;
-  typedef typename std::conditional<UNSHARD, PolUnshard, PolFormat>::type Pol;
   uint32_t x[UNIT];
   const int e = (int)threadIdx.x * UNIT;
   if (ALL || e + UNIT <= whole) {
@@ -265,7 +268,7 @@ __device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src
 // Moves tile `t` of a chunk.  shard_format: zero-padded piece of the flat variable -> packed shard
 // (all `len` slots written).  unshard_format: the `valid` real elements of a gathered piece -> flat
 // variable (padding dropped).  src and dst point at the chunk's first slot.
-template <int SRC, int DST, bool VEC, bool UNSHARD>
+template <typename Pol, int SRC, int DST, bool VEC, bool UNSHARD>
 __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const typename ElemOf<SRC>::type* src,
                                           typename ElemOf<DST>::type* dst) {
   typedef typename ElemOf<DST>::type DstT;
@@ -275,12 +278,12 @@ __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const type
   if (base >= (UNSHARD ? cv.valid : cv.len)) return;
   if constexpr (VEC) {
     if (base + TILE <= cv.valid) {
-      copy_units<SRC, DST, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
+      copy_units<Pol, SRC, DST, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
       return;
     }
     const int whole = cv.valid / UNIT * UNIT;                  // slots covered by fully real units
     const int zero_from = (cv.valid + UNIT - 1) / UNIT * UNIT; // first unit that is all padding
-    copy_units<SRC, DST, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
+    copy_units<Pol, SRC, DST, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
     // the unit that straddles the end of the variable: real elements, then (shard_format) zeros
     if (whole != cv.valid && whole >= base && whole < base + TILE && (int)threadIdx.x < UNIT) {
       const int e = whole + threadIdx.x;
@@ -297,7 +300,7 @@ __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const type
 // UNSHARD = false: shard_format; `packed` is the output, shard r0 + replica goes to row `replica`.
 // UNSHARD = true : unshard_format; `packed` is the gathered buffer, r0 = 0.
 // blockIdx.x = (replica * n_chunks + chunk) * tiles_per_chunk + tile.
-template <int SRC, int DST, bool VEC, bool UNSHARD>
+template <typename Pol, int SRC, int DST, bool VEC, bool UNSHARD>
 __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
                                               const void* const* __restrict__ ptrs, void* packed, int r0,
                                               int64_t row_stride, int n_chunks, int tiles_per_chunk) {
@@ -317,13 +320,13 @@ __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, 
   if constexpr (UNSHARD) {
     const SrcT* src = (const SrcT*)packed + (int64_t)replica * row_stride + cv.shard0;
     DstT* dst = (DstT*)const_cast<void*>(ptr) + cv.flat0;
-    if (vec) copy_tile<SRC, DST, true, true>(cv, tile, src, dst);
-    else copy_tile<SRC, DST, false, true>(cv, tile, src, dst);
+    if (vec) copy_tile<Pol, SRC, DST, true, true>(cv, tile, src, dst);
+    else copy_tile<Pol, SRC, DST, false, true>(cv, tile, src, dst);
   } else {
     const SrcT* src = (const SrcT*)ptr + cv.flat0;      // not dereferenced where there is no real element
     DstT* dst = (DstT*)packed + (int64_t)replica * row_stride + cv.shard0;
-    if (vec) copy_tile<SRC, DST, true, false>(cv, tile, src, dst);
-    else copy_tile<SRC, DST, false, false>(cv, tile, src, dst);
+    if (vec) copy_tile<Pol, SRC, DST, true, false>(cv, tile, src, dst);
+    else copy_tile<Pol, SRC, DST, false, false>(cv, tile, src, dst);
   }
 }
 
@@ -332,7 +335,15 @@ __global__ __launch_bounds__(kBlock) void format_kernel(const VarDesc* __restric
                                                         const ChunkDesc* __restrict__ chunks,
                                                         const void* const* __restrict__ ptrs, void* out, int r0,
                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<SRC, DST, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
+  reformat_body<PolFormat, SRC, DST, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
+}
+
+template <int SRC, int DST, bool VEC>
+__global__ __launch_bounds__(kBlock) void format_all_kernel(const VarDesc* __restrict__ vars,
+                                                            const ChunkDesc* __restrict__ chunks,
+                                                            const void* const* __restrict__ ptrs, void* out,
+                                                            int64_t row_stride, int n_chunks, int tiles_per_chunk) {
+  reformat_body<PolFormatAll, SRC, DST, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -340,7 +351,7 @@ __global__ __launch_bounds__(kBlock) void unshard_kernel(const VarDesc* __restri
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const void* const* __restrict__ ptrs, void* gathered,
                                                          int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<SRC, DST, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
+  reformat_body<PolUnshard, SRC, DST, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 // ---- element-wise optimizer arithmetic ------------------------------------------------------------
@@ -868,7 +879,8 @@ hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const
 
 namespace {
 
-template <int SRC, int DST, bool UNSHARD>
+// MODE: 0 = shard_format (one replica), 1 = unshard_format, 2 = shard_format_all
+template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
                        bool vec, hipStream_t stream) {
   const int n_chunks = (int)p->chunks.size();
@@ -878,7 +890,14 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  if constexpr (UNSHARD) {
+  if constexpr (MODE == 2) {
+    if (vec)
+      hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+                         n_chunks, tiles_per_chunk);
+    else
+      hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+                         n_chunks, tiles_per_chunk);
+  } else if constexpr (MODE == 1) {
     if (vec)
       hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride, n_chunks,
                          tiles_per_chunk);
@@ -895,17 +914,17 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   }
 }
 
-template <bool UNSHARD>
+template <int MODE>
 void reformat_any(shard_plan_t* p, int r0, int replicas, const void* const* tab, int src_dtype, void* packed,
                   int64_t stride, int dst_dtype, bool vec, hipStream_t stream) {
   if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_F32, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_F32, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
   else if (src_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_BF16, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_F32, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
   else if (dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_BF16, SHARD_F32, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_BF16, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
   else
-    reformat_dispatch<SHARD_BF16, SHARD_BF16, UNSHARD>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_BF16, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
 }
 }  // namespace
 
@@ -913,7 +932,7 @@ hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src
                          bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<false>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, stream);
+  reformat_any<0>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, stream);
   return hipGetLastError();
 }
 
@@ -921,7 +940,7 @@ hipError_t launch_format_all(shard_plan_t* p, const void* const* tab, int src_dt
                              int dst_dtype, bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<false>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, stream);
+  reformat_any<2>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, stream);
   return hipGetLastError();
 }
 
@@ -929,7 +948,7 @@ hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_str
                           int dst_dtype, bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_UNSHARD, stream);
-  reformat_any<true>(p, 0, p->N, reinterpret_cast<const void* const*>(tab), src_dtype, const_cast<void*>(gathered),
+  reformat_any<1>(p, 0, p->N, reinterpret_cast<const void* const*>(tab), src_dtype, const_cast<void*>(gathered),
                      row_stride, dst_dtype, vec, stream);
   return hipGetLastError();
 }
