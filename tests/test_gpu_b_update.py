@@ -473,3 +473,60 @@ def test_lars_fused_call_and_partials():
         assert torch.equal(mine, local[r])
         assert float((Wf[r] - W[r]).abs().max()) <= 1e-9
     plan.free()
+
+
+# ------------------------------------------------------------------------- beyond 2^31 elements
+
+def test_shard_longer_than_2_31_slots():
+    """One variable of 2^31 + 2^20 + 8 elements on a single replica: every 32-bit index would wrap.
+    Formatting, LAMB (chunk table with more than a million chunks) and Adam are checked on windows at
+    the start, across the 2^31 boundary and at the ragged end, against the oracle run on those windows
+    (the updates are element-wise; LAMB's sums come from torch's float64 reduction of the same data)."""
+    n = (1 << 31) + (1 << 20) + 8 + 3            # not a multiple of 8: the last piece ends in padding
+    print("2^31 test, n =", n, flush=True)
+    plan = su.shard_plan_bind(su.shard_plan([n], 1, 8))
+    S = plan.S
+    assert S == n + 5 and plan.n_chunks > (1 << 20)
+    gen = torch.Generator(device=DEV); gen.manual_seed(4242)
+    full = torch.empty(n, dtype=torch.float32, device=DEV).normal_(0.0, 0.02, generator=gen)
+    W = torch.empty(S, dtype=torch.float32, device=DEV)
+    su.shard_format(plan, 0, [full], W)
+    windows = [(0, 4096), ((1 << 31) - 2048, 4096), (n - 4096 - 3, 4096 + 3)]
+    for a, ln in windows:
+        assert torch.equal(W[a:a + ln], full[a:a + ln])
+    assert not bool(W[n:].view(torch.int32).any())                   # +0.0 padding
+    back = torch.zeros(n, dtype=torch.float32, device=DEV)
+    su.unshard_format(plan, W, [back])
+    assert torch.equal(back, full)
+    del back
+    G = torch.empty(S, dtype=torch.float32, device=DEV).normal_(0.0, 1e-3, generator=gen)
+    G[n:] = 0
+    M = torch.zeros(S, dtype=torch.float32, device=DEV); V = torch.zeros(S, dtype=torch.float32, device=DEV)
+    w0 = {a: to_host(W[a:a + ln]) for a, ln in windows}
+    g0 = {a: to_host(G[a:a + ln]) for a, ln in windows}
+    # LAMB, single replica: sums against a float64 reduction, windows against the oracle's apply
+    sums = torch.zeros((1, 2), dtype=torch.float32, device=DEV)
+    su.shard_update_lamb_partials(plan, 0, W, G, M, V, LAMB, 1, sums)
+    sw_ref = float((full.double() ** 2).sum())
+    assert abs(float(sums[0, 0]) / sw_ref - 1.0) < 3e-6
+    su.shard_update_lamb_apply(plan, 0, W, M, V, LAMB, 1, sums)
+    gs = to_host(sums).astype(np.float64)
+    for a, ln in windows:
+        op = oracle.make_plan([ln], 1, 1)
+        z = np.zeros(ln, np.float32)
+        m1, v1, u1, _ = oracle.lamb_shard_partials(op, 0, w0[a], g0[a], z, z, LAMB, 1)
+        w1 = oracle.lamb_shard_apply(op, w0[a], u1, gs, LAMB)
+        assert_weights_close(to_host(W[a:a + ln]), w1, "lamb window %d" % a)
+        assert_first_moment_close(to_host(M[a:a + ln]), m1, 1e-3)
+        assert_second_moment_close(to_host(V[a:a + ln]), v1)
+    # Adam on top, step 1 from fresh moments
+    M.zero_(); V.zero_()
+    w0 = {a: to_host(W[a:a + ln]) for a, ln in windows}
+    su.shard_update_adam(plan, 0, W, G, M, V, ADAM, 1)
+    for a, ln in windows:
+        z = np.zeros(ln, np.float32)
+        w1, m1, v1 = oracle.adam_step(w0[a], g0[a], z, z, ADAM, 1)
+        assert_weights_close(to_host(W[a:a + ln]), w1, "adam window %d" % a)
+        assert_first_moment_close(to_host(M[a:a + ln]), m1, 1e-3)
+    assert not bool(W[n:].view(torch.int32).any()) and not bool(M[n:].view(torch.int32).any())
+    plan.free()
