@@ -15,7 +15,7 @@ Every function here is pinned by tests/test_oracle_*.py against the paper's
 worked shape examples, closed forms, brute force on tiny inputs and library
 routines; no function is "parity unpinned".
 """
-from .plan import Plan, make_plan  # noqa: F401
+from .plan import Plan, make_plan, make_row_plan  # noqa: F401
 from .formatting import shard_format, unshard_format, f32_to_bf16_bits, bf16_bits_to_f32  # noqa: F401
 from .optim import (  # noqa: F401
     adam_step, momentum_step, lamb_unsharded_step, lamb_shard_partials, lamb_shard_apply,

@@ -52,7 +52,7 @@ def shard_format(plan: Plan, r: int, flats: Sequence[np.ndarray], dst: str = Non
     out = np.zeros(plan.S, dtype=np.uint16 if dst == "bf16" else np.uint32)   # all-zero bits == +0.0
     for i, flat in enumerate(flats):
         assert flat.ndim == 1 and flat.size == plan.numel[i]
-        start = r * plan.L[i]
+        start = r * plan.stride[i]
         real = plan.real_count(i, r)
         if real > 0:
             piece = _convert(flat[start:start + real], dst)
@@ -70,7 +70,7 @@ def unshard_format(plan: Plan, gathered: np.ndarray, dst: str = None) -> List[np
     for i in range(plan.V):
         flat = np.empty(plan.numel[i], dtype=np.uint16 if dst == "bf16" else np.float32)
         for r in range(plan.N):
-            start = r * plan.L[i]
+            start = r * plan.stride[i]
             real = plan.real_count(i, r)
             if real > 0:
                 flat[start:start + real] = _convert(gathered[r, plan.off[i]:plan.off[i] + real], dst)

@@ -123,8 +123,9 @@ def lamb_shard_partials(plan: Plan, r: int, w, g, m, v, hp, t: int, flags: Seque
         seg = slice(plan.off[i], plan.off[i] + plan.L[i])
         mi, vi, ui = _lamb_direction(w64[seg], g64[seg], m64[seg], v64[seg], hp, t,
                                      decay=not (fl & VAR_NO_DECAY))
-        position = r * plan.L[i] + np.arange(plan.L[i], dtype=np.int64)
-        real = position < plan.numel[i]
+        slot = np.arange(plan.L[i], dtype=np.int64)
+        position = r * plan.stride[i] + slot            # place in the full variable: replica offset + index
+        real = (slot < plan.stride[i]) & (position < plan.numel[i])
         partial[i, 0] = np.sum(np.where(real, w64[seg] * w64[seg], 0.0))
         partial[i, 1] = np.sum(np.where(real, ui * ui, 0.0))
         m_out[seg] = mi.astype(_f32); v_out[seg] = vi.astype(_f32); u_out[seg] = ui
@@ -187,8 +188,9 @@ def lars_shard_partials(plan: Plan, r: int, w, g):
     partial = np.zeros((plan.V, 2), _f64)
     for i in range(plan.V):
         seg = slice(plan.off[i], plan.off[i] + plan.L[i])
-        position = r * plan.L[i] + np.arange(plan.L[i], dtype=np.int64)
-        real = position < plan.numel[i]
+        slot = np.arange(plan.L[i], dtype=np.int64)
+        position = r * plan.stride[i] + slot            # place in the full variable: replica offset + index
+        real = (slot < plan.stride[i]) & (position < plan.numel[i])
         partial[i, 0] = np.sum(np.where(real, w64[seg] * w64[seg], 0.0))
         partial[i, 1] = np.sum(np.where(real, g64[seg] * g64[seg], 0.0))
     return partial

@@ -205,7 +205,7 @@ def test_plan_mutants_are_caught(monkeypatch, kind):
             if kind == "pad_up_front":
                 length += align
             L.append(length); off.append(0 if kind == "offsets_not_cumulative" else pos); pos += length
-        return pln.Plan(tuple(int(n) for n in numel), int(N), int(align), tuple(L), tuple(off), pos)
+        return pln.Plan(tuple(int(n) for n in numel), int(N), int(align), tuple(L), tuple(off), pos, tuple(L))
     monkeypatch.setattr(tp, "make_plan", make_plan)
     assert _fails(PLAN_PINS)
 
