@@ -95,6 +95,19 @@ const char* shard_kernel_name(int kernel_id);   /* NULL if out of range */
 int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32_t* var_flags,
                int chunk_elems, shard_plan_t** out);
 
+/* shard_plan_rows: the paper's own format (Section 4.1): variable i is a row-major rows_i x cols_i
+ * matrix (leading dimensions combined into rows, trailing ones into cols; e.g. [3,3,256,256] as
+ * 9 x 65536); the row dimension is padded to a multiple of N and replica r owns the whole rows
+ * [r*Lr_i, (r+1)*Lr_i), Lr_i = ceil(rows_i / N).  No reshape merges a row with a column, so
+ * reductions along either survive sharding (Section 4.1, "Non-elementwise operators").
+ *     L_i = roundup(Lr_i * cols_i, align);  shard_r[off_i + k] = (k < Lr_i*cols_i and
+ *     r*Lr_i*cols_i + k < rows_i*cols_i) ? var_i[r*Lr_i*cols_i + k] : +0.0
+ * Everything else (formatting, updates, unshard) works on such a plan unchanged.  Pieces whose
+ * start in the full tensor is not 16-byte aligned are moved element by element.
+ * rows, cols: host arrays [V], >= 0.  Other arguments and errors as shard_plan. */
+int shard_plan_rows(int V, const int64_t* rows, const int64_t* cols, int N, int align_elems,
+                    const uint32_t* var_flags, int chunk_elems, shard_plan_t** out);
+
 /* Sizes of a plan.  Any out pointer may be NULL.
  *   S                packed shard length in elements
  *   total            sum of n_i

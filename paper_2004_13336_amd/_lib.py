@@ -47,6 +47,7 @@ SIGNATURES = {
     "shard_strerror": (C.c_char_p, [C.c_int]),
     "shard_kernel_name": (C.c_char_p, [C.c_int]),
     "shard_plan": (C.c_int, [C.c_int, _I64P, C.c_int, C.c_int, C.POINTER(C.c_uint32), C.c_int, C.POINTER(_P)]),
+    "shard_plan_rows": (C.c_int, [C.c_int, _I64P, _I64P, C.c_int, C.c_int, C.POINTER(C.c_uint32), C.c_int, C.POINTER(_P)]),
     "shard_plan_info": (C.c_int, [_P, _I64P, _I64P, _I64P, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]),
     "shard_plan_segments": (C.c_int, [_P, _I64P, _I64P]),
     "shard_plan_real_count": (C.c_int, [_P, C.c_int, _I64P]),

@@ -49,7 +49,8 @@ class Plan:
     """Owner of a shard_plan_t handle (and of the workspace tensor, if it allocated one)."""
 
     def __init__(self, numel: Sequence[int], N: int, align_elems: int = 8,
-                 var_flags: Optional[Sequence[int]] = None, chunk_elems: int = 0):
+                 var_flags: Optional[Sequence[int]] = None, chunk_elems: int = 0, cols: Optional[Sequence[int]] = None):
+        """Flat plan over numel[i] elements, or, with cols, a row plan over numel[i] x cols[i] matrices."""
         V = len(numel)
         arr = (C.c_int64 * max(V, 1))(*[int(n) for n in numel])
         flags = None
@@ -58,11 +59,19 @@ class Plan:
                 raise ValueError("var_flags must have one entry per variable")
             flags = (C.c_uint32 * max(V, 1))(*[int(f) for f in var_flags])
         handle = C.c_void_p()
-        _check(lib().shard_plan(V, arr, int(N), int(align_elems), flags, int(chunk_elems), C.byref(handle)),
-               "shard_plan")
+        if cols is None:
+            _check(lib().shard_plan(V, arr, int(N), int(align_elems), flags, int(chunk_elems), C.byref(handle)),
+                   "shard_plan")
+            self.numel = tuple(int(n) for n in numel)
+        else:
+            if len(cols) != V:
+                raise ValueError("cols must have one entry per variable")
+            carr = (C.c_int64 * max(V, 1))(*[int(c) for c in cols])
+            _check(lib().shard_plan_rows(V, arr, carr, int(N), int(align_elems), flags, int(chunk_elems),
+                                         C.byref(handle)), "shard_plan_rows")
+            self.numel = tuple(int(n) * int(c) for n, c in zip(numel, cols))
         self.handle = handle
         self.V, self.N, self.align = V, int(N), int(align_elems)
-        self.numel = tuple(int(n) for n in numel)
         S, total, nch, chunk, wsb = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int(), C.c_size_t()
         _check(lib().shard_plan_info(handle, C.byref(S), C.byref(total), C.byref(nch), C.byref(chunk), C.byref(wsb)),
                "shard_plan_info")
@@ -96,6 +105,10 @@ class Plan:
 
 def shard_plan(numel, N, align_elems=8, var_flags=None, chunk_elems=0) -> Plan:
     return Plan(numel, N, align_elems, var_flags, chunk_elems)
+
+
+def shard_plan_rows(rows, cols, N, align_elems=8, var_flags=None, chunk_elems=0) -> Plan:
+    return Plan(rows, N, align_elems, var_flags, chunk_elems, cols=cols)
 
 
 def shard_plan_bind(plan: Plan, workspace: Optional[torch.Tensor] = None, stream=None, device="cuda") -> Plan:

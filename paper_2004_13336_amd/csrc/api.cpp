@@ -133,7 +133,24 @@ int shard_plan(int V, const int64_t* numel, int N, int align_elems, const uint32
   *out = nullptr;
   shard_plan_t* p = new (std::nothrow) shard_plan_s();
   if (p == nullptr) return SHARD_ENOMEM;
-  const int rc = plan_build(p, V, numel, N, align_elems, var_flags, chunk_elems);
+  const int rc = plan_build(p, V, numel, nullptr, N, align_elems, var_flags, chunk_elems);
+  if (rc != SHARD_OK) {
+    delete p;
+    return rc;
+  }
+  *out = p;
+  return SHARD_OK;
+}
+
+int shard_plan_rows(int V, const int64_t* rows, const int64_t* cols, int N, int align_elems, const uint32_t* var_flags,
+                    int chunk_elems, shard_plan_t** out) {
+  if (out == nullptr) return SHARD_EINVAL;
+  *out = nullptr;
+  if (V > 0 && cols == nullptr) return SHARD_EINVAL;
+  static const int64_t none = 0;
+  shard_plan_s* p = new (std::nothrow) shard_plan_s();
+  if (p == nullptr) return SHARD_ENOMEM;
+  const int rc = plan_build(p, V, rows, V > 0 ? cols : &none, N, align_elems, var_flags, chunk_elems);
   if (rc != SHARD_OK) {
     delete p;
     return rc;
@@ -165,8 +182,8 @@ int shard_plan_segments(const shard_plan_t* p, int64_t* seg_off, int64_t* seg_le
 int shard_plan_real_count(const shard_plan_t* p, int r, int64_t* real) {
   if (p == nullptr || real == nullptr || r < 0 || r >= p->N) return SHARD_EINVAL;
   for (int i = 0; i < p->V; ++i) {
-    const int64_t rem = p->n[i] - (int64_t)r * p->L[i];
-    real[i] = rem <= 0 ? 0 : (rem < p->L[i] ? rem : p->L[i]);
+    const int64_t rem = p->n[i] - (int64_t)r * p->stride[i];
+    real[i] = rem <= 0 ? 0 : (rem < p->stride[i] ? rem : p->stride[i]);
   }
   return SHARD_OK;
 }

@@ -13,18 +13,20 @@ namespace su {
 
 // ---- device-visible tables (uploaded by shard_plan_bind) ------------------------------------
 
-// One variable of the plan.  Section 4.1: the piece of replica r starts at r*L in the flat
-// variable; slots whose flat index reaches n are padding.
+// One variable of the plan.  Section 4.1: the piece of replica r starts at r*stride in the flat
+// variable; a slot is padding if it lies past the piece's `stride` real slots or if its flat
+// index reaches n.
 struct VarDesc {
   int64_t n;            // elements of the full variable
-  int64_t L;            // piece length per replica
+  int64_t L;            // slots per replica in the packed shard
   int64_t off;          // offset of the piece in a packed shard
+  int64_t stride;       // flat plan: L; row plan: rows per replica * cols (<= L)
   int32_t first_chunk;  // this variable's chunks are [first_chunk, first_chunk + n_chunks)
   int32_t n_chunks;
   uint32_t flags;       // SHARD_VAR_*
   uint32_t reserved;
 };
-static_assert(sizeof(VarDesc) == 40, "VarDesc layout");
+static_assert(sizeof(VarDesc) == 48, "VarDesc layout");
 
 // One work item of the table-driven kernels: `len` consecutive slots of one variable's piece,
 // starting k0 slots into the piece.  Never crosses a variable boundary.
@@ -74,7 +76,7 @@ struct ProfRecord {
 struct shard_plan_s {
   int V = 0, N = 1, align = 1, chunk = 0;
   int64_t S = 0, total = 0;
-  std::vector<int64_t> n, L, off;
+  std::vector<int64_t> n, L, off, stride;
   std::vector<uint32_t> flags;
   std::vector<su::VarDesc> vars;
   std::vector<su::ChunkDesc> chunks;
@@ -98,7 +100,9 @@ struct shard_plan_s {
 namespace su {
 
 // plan.cpp (host only)
-int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, const uint32_t* flags, int chunk);
+// cols == nullptr: flat plan over numel[i] elements; otherwise numel[i] is the row count of a rows x cols matrix
+int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols, int N, int align,
+               const uint32_t* flags, int chunk);
 size_t workspace_layout(const shard_plan_t* p, Workspace* ws);
 
 // kernels.hip: every launcher enqueues on `stream`, returns a hipError_t and never synchronises.

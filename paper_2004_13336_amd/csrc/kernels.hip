@@ -137,8 +137,9 @@ __device__ __forceinline__ ChunkView chunk_view(const VarDesc* __restrict__ vars
   ChunkView cv;
   cv.var = cd.var;
   cv.len = cd.len;
-  cv.flat0 = (int64_t)r * vd.L + cd.k0;
-  const int64_t rem = vd.n - cv.flat0;
+  cv.flat0 = (int64_t)r * vd.stride + cd.k0;
+  int64_t rem = vd.n - cv.flat0;                            // up to the end of the variable ...
+  if (vd.stride - cd.k0 < rem) rem = vd.stride - cd.k0;     // ... and of the piece's real slots
   cv.valid = rem <= 0 ? 0 : (rem < (int64_t)cd.len ? (int)rem : cd.len);
   cv.shard0 = vd.off + cd.k0;
   cv.flags = vd.flags;
@@ -314,9 +315,11 @@ __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, 
   constexpr int TILE = kBlock * UnitOf<SRC, DST>::n;
   if (tile * TILE >= (UNSHARD ? cv.valid : cv.len)) return;
   const void* ptr = ptrs[cv.var];
-  // 128-bit accesses need this variable's tensor on a 16-byte boundary (VEC already says the
-  // pieces are); a tensor that is not takes the element-wise path, the others are unaffected
-  const bool vec = VEC && (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0;
+  // 128-bit accesses need this chunk's place in the full tensor on a 16-byte boundary (VEC already
+  // says its place in the shard is); a tensor or a row-plan piece that is not takes the
+  // element-wise path, the others are unaffected
+  const uintptr_t full_addr = reinterpret_cast<uintptr_t>(ptr) + (uintptr_t)cv.flat0 * sizeof(typename ElemOf<UNSHARD ? DST : SRC>::type);
+  const bool vec = VEC && (full_addr & 15u) == 0;
   if constexpr (UNSHARD) {
     const SrcT* src = (const SrcT*)packed + (int64_t)replica * row_stride + cv.shard0;
     DstT* dst = (DstT*)const_cast<void*>(ptr) + cv.flat0;

@@ -17,7 +17,8 @@ constexpr int kDefaultChunk = 2048;   // measured best on MI355X for the formatt
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 }  // namespace
 
-int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, const uint32_t* flags, int chunk) {
+int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols, int N, int align,
+               const uint32_t* flags, int chunk) {
   if (V < 0 || N < 1 || align < 1 || (align & (align - 1)) != 0) return SHARD_EINVAL;
   if (V > 0 && numel == nullptr) return SHARD_EINVAL;
   if (chunk == 0) chunk = kDefaultChunk;
@@ -28,20 +29,34 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, c
   p->align = align;
   p->chunk = chunk;
   try {
-    p->n.assign(numel, numel + V);
+    p->n.assign(V, 0);
     p->L.resize(V);
+    p->stride.resize(V);
     p->off.resize(V);
     p->flags.assign(V, 0u);
     p->vars.resize(V);
     const int64_t kMax = std::numeric_limits<int64_t>::max() / 16;   // head-room for byte offsets
     int64_t pos = 0, total = 0;
     for (int i = 0; i < V; ++i) {
-      const int64_t n = numel[i];
+      int64_t n = numel[i], per;
       if (n < 0 || n > kMax) return SHARD_EINVAL;
-      const int64_t per = (n + N - 1) / N;                 // ceil(n / N)
+      if (cols) {
+        // row plan: the leading (combined) dimension is padded to a multiple of N and sliced,
+        // whole rows per replica; numel[i] is the row count
+        const int64_t c = cols[i];
+        if (c < 0 || c > kMax || (c > 0 && n > kMax / c)) return SHARD_EINVAL;
+        const int64_t rows_per = c > 0 ? (n + N - 1) / N : 0;
+        if (c > 0 && rows_per > kMax / c) return SHARD_EINVAL;
+        per = rows_per * c;
+        n = n * c;
+      } else {
+        per = (n + N - 1) / N;                             // ceil(n / N)
+      }
       const int64_t len = (per + align - 1) / align * align;
       if (len > kMax / N || pos > kMax - len) return SHARD_EINVAL;
+      p->n[i] = n;
       p->L[i] = len;
+      p->stride[i] = cols ? per : len;
       p->off[i] = pos;
       pos += len;
       total += n;
@@ -60,6 +75,7 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, int N, int align, c
       vd.n = p->n[i];
       vd.L = p->L[i];
       vd.off = p->off[i];
+      vd.stride = p->stride[i];
       vd.flags = p->flags[i];
       vd.reserved = 0;
       const int64_t count = (p->L[i] + chunk - 1) / chunk;

@@ -75,6 +75,7 @@ def assert_second_moment_close(got, ref, steps: int = 1, what: str = "v"):
 
 
 def pads_are_zero(plan: oracle.Plan, r: int, shard: np.ndarray) -> bool:
+    # real_count counts from the piece start in both plan kinds (row plans pad inside the piece too)
     bits = shard.view(np.uint32 if shard.dtype == np.float32 else np.uint16)
     for i in range(plan.V):
         real = plan.real_count(i, r)

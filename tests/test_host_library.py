@@ -136,3 +136,29 @@ def test_calls_that_need_a_workspace_say_so_without_touching_the_gpu():
     misaligned = C.c_void_p(0x1004)
     assert lib().shard_update_adam(p.handle, 0, misaligned, fake, fake, fake, None, C.byref(ahp), 1, None) == -3
     p.free()
+
+
+def test_row_plan_matches_oracle():
+    from oracle import make_row_plan
+    rnd = random.Random(11)
+    for _ in range(40):
+        N = rnd.randint(1, 40)
+        align = rnd.choice([1, 4, 8])
+        shapes = [(rnd.choice([0, 1, 2, 3, 7, 9, N - 1, N, N + 1, 100, 3000]), rnd.choice([0, 1, 3, 8, 10, 64, 100]))
+                  for _ in range(rnd.randint(0, 8))]
+        want = make_row_plan(shapes, N, align)
+        got = su.shard_plan_rows([s[0] for s in shapes], [s[1] for s in shapes], N, align)
+        assert (got.S, got.total) == (want.S, sum(want.numel))
+        off, length = got.segments()
+        assert off == want.off and length == want.L
+        for r in {0, N // 2, N - 1}:
+            assert got.real_count(r) == tuple(want.real_count(i, r) for i in range(len(shapes)))
+        got.free()
+    # the paper's example: [3,3,256,256] as 9 x 65536 at 10 replicas pads to 10 rows
+    p = su.shard_plan_rows([9], [65536], 10, 1)
+    assert p.S == 65536 and p.real_count(8) == (65536,) and p.real_count(9) == (0,)
+    p.free()
+    h = C.c_void_p()
+    assert lib().shard_plan_rows(1, (C.c_int64 * 1)(4), None, 2, 8, None, 0, C.byref(h)) == -1
+    assert lib().shard_plan_rows(1, (C.c_int64 * 1)(4), (C.c_int64 * 1)(-1), 2, 8, None, 0, C.byref(h)) == -1
+    assert lib().shard_plan_rows(1, (C.c_int64 * 1)(2 ** 40), (C.c_int64 * 1)(2 ** 40), 2, 8, None, 0, C.byref(h)) == -1
