@@ -20,5 +20,6 @@ from .formatting import shard_format, unshard_format, f32_to_bf16_bits, bf16_bit
 from .optim import (  # noqa: F401
     adam_step, momentum_step, lamb_unsharded_step, lamb_shard_partials, lamb_shard_apply,
     lars_unsharded_step, lars_shard_partials, lars_shard_apply,
+    rowcol_sumsq_unsharded, rowcol_sumsq_shard,
     VAR_NO_DECAY, VAR_NO_ADAPT,
 )

@@ -208,3 +208,39 @@ def lars_shard_apply(plan: Plan, w, g, m, global_sums, hp, flags: Sequence[int] 
         wi, mi = _lars_apply(w64[seg], g64[seg], m64[seg], local_lr, wd, hp)
         out_w[seg] = wi.astype(_f32); out_m[seg] = mi.astype(_f32)
     return out_w, out_m
+
+
+# ------------------------------------------------- reductions that keep a dimension (row plan)
+# Section 4.1, "Non-elementwise operators": a reduce may collapse some dimensions and pass others
+# through; the sharding format must not merge the two kinds, which the row plan guarantees.  With
+# rows sharded, a reduce over columns is complete on the replica that owns the row, and a reduce
+# over rows yields per-replica partial results that an all-reduce combines; padded rows contribute
+# the identity.  The sums of squares below are the two reductions factored second-moment optimizers
+# (Adafactor) take of the gradient.
+
+def rowcol_sumsq_unsharded(mats: Sequence):
+    """For each 2-D array X: (sum over columns of X^2, one value per row; sum over rows, one per column)."""
+    out = []
+    for X in mats:
+        X64 = np.asarray(X, dtype=_f32).astype(_f64)
+        sq = X64 * X64
+        out.append((sq.sum(axis=1), sq.sum(axis=0)))
+    return out
+
+
+def rowcol_sumsq_shard(plan: Plan, r: int, x):
+    """On replica r's packed shard of a row plan.  Returns (row_sums, col_partials): row_sums[i] has
+    Lr_i entries (0 for padded rows), col_partials[i] has cols_i entries summed over the replica's
+    real rows only."""
+    assert plan.rows is not None and 0 <= r < plan.N
+    (x64,) = _up(x)
+    row_sums, col_partials = [], []
+    for i in range(plan.V):
+        Lr, cols = plan.Lr[i], plan.cols[i]
+        piece = x64[plan.off[i]:plan.off[i] + Lr * cols].reshape(Lr, cols)
+        row_index = r * Lr + np.arange(Lr, dtype=np.int64)          # place in the full matrix
+        real = (row_index < plan.rows[i])[:, None]
+        sq = np.where(real, piece * piece, 0.0)
+        row_sums.append(sq.sum(axis=1))
+        col_partials.append(sq.sum(axis=0))
+    return row_sums, col_partials

@@ -117,3 +117,46 @@ def test_updates_on_a_row_plan_equal_the_unsharded_update():
     for i, b in enumerate(unshard_format(p, A)):
         a, _, _ = adam_step(ws[i], gs[i], z[i], z[i], {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8}, 1)
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ---------------------------------------------------------------- row / column sums of squares
+
+from oracle import rowcol_sumsq_shard, rowcol_sumsq_unsharded
+
+
+def test_rowcol_sums_by_loops_and_against_the_norm():
+    X = normal_f32(4, 0, "g", 35, 1.0).reshape(5, 7)
+    (rows, cols), = rowcol_sumsq_unsharded([X])
+    for i in range(5):
+        assert abs(rows[i] - sum(float(X[i, j]) ** 2 for j in range(7))) < 1e-12
+    for j in range(7):
+        assert abs(cols[j] - sum(float(X[i, j]) ** 2 for i in range(5))) < 1e-12
+    total = float(np.sum(X.astype(np.float64) ** 2))
+    assert abs(rows.sum() - total) < 1e-12 and abs(cols.sum() - total) < 1e-12
+    # a transposed operand would swap the two
+    (rt, ct), = rowcol_sumsq_unsharded([X.T.copy()])
+    assert np.allclose(rt, cols) and np.allclose(ct, rows)
+
+
+def test_sharded_rowcol_sums_put_together_equal_the_unsharded_ones():
+    shapes = [(9, 16), (5, 3), (1, 7), (30, 10), (4, 1), (0, 4)]
+    for N in (1, 3, 4, 10):
+        p = make_row_plan(shapes, N, 8)
+        mats = [normal_f32(6, i, "g", r * c, 1e-2).reshape(r, c) for i, (r, c) in enumerate(shapes)]
+        want = rowcol_sumsq_unsharded(mats)
+        rows_all = [[] for _ in shapes]
+        cols_sum = [np.zeros(c) for _, c in shapes]
+        for r in range(N):
+            x = shard_format(p, r, [m.ravel() for m in mats])
+            # garbage in every padded slot: masks go by position (Section 4.1)
+            for i in range(p.V):
+                x[p.off[i] + p.real_count(i, r): p.off[i] + p.L[i]] = 9.0
+            rs, cp = rowcol_sumsq_shard(p, r, x)
+            for i in range(p.V):
+                assert rs[i].shape == (p.Lr[i],) and cp[i].shape == (p.cols[i],)
+                assert not rs[i][p.real_rows(i, r):].any()                    # padded rows give the identity
+                rows_all[i].append(rs[i][:p.real_rows(i, r)])
+                cols_sum[i] += cp[i]                                           # the all-reduce over replicas
+        for i in range(p.V):
+            assert np.allclose(np.concatenate(rows_all[i]), want[i][0], rtol=1e-13, atol=0)   # rows stay sharded
+            assert np.allclose(cols_sum[i], want[i][1], rtol=1e-13, atol=0)
