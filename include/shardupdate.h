@@ -71,8 +71,8 @@ enum {
 enum {
   SHARD_K_FORMAT = 0, SHARD_K_UNSHARD = 1, SHARD_K_ADAM = 2, SHARD_K_MOMENTUM = 3,
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
-  SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9,
-  SHARD_K_COUNT = 10
+  SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9, SHARD_K_ROWCOL_P1 = 10, SHARD_K_ROWCOL_P2 = 11,
+  SHARD_K_COUNT = 12
 };
 
 const char* shard_strerror(int status);
@@ -237,6 +237,28 @@ int shard_update_lars_apply(shard_plan_t* plan, int r, float* w, const float* g,
 int shard_update_lars(shard_plan_t* plan, int r, float* w, const float* g, float* m,
                       void* w_bf16_out, const shard_lars_hp* hp, const float* other_replicas_sumsq,
                       float* local_sumsq_out, shard_stream_t stream);
+
+/* Reductions that keep a dimension, on a row plan (Section 4.1, "Non-elementwise operators": the
+ * format may not merge a collapsed dimension with a passed-through one; with rows sharded, a reduce
+ * over columns is complete on the owning replica and a reduce over rows gives per-replica partial
+ * results for an all-reduce; padded rows contribute the identity).  These are the two reductions
+ * factored second-moment optimizers (Adafactor) take of the gradient.
+ *
+ * shard_plan_rowcol_layout: host arrays row_off[V], col_off[V] (either may be NULL) and totals:
+ *   variable i's Lr_i row sums start at row_off[i] in row_out, its cols_i column sums at
+ *   col_off[i] in col_out; total_rows = sum Lr_i, total_cols = sum cols_i.  SHARD_EINVAL on a
+ *   flat plan.
+ * shard_reduce_sq_rows_cols: x is replica r's packed shard [S] (device, float32).
+ *   row_out[row_off[i] + k] = sum over columns of x^2 in row k of the piece (0 for padded rows)
+ *   col_out[col_off[i] + c] = sum over the replica's REAL rows of x^2 in column c
+ *   Both are device float32 arrays, 16-byte aligned.  Padding is masked by position.  The
+ *   summation order is fixed.  Needs a bound row plan.
+ */
+int shard_plan_rowcol_layout(const shard_plan_t* plan, int64_t* row_off, int64_t* col_off,
+                             int64_t* total_rows, int64_t* total_cols);
+
+int shard_reduce_sq_rows_cols(shard_plan_t* plan, int r, const float* x, float* row_out, float* col_out,
+                              shard_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events recorded on the launch stream, for benchmarks.

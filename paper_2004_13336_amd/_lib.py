@@ -64,6 +64,8 @@ SIGNATURES = {
     "shard_update_lars_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P]),
     "shard_update_lars_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P]),
     "shard_update_lars": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P, _P]),
+    "shard_plan_rowcol_layout": (C.c_int, [_P, _I64P, _I64P, _I64P, _I64P]),
+    "shard_reduce_sq_rows_cols": (C.c_int, [_P, C.c_int, _P, _P, _P, _P]),
     "shard_profile_enable": (C.c_int, [_P, C.c_int]),
     "shard_profile_read": (C.c_int, [_P, C.c_int, _I64P, C.POINTER(C.c_double)]),
     "shard_profile_reset": (C.c_int, [_P]),

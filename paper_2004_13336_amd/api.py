@@ -16,7 +16,7 @@ from ._lib import AdamHP, LambHP, LarsHP, MomentumHP, ShardError, lib
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
-              "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9}
+              "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -281,6 +281,23 @@ def shard_update_lars(plan: Plan, r: int, w, g, m, hp, other_replicas_sumsq=None
                                    _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
                                    _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
                                    _stream(stream)), "shard_update_lars")
+
+
+def shard_plan_rowcol_layout(plan: Plan):
+    """(row_off[V], col_off[V], total_rows, total_cols) of a row plan's row-sum and column-sum outputs."""
+    ro = (C.c_int64 * max(plan.V, 1))(); co = (C.c_int64 * max(plan.V, 1))()
+    tr, tc = C.c_int64(), C.c_int64()
+    _check(lib().shard_plan_rowcol_layout(plan.handle, ro, co, C.byref(tr), C.byref(tc)), "shard_plan_rowcol_layout")
+    return tuple(ro[: plan.V]), tuple(co[: plan.V]), tr.value, tc.value
+
+
+def shard_reduce_sq_rows_cols(plan: Plan, r: int, x, row_out, col_out, stream=None):
+    f = torch.float32
+    _, _, total_rows, total_cols = shard_plan_rowcol_layout(plan)
+    _check(lib().shard_reduce_sq_rows_cols(plan.handle, int(r), _dev(x, plan.S, f, "x"),
+                                           _dev(row_out, total_rows, f, "row_out"),
+                                           _dev(col_out, total_cols, f, "col_out"), _stream(stream)),
+           "shard_reduce_sq_rows_cols")
 
 
 def shard_profile_enable(plan: Plan, on: bool) -> None:

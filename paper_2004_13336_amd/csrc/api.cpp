@@ -91,7 +91,7 @@ int check_full_ptrs(const shard_plan_t* p, const void* const* ptrs) {
 const char* const kKernelNames[SHARD_K_COUNT] = {
     "format_kernel", "unshard_kernel", "adam_kernel", "momentum_kernel",
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
-    "lars_p1_kernel", "lars_p2_kernel",
+    "lars_p1_kernel", "lars_p2_kernel", "rowcol_p1_kernel", "rowcol_p2_kernel",
 };
 
 int fold_lars(const shard_lars_hp* hp, LarsK* k) {
@@ -204,6 +204,15 @@ int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard
   if (!p->chunks.empty() && hipMemcpyAsync(ws.base + ws.chunks, p->chunks.data(), p->chunks.size() * sizeof(ChunkDesc),
                                            hipMemcpyHostToDevice, s) != hipSuccess)
     return SHARD_EHIP;
+  if (p->row_plan) {
+    if (!p->rc_vars.empty() && hipMemcpyAsync(ws.base + ws.rc_vars, p->rc_vars.data(), p->rc_vars.size() * sizeof(RowColVar),
+                                              hipMemcpyHostToDevice, s) != hipSuccess)
+      return SHARD_EHIP;
+    if (!p->rc_items.empty() && hipMemcpyAsync(ws.base + ws.rc_items, p->rc_items.data(),
+                                               p->rc_items.size() * sizeof(RowColItem), hipMemcpyHostToDevice,
+                                               s) != hipSuccess)
+      return SHARD_EHIP;
+  }
   p->ws = ws;
   for (int i = 0; i < kPtrSlots; ++i) p->slot_valid[i] = false;
   return SHARD_OK;
@@ -401,6 +410,30 @@ int shard_update_lars(shard_plan_t* p, int r, float* w, const float* g, float* m
   if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
   if (e == hipSuccess) e = launch_lars_p2(p, r, w, g, m, w_bf16_out, k, sums, s);
   return hip_status(e);
+}
+
+int shard_plan_rowcol_layout(const shard_plan_t* p, int64_t* row_off, int64_t* col_off, int64_t* total_rows,
+                             int64_t* total_cols) {
+  if (p == nullptr || !p->row_plan) return SHARD_EINVAL;
+  for (int i = 0; i < p->V; ++i) {
+    if (row_off) row_off[i] = p->rc_vars[i].row_off;
+    if (col_off) col_off[i] = p->rc_vars[i].col_off;
+  }
+  if (total_rows) *total_rows = p->rc_total_rows;
+  if (total_cols) *total_cols = p->rc_total_cols;
+  return SHARD_OK;
+}
+
+int shard_reduce_sq_rows_cols(shard_plan_t* p, int r, const float* x, float* row_out, float* col_out,
+                              shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (!p->row_plan) return SHARD_EINVAL;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(x)) != SHARD_OK) return rc;
+  if (p->rc_total_rows > 0 && (rc = check_shard_ptr(row_out)) != SHARD_OK) return rc;
+  if (p->rc_total_cols > 0 && (rc = check_shard_ptr(col_out)) != SHARD_OK) return rc;
+  return hip_status(launch_rowcol_sumsq(p, r, x, row_out, col_out, as_stream(stream)));
 }
 
 int shard_profile_enable(shard_plan_t* p, int on) {

@@ -37,6 +37,28 @@ struct ChunkDesc {
 };
 static_assert(sizeof(ChunkDesc) == 16, "ChunkDesc layout");
 
+// Row plans only: one variable seen as a row-major rows x cols matrix whose rows are sharded, and
+// one work item of the row/column reduction: kRowBlock rows x one column tile.
+struct RowColVar {
+  int64_t off;        // piece offset in the packed shard
+  int64_t rows;       // rows of the full matrix
+  int64_t Lr;         // rows per replica
+  int64_t cols;
+  int64_t row_off;    // this variable's place in the row-sum output  (sum of Lr of earlier variables)
+  int64_t col_off;    // and in the column-sum output                 (sum of cols of earlier variables)
+  int64_t cp_off;     // column partials [n_rb][cols] in the workspace
+  int64_t rp_off;     // row partials [n_ct][Lr] in the workspace
+  int32_t n_rb;       // row blocks
+  int32_t n_ct;       // column tiles
+  int32_t vec;        // 1: rows start on 16-byte boundaries, threads own 4 adjacent columns
+  int32_t reserved;
+};
+static_assert(sizeof(RowColVar) == 80, "RowColVar layout");
+struct RowColItem {
+  int32_t var, rb, ct, reserved;
+};
+constexpr int kRowBlock = 32;        // rows per work item of the row/column reduction
+
 constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kPtrSlots = 4;         // cached device pointer tables per plan
 constexpr int kPtrBatch = 256;       // pointers carried by one table-writing launch
@@ -64,6 +86,7 @@ struct Workspace {
   size_t bytes = 0;
   // byte offsets inside base
   size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
+  size_t rc_vars = 0, rc_items = 0, rc_colpart = 0, rc_rowpart = 0;   // row plans only
 };
 
 struct ProfRecord {
@@ -80,6 +103,10 @@ struct shard_plan_s {
   std::vector<uint32_t> flags;
   std::vector<su::VarDesc> vars;
   std::vector<su::ChunkDesc> chunks;
+  bool row_plan = false;
+  std::vector<su::RowColVar> rc_vars;      // row plans only
+  std::vector<su::RowColItem> rc_items;
+  int64_t rc_total_rows = 0, rc_total_cols = 0, rc_colpart_elems = 0, rc_rowpart_elems = 0;
 
   su::Workspace ws;
   size_t ws_need = 0;
@@ -133,6 +160,11 @@ hipError_t launch_format_all(shard_plan_t* p, const void* const* dev_ptr_table, 
 hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, hipStream_t stream);
 hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w16, const LarsK& k,
                           const float* sums, hipStream_t stream);
+
+// Row/column sums of squares on a row plan: phase 1 writes per-item partials, phase 2 adds them in
+// a fixed order into row_out [sum Lr] and col_out [sum cols].
+hipError_t launch_rowcol_sumsq(shard_plan_t* p, int r, const float* x, float* row_out, float* col_out,
+                               hipStream_t stream);
 
 // RAII helper: records an event pair around a launch when profiling is on.
 struct ProfScope {

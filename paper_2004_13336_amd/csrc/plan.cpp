@@ -93,6 +93,45 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       }
     }
     for (int s = 0; s < kPtrSlots; ++s) p->slot_ptrs[s].assign(V, nullptr);
+
+    p->row_plan = cols != nullptr;
+    p->rc_vars.clear();
+    p->rc_items.clear();
+    if (cols) {
+      // work items of the row/column reduction: kRowBlock rows x one column tile (1024 columns
+      // where 128-bit accesses are possible, 256 otherwise)
+      int64_t row_off = 0, col_off = 0, cp = 0, rp = 0;
+      for (int i = 0; i < V; ++i) {
+        RowColVar rv;
+        rv.off = p->off[i];
+        rv.rows = numel[i];
+        rv.cols = cols[i];
+        rv.Lr = cols[i] > 0 ? (numel[i] + N - 1) / N : 0;
+        rv.vec = (cols[i] % 4 == 0 && p->off[i] % 4 == 0) ? 1 : 0;
+        rv.reserved = 0;
+        const int64_t tile_cols = rv.vec ? 4 * kBlock : kBlock;
+        const int64_t n_rb = (rv.Lr + kRowBlock - 1) / kRowBlock;
+        const int64_t n_ct = (rv.cols + tile_cols - 1) / tile_cols;
+        if (n_rb * n_ct + (int64_t)p->rc_items.size() > (int64_t)std::numeric_limits<int32_t>::max()) return SHARD_EINVAL;
+        rv.n_rb = (int32_t)n_rb;
+        rv.n_ct = (int32_t)n_ct;
+        rv.row_off = row_off;
+        rv.col_off = col_off;
+        rv.cp_off = cp;
+        rv.rp_off = rp;
+        row_off += rv.Lr;
+        col_off += rv.cols;
+        cp += (n_rb * rv.cols + 3) / 4 * 4;                // keeps every variable's partials 16-byte aligned
+        rp += n_ct * rv.Lr;
+        p->rc_vars.push_back(rv);
+        for (int64_t rb = 0; rb < n_rb; ++rb)
+          for (int64_t ct = 0; ct < n_ct; ++ct) p->rc_items.push_back(RowColItem{i, (int32_t)rb, (int32_t)ct, 0});
+      }
+      p->rc_total_rows = row_off;
+      p->rc_total_cols = col_off;
+      p->rc_colpart_elems = cp;
+      p->rc_rowpart_elems = rp;
+    }
   } catch (const std::bad_alloc&) {
     return SHARD_ENOMEM;
   }
@@ -109,6 +148,12 @@ size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
   ws->ptrs = pos;        pos = align_up(pos + (size_t)kPtrSlots * V * sizeof(void*), 256);
   ws->chunk_sums = pos;  pos = align_up(pos + C * 2 * sizeof(float), 256);
   ws->var_sums = pos;    pos = align_up(pos + V * 2 * sizeof(float), 256);
+  if (p->row_plan) {
+    ws->rc_vars = pos;     pos = align_up(pos + p->rc_vars.size() * sizeof(RowColVar), 256);
+    ws->rc_items = pos;    pos = align_up(pos + p->rc_items.size() * sizeof(RowColItem), 256);
+    ws->rc_colpart = pos;  pos = align_up(pos + (size_t)p->rc_colpart_elems * sizeof(float), 256);
+    ws->rc_rowpart = pos;  pos = align_up(pos + (size_t)p->rc_rowpart_elems * sizeof(float), 256);
+  }
   return pos < 256 ? 256 : pos;
 }
 

@@ -110,3 +110,77 @@ def test_row_plan_lamb_and_adam_resnet_shaped():
         a, _, _ = oracle.adam_step(ws[i], gs[i], z[i], z[i], ADAM, 1)
         assert_weights_close(b, a, "adam var %d" % i)
     plan.free()
+
+
+ROWCOL_CASES = [
+    ([(9, 16), (5, 3), (1, 7), (0, 4), (12, 10), (3, 0), (70, 260), (33, 1028), (100, 1)], 4, 8),
+    ([(9, 65536)], 10, 8),
+    ([(9, 4096), (1000, 1), (64, 1), (7, 4099), (300, 2048)], 8, 8),
+    ([(33, 100), (2, 5), (40, 8)], 3, 1),
+]
+
+
+@pytest.mark.parametrize("shapes,N,align", ROWCOL_CASES)
+def test_rowcol_sums_of_squares(shapes, N, align):
+    oplan = oracle.make_row_plan(shapes, N, align)
+    plan = su.shard_plan_bind(su.shard_plan_rows([s[0] for s in shapes], [s[1] for s in shapes], N, align))
+    row_off, col_off, total_rows, total_cols = su.shard_plan_rowcol_layout(plan)
+    assert total_rows == sum(oplan.Lr) and total_cols == sum(oplan.cols)
+    mats = [normal_f32(61, i, "g", n, 1e-2) for i, n in enumerate(oplan.numel)]
+    want_full = oracle.rowcol_sumsq_unsharded([m.reshape(s) for m, s in zip(mats, shapes)])
+    col_sum = torch.zeros(max(total_cols, 1), dtype=torch.float64, device=DEV)[:total_cols]
+    rows_seen = [[] for _ in shapes]
+    for r in range(N):
+        x = oracle.shard_format(oplan, r, mats)
+        for i in range(oplan.V):                                   # garbage in the padding: masked by position
+            x[oplan.off[i] + oplan.real_count(i, r): oplan.off[i] + oplan.L[i]] = 9.0
+        want_rows, want_cols = oracle.rowcol_sumsq_shard(oplan, r, x)
+        row_out = torch.full((total_rows + 4,), -1.0, dtype=torch.float32, device=DEV)
+        col_out = torch.full((total_cols + 4,), -1.0, dtype=torch.float32, device=DEV)
+        su.shard_reduce_sq_rows_cols(plan, r, to_dev(x), row_out, col_out)
+        ro, co = to_host(row_out), to_host(col_out)
+        assert (ro[total_rows:] == -1.0).all() and (co[total_cols:] == -1.0).all()
+        for i in range(oplan.V):
+            np.testing.assert_allclose(ro[row_off[i]:row_off[i] + oplan.Lr[i]].astype(np.float64), want_rows[i],
+                                       rtol=3e-6, atol=1e-30)
+            np.testing.assert_allclose(co[col_off[i]:col_off[i] + oplan.cols[i]].astype(np.float64), want_cols[i],
+                                       rtol=3e-6, atol=1e-30)
+            rows_seen[i].append(ro[row_off[i]:row_off[i] + oplan.real_rows(i, r)])
+        col_sum += col_out[:total_cols].double()                    # stands in for the all-reduce
+        # twice the same bits
+        row2 = torch.empty_like(row_out); col2 = torch.empty_like(col_out)
+        su.shard_reduce_sq_rows_cols(plan, r, to_dev(x), row2, col2)
+        assert torch.equal(row2[:total_rows], row_out[:total_rows]) and torch.equal(col2[:total_cols], col_out[:total_cols])
+    cs = col_sum.cpu().numpy()
+    for i in range(oplan.V):
+        if oplan.cols[i] == 0:                                      # a matrix without columns has no piece at all
+            continue
+        np.testing.assert_allclose(np.concatenate(rows_seen[i]).astype(np.float64), want_full[i][0], rtol=3e-6, atol=1e-30)
+        np.testing.assert_allclose(cs[col_off[i]:col_off[i] + oplan.cols[i]], want_full[i][1], rtol=3e-6, atol=1e-30)
+    plan.free()
+
+
+def test_rowcol_needs_a_row_plan():
+    plan = su.shard_plan_bind(su.shard_plan([100, 8], 2))
+    with pytest.raises(su.ShardError) as e:
+        su.shard_plan_rowcol_layout(plan)
+    assert e.value.status == -1
+    plan.free()
+
+
+def test_rowcol_resnet_shaped_full_size():
+    shapes = _resnet_rows_cols()
+    N = 8
+    oplan = oracle.make_row_plan(shapes, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan_rows([s[0] for s in shapes], [s[1] for s in shapes], N, 8))
+    row_off, col_off, total_rows, total_cols = su.shard_plan_rowcol_layout(plan)
+    mats = [normal_f32(62, i, "g", n, 1e-3) for i, n in enumerate(oplan.numel)]
+    for r in (0, 4, 7):
+        x = oracle.shard_format(oplan, r, mats)
+        want_rows, want_cols = oracle.rowcol_sumsq_shard(oplan, r, x)
+        row_out = torch.empty(total_rows, dtype=torch.float32, device=DEV)
+        col_out = torch.empty(total_cols, dtype=torch.float32, device=DEV)
+        su.shard_reduce_sq_rows_cols(plan, r, to_dev(x), row_out, col_out)
+        np.testing.assert_allclose(to_host(row_out).astype(np.float64), np.concatenate(want_rows), rtol=3e-6, atol=1e-30)
+        np.testing.assert_allclose(to_host(col_out).astype(np.float64), np.concatenate(want_cols), rtol=3e-6, atol=1e-30)
+    plan.free()
