@@ -261,3 +261,73 @@ def test_bf16_rounding_mutants_are_caught(monkeypatch, kind):
     monkeypatch.setattr(tf, "f32_to_bf16_bits", to_bf16)
     monkeypatch.setattr(fmt, "f32_to_bf16_bits", to_bf16)
     assert _fails(FORMAT_PINS)
+
+
+# ---- mutants of the replica-array arithmetic -----------------------------------------------------
+
+import oracle.topology as topo  # noqa: E402
+import test_oracle_topology as tt  # noqa: E402
+from fractions import Fraction  # noqa: E402
+
+TOPO_PINS = [(tt.test_papers_subgroup_example, (row,)) for row in tt._golden("rowgroup")] + \
+            [(tt.test_papers_pod_example, row) for row in tt._golden("groups")] + \
+            [(tt.test_partial_sharding_equals_the_full_all_reduce_piece, rc) for rc in ((2, 4), (4, 6))] + \
+            [(tt.test_two_phase_shard_id_by_simulation, rc) for rc in ((2, 3), (3, 5))] + \
+            [(tt.test_degenerate_arrays, ())] + \
+            [(tt.test_memory_model_hand_worked, row) for row in tt._golden("memory")] + \
+            [(tt.test_memory_model_properties, ())] + \
+            [(tt.test_concat_partition_tiles_the_concatenation, (13, 4)), (tt.test_combined_all_reduce_ignores_tensor_boundaries, ())]
+
+
+@pytest.mark.parametrize("kind", ["column_major_ids", "groups_are_columns", "shard_id_is_row"])
+def test_partial_sharding_mutants_are_caught(monkeypatch, kind):
+    def partial_sharding(rows, cols, replica):
+        topo._check_array(rows, cols, replica)
+        if kind == "column_major_ids":
+            col, row = divmod(replica, rows)
+            return row, col, [j * rows + row for j in range(cols)], [col * rows + i for i in range(rows)]
+        row, col = divmod(replica, cols)
+        sg, rg = [row * cols + j for j in range(cols)], [i * cols + col for i in range(rows)]
+        if kind == "groups_are_columns":
+            return col, row, rg, sg
+        return row, row, sg, rg                                  # shard_id_is_row
+    monkeypatch.setattr(tt, "partial_sharding", partial_sharding)
+    assert _fails(TOPO_PINS)
+
+
+@pytest.mark.parametrize("kind", ["row_major", "column_phase_first"])
+def test_two_phase_mutants_are_caught(monkeypatch, kind):
+    def two_phase(rows, cols, replica):
+        topo._check_array(rows, cols, replica)
+        i, j = divmod(replica, cols)
+        return i * cols + j if kind == "row_major" else i + j * cols
+    monkeypatch.setattr(tt, "two_phase_shard_id", two_phase)
+    assert _fails(TOPO_PINS)
+
+
+@pytest.mark.parametrize("kind", ["no_floor_of_full_state", "activations_not_counted", "weights_sharded_too", "sum_not_max"])
+def test_memory_model_mutants_are_caught(monkeypatch, kind):
+    def peak_memory(W, V, P, N):
+        if N < 1:
+            raise ValueError
+        W, V, P = Fraction(W), Fraction(V), Fraction(P)
+        a, b = W + V / N + P, W + V
+        if kind == "no_floor_of_full_state":
+            return W + V + P, a
+        if kind == "activations_not_counted":
+            return W + V + P, max(W + V / N, b)
+        if kind == "weights_sharded_too":
+            return W + V + P, max(W / N + V / N + P, b)
+        return W + V + P, a + b
+    monkeypatch.setattr(tt, "peak_memory", peak_memory)
+    assert _fails(TOPO_PINS)
+
+
+@pytest.mark.parametrize("kind", ["floor_pieces", "respects_nothing_but_overlaps"])
+def test_concat_partition_mutants_are_caught(monkeypatch, kind):
+    def concat_partition(total, parts, part):
+        piece = total // parts if kind == "floor_pieces" else -(-total // parts)
+        start = part * piece if kind == "floor_pieces" else max(0, min(part * piece, total) - 1)
+        return start, min(piece, total - start)
+    monkeypatch.setattr(tt, "concat_partition", concat_partition)
+    assert _fails(TOPO_PINS)
