@@ -261,6 +261,40 @@ int shard_reduce_sq_rows_cols(shard_plan_t* plan, int r, const float* x, float* 
                               shard_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Replica arrays (host only, integer arithmetic; the collectives themselves are the caller's).
+ * Replica ids are row-major over a rows x cols array: replica = row * cols + column.
+ *
+ * shard_partial_sharding (Section 5.2, "Partial sharding"): the rows of the array are independent
+ *   sharding groups and the columns all-reduce the groups' partial results.  For `replica`:
+ *   *group = its row; *shard_id = its column, i.e. the r to pass to shard_plan(.., N = cols, ..)'s
+ *   formatting and update calls; shard_group[cols] = the replicas of its row (its reduce-scatter and
+ *   all-gather partners, in shard-id order); reduce_group[rows] = the replicas of its column (all
+ *   hold the same shard id).  Any out pointer may be NULL.
+ * shard_two_phase_shard_id (Section 5.1): full sharding rows*cols ways by a reduce-scatter inside
+ *   every row, then inside every column; the final piece of replica (i, j), counted by position in
+ *   the data, is j * rows + i.
+ * shard_concat_partition (Section 5.2, "Batched communication operators"): a combined all-reduce
+ *   concatenates its inputs and cuts the concatenation into `parts` internal pieces of
+ *   ceil(total / parts) elements (the last ones shorter or empty), ignoring tensor boundaries.
+ * shard_peak_memory (Section 4.2, "Memory saving"): W weights, V auxiliary variables, P peak of
+ *   live activations and gradients, in any one unit: *replicated = W + V + P,
+ *   *sharded = max(W + V/N + P, W + V).
+ * shard_plan_peak_bytes: the same model on a plan, in bytes: W = total * weight_bytes,
+ *   V = total * aux_bytes (aux_bytes = bytes of all auxiliary variables per weight element, 8 for
+ *   Adam's two float32 moments, weight_bytes + aux_bytes <= 16), and V/N becomes S * aux_bytes,
+ *   padding included.
+ * Errors: SHARD_EINVAL (dimension < 1, rows * cols >= 2^31, replica or part out of range, negative
+ * size, NULL where a result is required).
+ */
+int shard_partial_sharding(int rows, int cols, int replica, int* group, int* shard_id, int* shard_group,
+                           int* reduce_group);
+int shard_two_phase_shard_id(int rows, int cols, int replica, int* shard_id);
+int shard_concat_partition(int64_t total, int parts, int part, int64_t* start, int64_t* length);
+int shard_peak_memory(double W, double V, double P, int N, double* replicated, double* sharded);
+int shard_plan_peak_bytes(const shard_plan_t* plan, int weight_bytes, int aux_bytes, int64_t P,
+                          int64_t* replicated, int64_t* sharded);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events recorded on the launch stream, for benchmarks.
  * shard_profile_enable(plan, 1) makes every later launch through this plan record an event
  * pair; shard_profile_read synchronises with the recorded events and returns, for one kernel

@@ -41,6 +41,8 @@ class LarsHP(C.Structure):
 
 _P = C.c_void_p
 _I64P = C.POINTER(C.c_int64)
+_IP = C.POINTER(C.c_int)
+_DP = C.POINTER(C.c_double)
 
 # name -> (restype, argtypes); mirrors include/shardupdate.h declaration by declaration
 SIGNATURES = {
@@ -66,6 +68,11 @@ SIGNATURES = {
     "shard_update_lars": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P, _P]),
     "shard_plan_rowcol_layout": (C.c_int, [_P, _I64P, _I64P, _I64P, _I64P]),
     "shard_reduce_sq_rows_cols": (C.c_int, [_P, C.c_int, _P, _P, _P, _P]),
+    "shard_partial_sharding": (C.c_int, [C.c_int, C.c_int, C.c_int, _IP, _IP, _IP, _IP]),
+    "shard_two_phase_shard_id": (C.c_int, [C.c_int, C.c_int, C.c_int, _IP]),
+    "shard_concat_partition": (C.c_int, [C.c_int64, C.c_int, C.c_int, _I64P, _I64P]),
+    "shard_peak_memory": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_int, _DP, _DP]),
+    "shard_plan_peak_bytes": (C.c_int, [_P, C.c_int, C.c_int, C.c_int64, _I64P, _I64P]),
     "shard_profile_enable": (C.c_int, [_P, C.c_int]),
     "shard_profile_read": (C.c_int, [_P, C.c_int, _I64P, C.POINTER(C.c_double)]),
     "shard_profile_reset": (C.c_int, [_P]),

@@ -313,3 +313,40 @@ def shard_profile_read(plan: Plan, kernel: str) -> Tuple[int, float]:
 
 def shard_profile_reset(plan: Plan) -> None:
     _check(lib().shard_profile_reset(plan.handle), "shard_profile_reset")
+
+
+# ---- replica arrays (host only) ---------------------------------------------------------------------
+
+def shard_partial_sharding(rows: int, cols: int, replica: int):
+    """(group, shard_id, shard_group[cols], reduce_group[rows]) of a replica in a rows x cols array."""
+    group, sid = C.c_int(), C.c_int()
+    sg, rg = (C.c_int * max(int(cols), 1))(), (C.c_int * max(int(rows), 1))()
+    _check(lib().shard_partial_sharding(int(rows), int(cols), int(replica), C.byref(group), C.byref(sid), sg, rg),
+           "shard_partial_sharding")
+    return group.value, sid.value, list(sg[: cols]), list(rg[: rows])
+
+
+def shard_two_phase_shard_id(rows: int, cols: int, replica: int) -> int:
+    sid = C.c_int()
+    _check(lib().shard_two_phase_shard_id(int(rows), int(cols), int(replica), C.byref(sid)), "shard_two_phase_shard_id")
+    return sid.value
+
+
+def shard_concat_partition(total: int, parts: int, part: int) -> Tuple[int, int]:
+    start, length = C.c_int64(), C.c_int64()
+    _check(lib().shard_concat_partition(int(total), int(parts), int(part), C.byref(start), C.byref(length)),
+           "shard_concat_partition")
+    return start.value, length.value
+
+
+def shard_peak_memory(W: float, V: float, P: float, N: int) -> Tuple[float, float]:
+    rep, sh = C.c_double(), C.c_double()
+    _check(lib().shard_peak_memory(float(W), float(V), float(P), int(N), C.byref(rep), C.byref(sh)), "shard_peak_memory")
+    return rep.value, sh.value
+
+
+def shard_plan_peak_bytes(plan: Plan, weight_bytes: int, aux_bytes: int, P: int) -> Tuple[int, int]:
+    rep, sh = C.c_int64(), C.c_int64()
+    _check(lib().shard_plan_peak_bytes(plan.handle, int(weight_bytes), int(aux_bytes), int(P), C.byref(rep),
+                                       C.byref(sh)), "shard_plan_peak_bytes")
+    return rep.value, sh.value

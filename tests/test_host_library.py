@@ -162,3 +162,50 @@ def test_row_plan_matches_oracle():
     assert lib().shard_plan_rows(1, (C.c_int64 * 1)(4), None, 2, 8, None, 0, C.byref(h)) == -1
     assert lib().shard_plan_rows(1, (C.c_int64 * 1)(4), (C.c_int64 * 1)(-1), 2, 8, None, 0, C.byref(h)) == -1
     assert lib().shard_plan_rows(1, (C.c_int64 * 1)(2 ** 40), (C.c_int64 * 1)(2 ** 40), 2, 8, None, 0, C.byref(h)) == -1
+
+
+def test_replica_array_arithmetic_matches_oracle():
+    from oracle import topology as topo
+    for rows, cols in [(1, 1), (1, 7), (7, 1), (2, 4), (3, 5), (32, 64)]:
+        for replica in sorted({0, 1 % (rows * cols), rows * cols // 2, rows * cols - 1}):
+            assert su.shard_partial_sharding(rows, cols, replica) == topo.partial_sharding(rows, cols, replica)
+            assert su.shard_two_phase_shard_id(rows, cols, replica) == topo.two_phase_shard_id(rows, cols, replica)
+    # the subgroup example of Section 2.1: devices 0-3 and 4-7
+    assert su.shard_partial_sharding(2, 4, 6)[2] == [4, 5, 6, 7]
+    for total, parts in [(0, 1), (0, 3), (1, 4), (10, 3), (13, 4), (5, 8), (2 ** 40 + 3, 2048)]:
+        for part in sorted({0, parts // 2, parts - 1}):
+            assert su.shard_concat_partition(total, parts, part) == topo.concat_partition(total, parts, part)
+    EINVAL = -1
+    i = C.c_int()
+    assert lib().shard_partial_sharding(2, 2, 4, None, None, None, None) == EINVAL
+    assert lib().shard_partial_sharding(0, 2, 0, None, None, None, None) == EINVAL
+    assert lib().shard_partial_sharding(2 ** 16, 2 ** 16, 0, None, None, None, None) == EINVAL
+    assert lib().shard_partial_sharding(2, 2, 3, None, None, None, None) == 0          # every out pointer is optional
+    assert lib().shard_two_phase_shard_id(2, 2, -1, C.byref(i)) == EINVAL
+    assert lib().shard_two_phase_shard_id(2, 2, 0, None) == EINVAL
+    assert lib().shard_concat_partition(-1, 2, 0, None, None) == EINVAL
+    assert lib().shard_concat_partition(4, 2, 2, None, None) == EINVAL
+
+
+def test_peak_memory_matches_oracle():
+    from oracle import topology as topo
+    for W, V, P, N in [(4, 8, 10, 4), (4, 8, 1, 8), (4, 0, 10, 16), (5, 10, 100, 1), (1344904432, 2689808864, 10 ** 9, 8)]:
+        want = topo.peak_memory(W, V, P, N)
+        got = su.shard_peak_memory(W, V, P, N)
+        assert got == pytest.approx((float(want[0]), float(want[1])), rel=1e-15)
+    assert lib().shard_peak_memory(1.0, 1.0, 1.0, 0, None, None) == -1
+    assert lib().shard_peak_memory(-1.0, 1.0, 1.0, 2, None, None) == -1
+    assert lib().shard_peak_memory(float("nan"), 1.0, 1.0, 2, None, None) == -1
+    for cfg in CONFIGS:
+        for N in cfg.replicas:
+            plan = su.shard_plan(cfg.numel, N, 8)
+            for wb, ab in [(4, 8), (4, 4), (2, 12)]:
+                assert su.shard_plan_peak_bytes(plan, wb, ab, 10 ** 9) == \
+                    topo.plan_peak_bytes(cfg.numel, make_plan(cfg.numel, N, 8).S, wb, ab, 10 ** 9)
+            plan.free()
+    p = su.shard_plan([10, 3], 4)
+    assert lib().shard_plan_peak_bytes(p.handle, 0, 8, 0, None, None) == -1
+    assert lib().shard_plan_peak_bytes(p.handle, 4, 16, 0, None, None) == -1
+    assert lib().shard_plan_peak_bytes(p.handle, 4, 8, -1, None, None) == -1
+    assert lib().shard_plan_peak_bytes(None, 4, 8, 0, None, None) == -1
+    p.free()
