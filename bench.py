@@ -198,6 +198,31 @@ def headline(args, torch, su, cfgs):
         "GBps": round(40 * S / (lamb_us * 1e-6) / 1e9, 1),
         "frac_of_hbm_peak": round(40 * S / (lamb_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
     }
+    # The same step as the paper runs it (Section 4.2, all-gather in bfloat16): the float32 update also
+    # emits bf16(w') into this replica's row of a bfloat16 gathered buffer, and unshard_format restores
+    # bfloat16 tensors for the forward pass.  Reported beside the float32 headline, never as `value`.
+    g16 = su.gathered_empty(plan, dtype=torch.bfloat16).normal_(0.0, cfg.weight_std, generator=wb.gen)
+    flat16 = torch.empty(cfg.total, dtype=torch.bfloat16, device="cuda")
+    full16, pos = [], 0
+    for n in cfg.numel:
+        full16.append(flat16[pos:pos + n])
+        pos += n
+    full16 = su.FullTensors(plan, full16)
+
+    def one_step_bf16():
+        state["t"] += 1
+        su.shard_format(plan, r, wb.full_g, wb.g)
+        su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, hp, state["t"], other_replicas_sumsq=wb.other,
+                             w_bf16_out=g16[r])
+        su.unshard_format(plan, g16, full16)
+
+    for _ in range(3):
+        one_step_bf16()
+    ms16, _ = _time_region(torch, one_step_bf16, args.steps)
+    bf16_gather = {"ms_per_step": round(ms16, 5), "params_per_s": wb.real / (ms16 * 1e-3),
+                   "what": "float32 LAMB update that also writes bf16(w'), bfloat16 gathered buffer and full tensors"}
+    del g16, flat16, full16
+
     out = {
         "metric": "shard weight-update params/s (340M LAMB, N=8, one replica's shard)",
         "value": wb.real / (ms_step * 1e-3),
@@ -213,6 +238,7 @@ def headline(args, torch, su, cfgs):
         "roofline": roof,
         "kernels": rooflines,
         "update_only": update_only,
+        "bf16_gather": bf16_gather,
         "wall_ms_per_step": round(wall_ms, 5),
     }
     wb.free()

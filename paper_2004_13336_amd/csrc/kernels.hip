@@ -49,6 +49,21 @@
 #ifndef SU_NT_UNSHARD
 #define SU_NT_UNSHARD 5
 #endif
+#ifndef SU_COPY_BLOCK
+#define SU_COPY_BLOCK 256     // threads per workgroup of the formatting kernels
+#endif
+// Units per thread of the formatting kernels, all loaded before the first store.  One replica's
+// formatting (a few hundred MB, partly served by the memory-side cache) measures fastest with 2;
+// the whole-model copies (unshard, all-replica formatting) with 1.
+#ifndef SU_FORMAT_UNROLL
+#define SU_FORMAT_UNROLL 2
+#endif
+#ifndef SU_UNSHARD_UNROLL
+#define SU_UNSHARD_UNROLL 1
+#endif
+#ifndef SU_FORMAT_ALL_UNROLL
+#define SU_FORMAT_ALL_UNROLL 1
+#endif
 #ifndef SU_P1_REVERSE
 #define SU_P1_REVERSE 0        // 1: LAMB phase 1 walks the chunk table from the end
 #endif
@@ -68,6 +83,7 @@ typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 constexpr int kUnroll = SU_UNROLL;
 constexpr int kFlatUnroll = SU_FLAT_UNROLL;
+constexpr int kCopyBlock = SU_COPY_BLOCK;
 
 // Four consecutive floats held in registers; moved with one 128-bit access.
 struct F4 {
@@ -235,8 +251,8 @@ __device__ __forceinline__ uint32_t convert(uint32_t b) {
   else return b << 16;
 }
 
-// Work items of the two formatting kernels are (replica, chunk, tile) triples: a chunk is cut into
-// tiles of kBlock units and every tile is one short-lived workgroup.  Many small workgroups,
+// Work items of the formatting kernels are (replica, chunk, tile) triples: a chunk is cut into
+// tiles of kCopyBlock * U units (U per thread) and every tile is one short-lived workgroup.  Many small workgroups,
 // dispatched in address order, keep the set of DRAM pages in flight compact, which measures
 // faster on MI355X than fewer workgroups that each loop over more data.  The table look-ups
 // (chunk -> variable -> pointer) of the tiles of one chunk hit the same cache lines.
@@ -248,43 +264,50 @@ __device__ __forceinline__ uint32_t convert(uint32_t b) {
 // Otherwise units that end at or before `whole` are moved whole, and (shard_format only) units
 // that start at or after `zero_from` and before `len` are written as zeros.  The one unit that
 // straddles the end of the variable, if any, is left to copy_tile's caller.
-template <typename Pol, int SRC, int DST, bool ALL, bool UNSHARD>
+template <typename Pol, int SRC, int DST, int U, bool ALL, bool UNSHARD>
 __device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src, typename ElemOf<DST>::type* dst,
                                            int whole, int zero_from, int len) {
   constexpr int UNIT = UnitOf<SRC, DST>::n;
-  uint32_t x[UNIT];
-  const int e = (int)threadIdx.x * UNIT;
-  if (ALL || e + UNIT <= whole) {
-    load_unit<Pol, SRC, UNIT>(src + e, x);
+  uint32_t x[U][UNIT];
 #pragma unroll
-    for (int j = 0; j < UNIT; ++j) x[j] = convert<SRC, DST>(x[j]);
-    store_unit<Pol, DST, UNIT>(dst + e, x);
-  } else if (!UNSHARD && e >= zero_from && e < len) {
+  for (int i = 0; i < U; ++i) {
+    const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
+    if (ALL || e + UNIT <= whole) load_unit<Pol, SRC, UNIT>(src + e, x[i]);
+  }
 #pragma unroll
-    for (int j = 0; j < UNIT; ++j) x[j] = 0u;
-    store_unit<Pol, DST, UNIT>(dst + e, x);
+  for (int i = 0; i < U; ++i) {
+    const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
+    if (ALL || e + UNIT <= whole) {
+#pragma unroll
+      for (int j = 0; j < UNIT; ++j) x[i][j] = convert<SRC, DST>(x[i][j]);
+      store_unit<Pol, DST, UNIT>(dst + e, x[i]);
+    } else if (!UNSHARD && e >= zero_from && e < len) {
+#pragma unroll
+      for (int j = 0; j < UNIT; ++j) x[i][j] = 0u;
+      store_unit<Pol, DST, UNIT>(dst + e, x[i]);
+    }
   }
 }
 
 // Moves tile `t` of a chunk.  shard_format: zero-padded piece of the flat variable -> packed shard
 // (all `len` slots written).  unshard_format: the `valid` real elements of a gathered piece -> flat
 // variable (padding dropped).  src and dst point at the chunk's first slot.
-template <typename Pol, int SRC, int DST, bool VEC, bool UNSHARD>
+template <typename Pol, int SRC, int DST, int U, bool VEC, bool UNSHARD>
 __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const typename ElemOf<SRC>::type* src,
                                           typename ElemOf<DST>::type* dst) {
   typedef typename ElemOf<DST>::type DstT;
   constexpr int UNIT = UnitOf<SRC, DST>::n;
-  constexpr int TILE = kBlock * UNIT;
+  constexpr int TILE = kCopyBlock * U * UNIT;
   const int base = t * TILE;
   if (base >= (UNSHARD ? cv.valid : cv.len)) return;
   if constexpr (VEC) {
     if (base + TILE <= cv.valid) {
-      copy_units<Pol, SRC, DST, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
+      copy_units<Pol, SRC, DST, U, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
       return;
     }
     const int whole = cv.valid / UNIT * UNIT;                  // slots covered by fully real units
     const int zero_from = (cv.valid + UNIT - 1) / UNIT * UNIT; // first unit that is all padding
-    copy_units<Pol, SRC, DST, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
+    copy_units<Pol, SRC, DST, U, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
     // the unit that straddles the end of the variable: real elements, then (shard_format) zeros
     if (whole != cv.valid && whole >= base && whole < base + TILE && (int)threadIdx.x < UNIT) {
       const int e = whole + threadIdx.x;
@@ -293,7 +316,7 @@ __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const type
     }
   } else {
     const int end = (UNSHARD ? cv.valid : cv.len) < base + TILE ? (UNSHARD ? cv.valid : cv.len) : base + TILE;
-    for (int e = base + threadIdx.x; e < end; e += kBlock)
+    for (int e = base + threadIdx.x; e < end; e += kCopyBlock)
       dst[e] = (DstT)((e < cv.valid) ? convert<SRC, DST>((uint32_t)src[e]) : 0u);
   }
 }
@@ -301,7 +324,7 @@ __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const type
 // UNSHARD = false: shard_format; `packed` is the output, shard r0 + replica goes to row `replica`.
 // UNSHARD = true : unshard_format; `packed` is the gathered buffer, r0 = 0.
 // blockIdx.x = (replica * n_chunks + chunk) * tiles_per_chunk + tile.
-template <typename Pol, int SRC, int DST, bool VEC, bool UNSHARD>
+template <typename Pol, int SRC, int DST, int U, bool VEC, bool UNSHARD>
 __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
                                               const void* const* __restrict__ ptrs, void* packed, int r0,
                                               int64_t row_stride, int n_chunks, int tiles_per_chunk) {
@@ -312,7 +335,7 @@ __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, 
   const int replica = item / n_chunks;
   const ChunkView cv = chunk_view(vars, chunks, item - replica * n_chunks, r0 + replica);
   // skip the pointer look-up for tiles with nothing to do (beyond a short chunk, or all padding)
-  constexpr int TILE = kBlock * UnitOf<SRC, DST>::n;
+  constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   if (tile * TILE >= (UNSHARD ? cv.valid : cv.len)) return;
   const void* ptr = ptrs[cv.var];
   // 128-bit accesses need this chunk's place in the full tensor on a 16-byte boundary (VEC already
@@ -323,38 +346,38 @@ __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, 
   if constexpr (UNSHARD) {
     const SrcT* src = (const SrcT*)packed + (int64_t)replica * row_stride + cv.shard0;
     DstT* dst = (DstT*)const_cast<void*>(ptr) + cv.flat0;
-    if (vec) copy_tile<Pol, SRC, DST, true, true>(cv, tile, src, dst);
-    else copy_tile<Pol, SRC, DST, false, true>(cv, tile, src, dst);
+    if (vec) copy_tile<Pol, SRC, DST, U, true, true>(cv, tile, src, dst);
+    else copy_tile<Pol, SRC, DST, U, false, true>(cv, tile, src, dst);
   } else {
     const SrcT* src = (const SrcT*)ptr + cv.flat0;      // not dereferenced where there is no real element
     DstT* dst = (DstT*)packed + (int64_t)replica * row_stride + cv.shard0;
-    if (vec) copy_tile<Pol, SRC, DST, true, false>(cv, tile, src, dst);
-    else copy_tile<Pol, SRC, DST, false, false>(cv, tile, src, dst);
+    if (vec) copy_tile<Pol, SRC, DST, U, true, false>(cv, tile, src, dst);
+    else copy_tile<Pol, SRC, DST, U, false, false>(cv, tile, src, dst);
   }
 }
 
 template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kBlock) void format_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __restrict__ vars,
                                                         const ChunkDesc* __restrict__ chunks,
                                                         const void* const* __restrict__ ptrs, void* out, int r0,
                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormat, SRC, DST, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
+  reformat_body<PolFormat, SRC, DST, SU_FORMAT_UNROLL, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kBlock) void format_all_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kCopyBlock) void format_all_kernel(const VarDesc* __restrict__ vars,
                                                             const ChunkDesc* __restrict__ chunks,
                                                             const void* const* __restrict__ ptrs, void* out,
                                                             int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormatAll, SRC, DST, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk);
+  reformat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kBlock) void unshard_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const void* const* __restrict__ ptrs, void* gathered,
                                                          int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolUnshard, SRC, DST, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
+  reformat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 // ---- element-wise optimizer arithmetic ------------------------------------------------------------
@@ -972,10 +995,11 @@ template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
                        bool vec, hipStream_t stream) {
   const int n_chunks = (int)p->chunks.size();
-  constexpr int TILE = kBlock * UnitOf<SRC, DST>::n;
+  constexpr int U = MODE == 0 ? SU_FORMAT_UNROLL : (MODE == 1 ? SU_UNSHARD_UNROLL : SU_FORMAT_ALL_UNROLL);
+  constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
-  // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31
-  const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kBlock);
+  // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31, and a tile is at least 1024 slots
+  const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kCopyBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   if constexpr (MODE == 2) {
