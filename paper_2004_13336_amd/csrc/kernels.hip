@@ -620,18 +620,23 @@ __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restri
   }
 }
 
-// One wavefront per variable: adds the variable's chunk sums in a fixed order (float64
-// accumulators), optionally adds the other replicas' table (the all-reduce stand-in).
+// One workgroup per variable: adds the variable's chunk sums in an order that depends only on the
+// chunk table (thread t takes chunks t, t + kBlock, ...; float64 accumulators; wavefront shuffles,
+// then the four wavefronts in order), optionally adds the other replicas' table (the all-reduce
+// stand-in).
+// (Folding this into phase 1, with the workgroup that finishes a variable's last chunk doing the
+// addition, was measured and rejected: publishing a chunk's sums to workgroups on other XCDs needs a
+// device-scope release, which on this multi-XCD part writes back the XCD's whole L2; with every
+// workgroup doing that, phase 1 ran 9x slower.)
 __global__ __launch_bounds__(kBlock) void norm_reduce_kernel(const VarDesc* __restrict__ vars,
                                                              const float* __restrict__ chunk_sums, int V,
                                                              const float* __restrict__ other, float* sums_out,
                                                              float* local_out) {
-  const int i = (blockIdx.x * kBlock + threadIdx.x) >> 6;    // uniform per wavefront
-  if (i >= V) return;
-  const int lane = threadIdx.x & 63;
+  __shared__ double part[2 * (kBlock / 64)];
+  const int i = blockIdx.x;
   const VarDesc vd = vars[i];
   double a = 0.0, b = 0.0;
-  for (int c = lane; c < vd.n_chunks; c += 64) {
+  for (int c = threadIdx.x; c < vd.n_chunks; c += kBlock) {
     a += (double)chunk_sums[2 * (int64_t)(vd.first_chunk + c)];
     b += (double)chunk_sums[2 * (int64_t)(vd.first_chunk + c) + 1];
   }
@@ -640,7 +645,20 @@ __global__ __launch_bounds__(kBlock) void norm_reduce_kernel(const VarDesc* __re
     a += __shfl_xor(a, s, 64);
     b += __shfl_xor(b, s, 64);
   }
-  if (lane == 0) {
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    part[2 * wave] = a;
+    part[2 * wave + 1] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = part[0];
+    b = part[1];
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) {
+      a += part[2 * w];
+      b += part[2 * w + 1];
+    }
     const float la = (float)a, lb = (float)b;
     if (local_out) {
       local_out[2 * i] = la;
@@ -1114,8 +1132,7 @@ hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_o
                               hipStream_t stream) {
   if (p->V == 0) return hipSuccess;
   ProfScope ps(p, SHARD_K_NORM_REDUCE, stream);
-  const int waves_per_block = kBlock / 64;
-  const dim3 grid((unsigned)((p->V + waves_per_block - 1) / waves_per_block));
+  const dim3 grid((unsigned)p->V);
   hipLaunchKernelGGL(norm_reduce_kernel, grid, dim3(kBlock), 0, stream, ws_at<VarDesc>(p, p->ws.vars),
                      ws_at<float>(p, p->ws.chunk_sums), p->V, other, sums_out, local_out);
   return hipGetLastError();
