@@ -2,7 +2,7 @@
 
 A plain, slow, numpy implementation of what the HIP library computes, written
 from the paper's description (Sections 2.2, 4.1, 4.2, 5.1, 5.2) and from the published
-definitions of Adam, momentum SGD, LAMB and LARS.  It shares no code with the HIP
+definitions of Adam, momentum SGD, LAMB, LARS and Adafactor.  It shares no code with the HIP
 path and must never be imported by it: only tests, the smoke check and the
 benchmark's cpu_baseline leg may use it.
 
@@ -22,6 +22,10 @@ from .optim import (  # noqa: F401
     lars_unsharded_step, lars_shard_partials, lars_shard_apply,
     rowcol_sumsq_unsharded, rowcol_sumsq_shard,
     VAR_NO_DECAY, VAR_NO_ADAPT,
+)
+from .adafactor import (  # noqa: F401
+    adafactor_schedule, adafactor_second_moment, adafactor_unsharded_step,
+    adafactor_shard_partials, adafactor_shard_moments, adafactor_shard_apply,
 )
 from .topology import (  # noqa: F401
     partial_sharding, two_phase_shard_id, concat_partition, peak_memory, plan_peak_bytes,

@@ -331,3 +331,126 @@ def test_concat_partition_mutants_are_caught(monkeypatch, kind):
         return start, min(piece, total - start)
     monkeypatch.setattr(tt, "concat_partition", concat_partition)
     assert _fails(TOPO_PINS)
+
+
+# ---- mutants of Adafactor ------------------------------------------------------------------------
+
+import oracle.adafactor as ada  # noqa: E402
+import test_oracle_adafactor as ta  # noqa: E402
+
+ADAFACTOR_PINS = [(ta.test_schedule_values, ()), (ta.test_two_by_two_matrix_by_hand, ()),
+                  (ta.test_vector_by_hand_with_clipping_on_the_second_step, ()),
+                  (ta.test_rank_one_gradient_first_step_is_a_sign_step, (1.0, 1.0)),
+                  (ta.test_rank_one_gradient_first_step_is_a_sign_step, (0.5, 0.5)),
+                  (ta.test_factored_estimate_keeps_the_row_and_column_sums, ()),
+                  (ta.test_update_size_and_invariances, ()), (ta.test_against_torch_adafactor_float64, (5,)),
+                  (ta.test_sharded_equals_unsharded, ([(9, 6), (5, 1), (4, 16)], 4, 8))]
+
+
+@pytest.mark.parametrize("kind", ["constant_beta2", "rho_uncapped", "rho_not_decaying", "beta2_exponent_sign"])
+def test_adafactor_schedule_mutants_are_caught(monkeypatch, kind):
+    def schedule(t, hp):
+        e = ada._hp(hp, "decay_exponent")
+        beta2 = f64(0.999) if kind == "constant_beta2" else f64(1.0) - f64(t) ** (e if kind == "beta2_exponent_sign" else -e)
+        rho = f64(1.0) / np.sqrt(f64(t)) if kind == "rho_uncapped" else min(ada._hp(hp, "max_rho"), f64(1.0) / np.sqrt(f64(t)))
+        if kind == "rho_not_decaying":
+            rho = ada._hp(hp, "max_rho")
+        return beta2, rho
+    monkeypatch.setattr(ada, "adafactor_schedule", schedule)
+    monkeypatch.setattr(ta, "adafactor_schedule", schedule)
+    assert _fails(ADAFACTOR_PINS)
+
+
+@pytest.mark.parametrize("kind", ["no_division_by_sum", "mean_instead_of_sum", "eps1_dropped", "rows_and_columns_swapped",
+                                  "eps1_added_once_per_row"])
+def test_adafactor_second_moment_mutants_are_caught(monkeypatch, kind):
+    def second_moment(G, R, C, beta2, eps1):
+        G = np.asarray(G, f64)
+        term = G * G + (0.0 if kind == "eps1_dropped" else eps1)
+        if G.shape[1] == 1:
+            R = beta2 * R + (1.0 - beta2) * term[:, 0]
+            return R, C, R[:, None]
+        if kind == "rows_and_columns_swapped" and G.shape[0] == G.shape[1]:
+            R = beta2 * R + (1.0 - beta2) * term.sum(axis=0)
+            C = beta2 * C + (1.0 - beta2) * term.sum(axis=1)
+        else:
+            rs = (G * G).sum(axis=1) + eps1 if kind == "eps1_added_once_per_row" else term.sum(axis=1)
+            R = beta2 * R + (1.0 - beta2) * rs
+            C = beta2 * C + (1.0 - beta2) * term.sum(axis=0)
+        if kind == "no_division_by_sum":
+            return R, C, np.outer(R, C)
+        if kind == "mean_instead_of_sum":
+            return R, C, np.outer(R, C) / R.mean()
+        return R, C, np.outer(R, C) / R.sum()
+    monkeypatch.setattr(ada, "adafactor_second_moment", second_moment)
+    monkeypatch.setattr(ta, "adafactor_second_moment", second_moment)
+    pins = ADAFACTOR_PINS
+    if kind == "eps1_added_once_per_row":            # only visible where eps1 matters: make it large
+        pins = [(_eps1_counts_every_element, ())]
+    assert _fails(pins)
+
+
+def _eps1_counts_every_element():
+    # with eps1 far above g^2 the row term is cols * eps1 and the column term rows * eps1
+    G = np.zeros((3, 5))
+    R, C, _ = ada.adafactor_second_moment(G, np.zeros(3), np.zeros(5), 0.0, 2.0)
+    assert R.tolist() == [10.0] * 3 and C.tolist() == [6.0] * 5
+
+
+def test_eps1_counts_every_element():
+    _eps1_counts_every_element()
+
+
+@pytest.mark.parametrize("kind", ["no_eps2_floor", "clip_with_min", "rms_is_a_norm", "sign", "no_clipping",
+                                  "step_not_relative", "rms_of_new_weights"])
+def test_adafactor_step_mutants_are_caught(monkeypatch, kind):
+    def step(shapes, ws, gs, Rs, Cs, hp, t):
+        beta2, rho = ada.adafactor_schedule(t, hp)
+        eps1, eps2, d = ada._hp(hp, "eps1"), ada._hp(hp, "eps2"), ada._hp(hp, "clip_threshold")
+        out_w, out_R, out_C = [], [], []
+        for (rows, cols), w, g, R, C in zip(shapes, ws, gs, Rs, Cs):
+            n = rows * cols
+            if n == 0:
+                out_w.append(np.asarray(w, np.float32).copy()); out_R.append(np.asarray(R, np.float32).copy())
+                out_C.append(np.asarray(C, np.float32).copy())
+                continue
+            X, G = ada._up(w).reshape(rows, cols), ada._up(g).reshape(rows, cols)
+            R, C, Vhat = ada.adafactor_second_moment(G, ada._up(R), ada._up(C), beta2, eps1)
+            U = G / np.sqrt(Vhat)
+            rms_u = np.sqrt(np.sum(U * U)) if kind == "rms_is_a_norm" else np.sqrt(np.sum(U * U) / n)
+            if kind == "clip_with_min":
+                U_hat = U / min(f64(1.0), rms_u / d)
+            elif kind == "no_clipping":
+                U_hat = U
+            else:
+                U_hat = U / max(f64(1.0), rms_u / d)
+            rms_x = np.sqrt(np.sum(X * X) / n)
+            alpha = (rms_x if kind == "no_eps2_floor" else max(eps2, rms_x)) * rho
+            if kind == "step_not_relative":
+                alpha = rho
+            X_new = X + alpha * U_hat if kind == "sign" else X - alpha * U_hat
+            if kind == "rms_of_new_weights":
+                X_new = X - max(eps2, np.sqrt(np.sum(X_new * X_new) / n)) * rho * U_hat
+            out_w.append(X_new.reshape(-1).astype(np.float32)); out_R.append(R.astype(np.float32)); out_C.append(C.astype(np.float32))
+        return out_w, out_R, out_C
+    monkeypatch.setattr(ta, "adafactor_unsharded_step", step)
+    assert _fails(ADAFACTOR_PINS)
+
+
+@pytest.mark.parametrize("kind", ["forgets_the_row_mask", "sum_R_without_decay"])
+def test_adafactor_sharding_mutants_are_caught(monkeypatch, kind):
+    if kind == "forgets_the_row_mask":
+        def piece(plan, r, i, x64):
+            Lr, cols = plan.Lr[i], plan.cols[i]
+            return x64[plan.off[i]:plan.off[i] + Lr * cols].reshape(Lr, cols), np.ones(Lr, bool)
+        monkeypatch.setattr(ada, "_piece", piece)
+    else:
+        orig = ada.adafactor_shard_partials
+
+        def partials(plan, r, w, g, R_rows, hp):
+            a, b, table = orig(plan, r, w, g, R_rows, hp)
+            table[:, 1] = 0.0                         # the old row state's sum is left out of the all-reduce
+            return a, b, table
+        monkeypatch.setattr(ta, "adafactor_shard_partials", partials)
+    assert _fails([(ta.test_sharded_equals_unsharded, ([(9, 6), (5, 1), (4, 16)], 4, 8)),
+                   (ta.test_sharded_equals_unsharded, ([(10, 3), (0, 5), (7, 1), (3, 0), (1, 8)], 3, 1))])
