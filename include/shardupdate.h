@@ -72,7 +72,8 @@ enum {
   SHARD_K_FORMAT = 0, SHARD_K_UNSHARD = 1, SHARD_K_ADAM = 2, SHARD_K_MOMENTUM = 3,
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
   SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9, SHARD_K_ROWCOL_P1 = 10, SHARD_K_ROWCOL_P2 = 11,
-  SHARD_K_COUNT = 12
+  SHARD_K_ADAFACTOR_STATE = 12, SHARD_K_ADAFACTOR_USQ = 13, SHARD_K_ADAFACTOR_APPLY = 14,
+  SHARD_K_COUNT = 15
 };
 
 const char* shard_strerror(int status);
@@ -259,6 +260,55 @@ int shard_plan_rowcol_layout(const shard_plan_t* plan, int64_t* row_off, int64_t
 
 int shard_reduce_sq_rows_cols(shard_plan_t* plan, int r, const float* x, float* row_out, float* col_out,
                               shard_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Adafactor on a row plan: an optimizer whose update reduces along rows and along columns (named in
+ * Section 3, "Non-elementwise optimizers"; sharded as Section 4.1, "Non-elementwise operators",
+ * prescribes: local reduces with the padding masked by position, an all-reduce of the partial
+ * results, then element-wise work).  Variable i is a rows_i x cols_i matrix with Lr_i rows on this
+ * replica; step t >= 1:
+ *     beta2 = 1 - t^(-decay_exponent),  rho = min(max_rho, 1/sqrt(t))
+ *     R_k = beta2 R_k + (1-beta2) sum_j (g_kj^2 + eps1)          row state, this replica's rows
+ *     C_j = beta2 C_j + (1-beta2) sum_k (g_kj^2 + eps1)          column state, sums over ALL rows, same on all replicas
+ *     Vhat_kj = R_k C_j / sum_k R_k;   U = G / sqrt(Vhat);   Uhat = U / max(1, RMS(U) / clip_threshold)
+ *     X -= max(eps2, RMS(X)) * rho * Uhat                        RMS over the whole variable
+ *   A variable with cols_i == 1 is a vector: R holds the unfactored second moment, Vhat = R, and its
+ *   slot of C is never touched.  No momentum, no weight decay; variable flags are ignored.
+ * State (device, float32): R [total_rows] laid out by row_off, C [total_cols] laid out by col_off
+ * (shard_plan_rowcol_layout); both start at zero.  Padded rows keep R = 0; padded slots of w are not
+ * touched.  Two all-reduces separate three local phases:
+ *   shard_update_adafactor_partials: reads w, g, R.  row_sq_out [total_rows]: sum over columns of g^2
+ *     per row of the piece (0 for padded rows), stays local.  col_sq_out [total_cols]: sum over this
+ *     replica's real rows of g^2 per column.  table_out [V][2]: {sum of w^2 over real elements, sum of
+ *     R over real rows}.  The caller all-reduces (adds over replicas) col_sq_out and table_out.
+ *   shard_update_adafactor_moments: updates R and C in place from row_sq (local) and the all-reduced
+ *     col_sq_global and table_global, keeps the factors of 1/sqrt(Vhat) in the plan's workspace and
+ *     writes u_sumsq_out [V] = this replica's sum of U^2 over real elements.  The caller all-reduces it.
+ *   shard_update_adafactor_apply: updates w (and writes bf16(w') to w_bf16_out, if not NULL) from the
+ *     factors phase 2 left in the workspace; must follow the moments call of the same step on the same
+ *     plan, with the same hp and step.
+ *   shard_update_adafactor: all three; other_col_sq [total_cols], other_table [V][2], other_u_sumsq [V]
+ *     (each may be NULL = zeros) are added to the local results in place of the all-reduces.
+ * Requirements: a bound row plan; eps1 > 0, eps2 >= 0, clip_threshold > 0, decay_exponent > 0,
+ * max_rho > 0, step >= 1 (SHARD_EINVAL otherwise); w and g 16-byte aligned.  Summation orders are fixed.
+ */
+typedef struct { float eps1, eps2, clip_threshold, decay_exponent, max_rho; } shard_adafactor_hp;
+
+int shard_update_adafactor_partials(shard_plan_t* plan, int r, const float* w, const float* g, const float* R,
+                                    float* row_sq_out, float* col_sq_out, float* table_out, shard_stream_t stream);
+
+int shard_update_adafactor_moments(shard_plan_t* plan, int r, const float* g, float* R, float* C, const float* row_sq,
+                                   const float* col_sq_global, const float* table_global,
+                                   const shard_adafactor_hp* hp, int64_t step, float* u_sumsq_out,
+                                   shard_stream_t stream);
+
+int shard_update_adafactor_apply(shard_plan_t* plan, int r, float* w, const float* g, const float* table_global,
+                                 const float* u_sumsq_global, void* w_bf16_out, const shard_adafactor_hp* hp,
+                                 int64_t step, shard_stream_t stream);
+
+int shard_update_adafactor(shard_plan_t* plan, int r, float* w, const float* g, float* R, float* C, void* w_bf16_out,
+                           const shard_adafactor_hp* hp, int64_t step, const float* other_col_sq,
+                           const float* other_table, const float* other_u_sumsq, shard_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Replica arrays (host only, integer arithmetic; the collectives themselves are the caller's).

@@ -39,6 +39,11 @@ class LarsHP(C.Structure):
                 ("eps", C.c_float)]
 
 
+class AdafactorHP(C.Structure):
+    _fields_ = [("eps1", C.c_float), ("eps2", C.c_float), ("clip_threshold", C.c_float),
+                ("decay_exponent", C.c_float), ("max_rho", C.c_float)]
+
+
 _P = C.c_void_p
 _I64P = C.POINTER(C.c_int64)
 _IP = C.POINTER(C.c_int)
@@ -68,6 +73,10 @@ SIGNATURES = {
     "shard_update_lars": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LarsHP), _P, _P, _P]),
     "shard_plan_rowcol_layout": (C.c_int, [_P, _I64P, _I64P, _I64P, _I64P]),
     "shard_reduce_sq_rows_cols": (C.c_int, [_P, C.c_int, _P, _P, _P, _P]),
+    "shard_update_adafactor_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, _P, _P]),
+    "shard_update_adafactor_moments": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, _P, C.POINTER(AdafactorHP), C.c_int64, _P, _P]),
+    "shard_update_adafactor_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(AdafactorHP), C.c_int64, _P]),
+    "shard_update_adafactor": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(AdafactorHP), C.c_int64, _P, _P, _P, _P]),
     "shard_partial_sharding": (C.c_int, [C.c_int, C.c_int, C.c_int, _IP, _IP, _IP, _IP]),
     "shard_two_phase_shard_id": (C.c_int, [C.c_int, C.c_int, C.c_int, _IP]),
     "shard_concat_partition": (C.c_int, [C.c_int64, C.c_int, C.c_int, _I64P, _I64P]),

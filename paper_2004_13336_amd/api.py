@@ -11,12 +11,13 @@ from typing import Dict, Optional, Sequence, Tuple
 
 import torch
 
-from ._lib import AdamHP, LambHP, LarsHP, MomentumHP, ShardError, lib
+from ._lib import AdafactorHP, AdamHP, LambHP, LarsHP, MomentumHP, ShardError, lib
 
 SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
-              "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11}
+              "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11,
+              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -298,6 +299,61 @@ def shard_reduce_sq_rows_cols(plan: Plan, r: int, x, row_out, col_out, stream=No
                                            _dev(row_out, total_rows, f, "row_out"),
                                            _dev(col_out, total_cols, f, "col_out"), _stream(stream)),
            "shard_reduce_sq_rows_cols")
+
+
+ADAFACTOR_DEFAULTS = {"eps1": 1e-30, "eps2": 1e-3, "clip_threshold": 1.0, "decay_exponent": 0.8, "max_rho": 1e-2}
+
+
+def _adafactor_hp(hp: Dict[str, float]):
+    return AdafactorHP(**{name: float(hp.get(name, ADAFACTOR_DEFAULTS[name])) for name, _ in AdafactorHP._fields_})
+
+
+def shard_update_adafactor_partials(plan: Plan, r: int, w, g, R, row_sq_out, col_sq_out, table_out, stream=None):
+    f = torch.float32
+    _, _, total_rows, total_cols = shard_plan_rowcol_layout(plan)
+    _check(lib().shard_update_adafactor_partials(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                                 _dev(R, total_rows, f, "R"), _dev(row_sq_out, total_rows, f, "row_sq_out"),
+                                                 _dev(col_sq_out, total_cols, f, "col_sq_out"),
+                                                 _dev(table_out, 2 * plan.V, f, "table_out"), _stream(stream)),
+           "shard_update_adafactor_partials")
+
+
+def shard_update_adafactor_moments(plan: Plan, r: int, g, R, Cst, row_sq, col_sq_global, table_global, hp, step: int,
+                                   u_sumsq_out, stream=None):
+    f = torch.float32
+    _, _, total_rows, total_cols = shard_plan_rowcol_layout(plan)
+    _check(lib().shard_update_adafactor_moments(plan.handle, int(r), _dev(g, plan.S, f, "g"), _dev(R, total_rows, f, "R"),
+                                                _dev(Cst, total_cols, f, "C"), _dev(row_sq, total_rows, f, "row_sq"),
+                                                _dev(col_sq_global, total_cols, f, "col_sq_global"),
+                                                _dev(table_global, 2 * plan.V, f, "table_global"),
+                                                C.byref(_adafactor_hp(hp)), int(step),
+                                                _dev(u_sumsq_out, plan.V, f, "u_sumsq_out"), _stream(stream)),
+           "shard_update_adafactor_moments")
+
+
+def shard_update_adafactor_apply(plan: Plan, r: int, w, g, table_global, u_sumsq_global, hp, step: int,
+                                 w_bf16_out=None, stream=None):
+    f = torch.float32
+    _check(lib().shard_update_adafactor_apply(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                              _dev(table_global, 2 * plan.V, f, "table_global"),
+                                              _dev(u_sumsq_global, plan.V, f, "u_sumsq_global"),
+                                              _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                              C.byref(_adafactor_hp(hp)), int(step), _stream(stream)),
+           "shard_update_adafactor_apply")
+
+
+def shard_update_adafactor(plan: Plan, r: int, w, g, R, Cst, hp, step: int, other_col_sq=None, other_table=None,
+                           other_u_sumsq=None, w_bf16_out=None, stream=None):
+    f = torch.float32
+    _, _, total_rows, total_cols = shard_plan_rowcol_layout(plan)
+    _check(lib().shard_update_adafactor(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                        _dev(R, total_rows, f, "R"), _dev(Cst, total_cols, f, "C"),
+                                        _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                        C.byref(_adafactor_hp(hp)), int(step),
+                                        _dev(other_col_sq, total_cols, f, "other_col_sq"),
+                                        _dev(other_table, 2 * plan.V, f, "other_table"),
+                                        _dev(other_u_sumsq, plan.V, f, "other_u_sumsq"), _stream(stream)),
+           "shard_update_adafactor")
 
 
 def shard_profile_enable(plan: Plan, on: bool) -> None:

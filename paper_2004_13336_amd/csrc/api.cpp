@@ -92,7 +92,33 @@ const char* const kKernelNames[SHARD_K_COUNT] = {
     "format_kernel", "unshard_kernel", "adam_kernel", "momentum_kernel",
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
     "lars_p1_kernel", "lars_p2_kernel", "rowcol_p1_kernel", "rowcol_p2_kernel",
+    "adafactor_state_kernel", "adafactor_usq_kernel", "adafactor_apply_kernel",
 };
+
+// Step-dependent constants of Adafactor, taken in double and rounded once.
+int fold_adafactor(const shard_adafactor_hp* hp, int64_t step, AdafactorK* k) {
+  if (hp == nullptr || step < 1) return SHARD_EINVAL;
+  if (!(hp->eps1 > 0.0f) || !(hp->eps2 >= 0.0f) || !(hp->clip_threshold > 0.0f) || !(hp->decay_exponent > 0.0f) ||
+      !(hp->max_rho > 0.0f) || !std::isfinite(hp->eps1) || !std::isfinite(hp->eps2) ||
+      !std::isfinite(hp->clip_threshold) || !std::isfinite(hp->decay_exponent) || !std::isfinite(hp->max_rho))
+    return SHARD_EINVAL;
+  const double t = (double)step;
+  const double one_minus = std::pow(t, -(double)hp->decay_exponent);       // 1 - beta2
+  const double inv_sqrt_t = 1.0 / std::sqrt(t);
+  k->beta2 = (float)(1.0 - one_minus);
+  k->omb2 = (float)one_minus;
+  k->rho = (float)((double)hp->max_rho < inv_sqrt_t ? (double)hp->max_rho : inv_sqrt_t);
+  k->eps1 = hp->eps1;
+  k->eps2 = hp->eps2;
+  k->inv_clip = (float)(1.0 / (double)hp->clip_threshold);
+  return SHARD_OK;
+}
+
+int check_row_plan(const shard_plan_t* p, int r) {
+  const int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  return p->row_plan ? SHARD_OK : SHARD_EINVAL;
+}
 
 int fold_lars(const shard_lars_hp* hp, LarsK* k) {
   if (hp == nullptr) return SHARD_EINVAL;
@@ -434,6 +460,73 @@ int shard_reduce_sq_rows_cols(shard_plan_t* p, int r, const float* x, float* row
   if (p->rc_total_rows > 0 && (rc = check_shard_ptr(row_out)) != SHARD_OK) return rc;
   if (p->rc_total_cols > 0 && (rc = check_shard_ptr(col_out)) != SHARD_OK) return rc;
   return hip_status(launch_rowcol_sumsq(p, r, x, row_out, col_out, as_stream(stream)));
+}
+
+int shard_update_adafactor_partials(shard_plan_t* p, int r, const float* w, const float* g, const float* R,
+                                    float* row_sq_out, float* col_sq_out, float* table_out, shard_stream_t stream) {
+  int rc = check_row_plan(p, r);
+  if (rc != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if (table_out == nullptr) return SHARD_EINVAL;
+  if ((p->rc_total_rows > 0 && (R == nullptr || row_sq_out == nullptr)) || (p->rc_total_cols > 0 && col_sq_out == nullptr))
+    return SHARD_EINVAL;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK)) return rc;
+  return hip_status(launch_adafactor_partials(p, r, w, g, R, nullptr, nullptr, row_sq_out, col_sq_out, table_out,
+                                              as_stream(stream)));
+}
+
+int shard_update_adafactor_moments(shard_plan_t* p, int r, const float* g, float* R, float* C, const float* row_sq,
+                                   const float* col_sq_global, const float* table_global,
+                                   const shard_adafactor_hp* hp, int64_t step, float* u_sumsq_out,
+                                   shard_stream_t stream) {
+  int rc = check_row_plan(p, r);
+  if (rc != SHARD_OK) return rc;
+  AdafactorK k;
+  if ((rc = fold_adafactor(hp, step, &k)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if (table_global == nullptr || u_sumsq_out == nullptr) return SHARD_EINVAL;
+  if ((p->rc_total_rows > 0 && (R == nullptr || row_sq == nullptr)) ||
+      (p->rc_total_cols > 0 && (C == nullptr || col_sq_global == nullptr)))
+    return SHARD_EINVAL;
+  if (p->S > 0 && (rc = check_shard_ptr(g)) != SHARD_OK) return rc;
+  return hip_status(launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq_global, table_global, k, nullptr,
+                                             u_sumsq_out, nullptr, as_stream(stream)));
+}
+
+int shard_update_adafactor_apply(shard_plan_t* p, int r, float* w, const float* g, const float* table_global,
+                                 const float* u_sumsq_global, void* w_bf16_out, const shard_adafactor_hp* hp,
+                                 int64_t step, shard_stream_t stream) {
+  int rc = check_row_plan(p, r);
+  if (rc != SHARD_OK) return rc;
+  AdafactorK k;
+  if ((rc = fold_adafactor(hp, step, &k)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if (table_global == nullptr || u_sumsq_global == nullptr) return SHARD_EINVAL;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK) return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  return hip_status(launch_adafactor_apply(p, r, w, g, table_global, u_sumsq_global, w_bf16_out, k, as_stream(stream)));
+}
+
+int shard_update_adafactor(shard_plan_t* p, int r, float* w, const float* g, float* R, float* C, void* w_bf16_out,
+                           const shard_adafactor_hp* hp, int64_t step, const float* other_col_sq,
+                           const float* other_table, const float* other_u_sumsq, shard_stream_t stream) {
+  int rc = check_row_plan(p, r);
+  if (rc != SHARD_OK) return rc;
+  AdafactorK k;
+  if ((rc = fold_adafactor(hp, step, &k)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((p->rc_total_rows > 0 && R == nullptr) || (p->rc_total_cols > 0 && C == nullptr)) return SHARD_EINVAL;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK)) return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  float* row_sq = reinterpret_cast<float*>(p->ws.base + p->ws.af_rowsq);
+  float* col_sq = reinterpret_cast<float*>(p->ws.base + p->ws.af_colsq);
+  float* table = reinterpret_cast<float*>(p->ws.base + p->ws.af_table);
+  float* usq = reinterpret_cast<float*>(p->ws.base + p->ws.af_usq);
+  hipError_t e = launch_adafactor_partials(p, r, w, g, R, other_col_sq, other_table, row_sq, col_sq, table, s);
+  if (e == hipSuccess) e = launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq, table, k, other_u_sumsq, nullptr, usq, s);
+  if (e == hipSuccess) e = launch_adafactor_apply(p, r, w, g, table, usq, w_bf16_out, k, s);
+  return hip_status(e);
 }
 
 int shard_profile_enable(shard_plan_t* p, int on) {

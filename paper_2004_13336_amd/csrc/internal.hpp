@@ -51,9 +51,10 @@ struct RowColVar {
   int32_t n_rb;       // row blocks
   int32_t n_ct;       // column tiles
   int32_t vec;        // 1: rows start on 16-byte boundaries, threads own 4 adjacent columns
-  int32_t reserved;
+  int32_t first_item; // this variable's work items are [first_item, first_item + n_rb * n_ct)
+  int64_t L;          // slots of the piece in the packed shard (>= Lr * cols: alignment tail)
 };
-static_assert(sizeof(RowColVar) == 80, "RowColVar layout");
+static_assert(sizeof(RowColVar) == 88, "RowColVar layout");
 struct RowColItem {
   int32_t var, rb, ct, reserved;
 };
@@ -78,6 +79,10 @@ struct MomentumK {
 struct LarsK {
   float mu, lr, wd, trust, eps;
 };
+// Adafactor, step t: beta2 = 1 - t^-decay_exponent, omb2 = t^-decay_exponent, rho = min(max_rho, 1/sqrt(t))
+struct AdafactorK {
+  float beta2, omb2, rho, eps1, eps2, inv_clip;
+};
 
 // ---- the plan --------------------------------------------------------------------------------
 
@@ -87,6 +92,10 @@ struct Workspace {
   // byte offsets inside base
   size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
   size_t rc_vars = 0, rc_items = 0, rc_colpart = 0, rc_rowpart = 0;   // row plans only
+  // Adafactor (row plans only): per-item partial sums, per-variable scalars, the factors of 1/sqrt(Vhat),
+  // and the tables the fused call keeps between its phases
+  size_t af_wpart = 0, af_upart = 0, af_sumr = 0, af_inv_r = 0, af_inv_c = 0;
+  size_t af_rowsq = 0, af_colsq = 0, af_table = 0, af_usq = 0;
 };
 
 struct ProfRecord {
@@ -165,6 +174,19 @@ hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, floa
 // a fixed order into row_out [sum Lr] and col_out [sum cols].
 hipError_t launch_rowcol_sumsq(shard_plan_t* p, int r, const float* x, float* row_out, float* col_out,
                                hipStream_t stream);
+
+// Adafactor on a row plan (rowplan.hip).  Phase 1: row sums and column sums of g^2, and per variable
+// {sum w^2, sum of the old row state}; other_* (nullable) are added (all-reduce stand-ins).
+hipError_t launch_adafactor_partials(shard_plan_t* p, int r, const float* w, const float* g, const float* R,
+                                     const float* other_col, const float* other_table, float* row_sq, float* col_sq,
+                                     float* table, hipStream_t stream);
+// Phase 2: new row/column state, the factors of 1/sqrt(Vhat) (kept in the workspace), per-variable sum of U^2.
+hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, float* R, float* C, const float* row_sq,
+                                    const float* col_sq_global, const float* table_global, const AdafactorK& k,
+                                    const float* other_usq, float* usq_local, float* usq_total, hipStream_t stream);
+// Phase 3: the weight update, from the factors phase 2 left in the workspace.
+hipError_t launch_adafactor_apply(shard_plan_t* p, int r, float* w, const float* g, const float* table_global,
+                                  const float* usq_global, void* w16, const AdafactorK& k, hipStream_t stream);
 
 // RAII helper: records an event pair around a launch when profiling is on.
 struct ProfScope {

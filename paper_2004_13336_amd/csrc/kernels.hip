@@ -17,7 +17,7 @@
 // arithmetic per element.
 #include <type_traits>
 
-#include "internal.hpp"
+#include "device_common.hpp"
 
 #ifndef SU_UNROLL
 #define SU_UNROLL 4        // LAMB kernels: 128-bit accesses per thread per stream in flight
@@ -77,23 +77,10 @@
 namespace su {
 namespace {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u2 __attribute__((ext_vector_type(2)));
-
 constexpr int kUnroll = SU_UNROLL;
 constexpr int kFlatUnroll = SU_FLAT_UNROLL;
 constexpr int kCopyBlock = SU_COPY_BLOCK;
 
-// Four consecutive floats held in registers; moved with one 128-bit access.
-struct F4 {
-  float x, y, z, w;
-};
-
-template <int MASK>
-struct Policy {
-  static constexpr bool RO = (MASK & 4) != 0, RW = (MASK & 2) != 0, ST = (MASK & 1) != 0;
-};
 typedef Policy<SU_NT_ADAM> PolAdam;
 typedef Policy<SU_NT_MOMENTUM> PolMomentum;
 typedef Policy<SU_NT_LAMB> PolLamb;
@@ -101,38 +88,6 @@ typedef Policy<SU_NT_LARS> PolLars;
 typedef Policy<SU_NT_FORMAT> PolFormat;
 typedef Policy<SU_NT_UNSHARD> PolUnshard;
 typedef Policy<SU_NT_FORMAT_ALL> PolFormatAll;
-
-template <bool NT, typename T>
-__device__ __forceinline__ T ld(const T* p) {
-  if constexpr (NT) return __builtin_nontemporal_load(p);
-  else return *p;
-}
-template <bool NT, typename T>
-__device__ __forceinline__ void st(T* p, T x) {
-  if constexpr (NT) __builtin_nontemporal_store(x, p);
-  else *p = x;
-}
-template <bool NT>
-__device__ __forceinline__ F4 ld4(const float* p) {
-  const f4 t = ld<NT>((const f4*)p);
-  return F4{t.x, t.y, t.z, t.w};
-}
-template <bool NT>
-__device__ __forceinline__ void st4(float* p, const F4& a) {
-  f4 t;
-  t.x = a.x; t.y = a.y; t.z = a.z; t.w = a.w;
-  st<NT>((f4*)p, t);
-}
-
-// ---- bfloat16 ---------------------------------------------------------------------------------
-// Round to nearest, ties to even, on the bit pattern; NaN keeps sign and upper payload and gets
-// the quiet bit.
-__device__ __forceinline__ uint32_t bf16_from_f32_bits(uint32_t b) {
-  const uint32_t rounded = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
-  const uint32_t quiet = (b >> 16) | 0x0040u;
-  return ((b & 0x7FFFFFFFu) > 0x7F800000u) ? quiet : rounded;
-}
-__device__ __forceinline__ uint32_t bf16_of(float x) { return bf16_from_f32_bits(__float_as_uint(x)); }
 
 // ---- pieces shared by the table-driven kernels ----------------------------------------------------
 
@@ -408,14 +363,6 @@ __device__ __forceinline__ void lamb_moments(float g, float& m, float& v, const 
 __device__ __forceinline__ float lamb_dir(float w, float m, float v, float wd, const AdamK& k) {
   const float denom = __builtin_amdgcn_sqrtf(v * k.rbc2) + k.eps;
   return fmaf(wd, w, (m * k.rbc1) * __builtin_amdgcn_rcpf(denom));
-}
-
-template <bool NT>
-__device__ __forceinline__ void store_bf16x4(uint16_t* p, const F4& w) {
-  u2 o;
-  o.x = bf16_of(w.x) | (bf16_of(w.y) << 16);
-  o.y = bf16_of(w.z) | (bf16_of(w.w) << 16);
-  st<NT>((u2*)p, o);
 }
 
 // ---- flat kernels: Adam and momentum ---------------------------------------------------------------
@@ -869,91 +816,6 @@ __global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restri
   }
 }
 
-// ---- row / column sums of squares on a row plan ----------------------------------------------------
-// One pass over x.  A workgroup takes kRowBlock rows x one column tile of one variable's piece: every
-// thread owns 4 adjacent columns (1 where the row length is not a multiple of 4), walks down the
-// rows in batches of kRowBatch independent loads, keeps its columns' sums in registers and parks its
-// per-row sums in LDS, which the four wavefronts then reduce row by row.  Rows past the end of the
-// full matrix are skipped (Section 4.1: padded positions contribute the identity).  Partial results
-// go to the workspace; rowcol_p2_kernel adds them in a fixed order.
-#ifndef SU_NT_ROWCOL
-#define SU_NT_ROWCOL 1     // 1: non-temporal loads of x
-#endif
-constexpr int kRowBatch = 8;
-
-__global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __restrict__ vars,
-                                                           const RowColItem* __restrict__ items,
-                                                           const float* __restrict__ x,
-                                                           float* __restrict__ colpart, float* __restrict__ rowpart,
-                                                           int r) {
-  __shared__ float row_lds[kRowBlock][kBlock];
-  const RowColItem it = items[blockIdx.x];
-  const RowColVar v = vars[it.var];
-  const bool vec = v.vec != 0;
-  const int w = vec ? 4 : 1;
-  const int64_t col0 = (int64_t)it.ct * (kBlock * w) + (int64_t)threadIdx.x * w;
-  const int64_t row0 = (int64_t)it.rb * kRowBlock;
-  int64_t real_rows = v.rows - (int64_t)r * v.Lr;           // rows of this replica's piece that exist
-  real_rows = real_rows < 0 ? 0 : (real_rows > v.Lr ? v.Lr : real_rows);
-  const int in_block = (int)((v.Lr - row0 < kRowBlock) ? (v.Lr - row0) : kRowBlock);       // rows of the piece
-  const int live = (int)((real_rows - row0 < 0) ? 0 : ((real_rows - row0 < in_block) ? (real_rows - row0) : in_block));
-  const bool col_ok = col0 < v.cols;
-  const float* base = x + v.off + row0 * v.cols + col0;
-  float c0 = 0.0f, c1 = 0.0f, c2 = 0.0f, c3 = 0.0f;
-  for (int rr0 = 0; rr0 < in_block; rr0 += kRowBatch) {
-    F4 val[kRowBatch];
-#pragma unroll
-    for (int j = 0; j < kRowBatch; ++j) {
-      val[j] = F4{0.0f, 0.0f, 0.0f, 0.0f};
-      if (rr0 + j < live && col_ok) {
-        const float* q = base + (int64_t)(rr0 + j) * v.cols;
-        if (vec) val[j] = ld4<SU_NT_ROWCOL != 0>(q);
-        else val[j].x = ld<SU_NT_ROWCOL != 0>(q);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < kRowBatch; ++j) {
-      if (rr0 + j < in_block) {
-        const float a = val[j].x * val[j].x, b = val[j].y * val[j].y, c = val[j].z * val[j].z, d = val[j].w * val[j].w;
-        c0 += a; c1 += b; c2 += c; c3 += d;
-        row_lds[rr0 + j][threadIdx.x] = (a + b) + (c + d);
-      }
-    }
-  }
-  if (col_ok) {
-    float* cp = colpart + v.cp_off + (int64_t)it.rb * v.cols + col0;
-    if (vec) st4<false>(cp, F4{c0, c1, c2, c3});
-    else cp[0] = c0;
-  }
-  __syncthreads();
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int row = wave; row < in_block; row += kBlock / 64) {
-    float s = (row_lds[row][lane] + row_lds[row][lane + 64]) + (row_lds[row][lane + 128] + row_lds[row][lane + 192]);
-#pragma unroll
-    for (int sh = 32; sh >= 1; sh >>= 1) s += __shfl_xor(s, sh, 64);
-    if (lane == 0) rowpart[v.rp_off + (int64_t)it.ct * v.Lr + row0 + row] = s;
-  }
-}
-
-// blockIdx.x = variable, blockIdx.y strides over its columns and rows.
-__global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __restrict__ vars,
-                                                           const float* __restrict__ colpart,
-                                                           const float* __restrict__ rowpart,
-                                                           float* __restrict__ row_out, float* __restrict__ col_out) {
-  const RowColVar v = vars[blockIdx.x];
-  const int64_t step = (int64_t)gridDim.y * kBlock;
-  for (int64_t c = (int64_t)blockIdx.y * kBlock + threadIdx.x; c < v.cols; c += step) {
-    float s = 0.0f;
-    for (int rb = 0; rb < v.n_rb; ++rb) s += colpart[v.cp_off + (int64_t)rb * v.cols + c];
-    col_out[v.col_off + c] = s;
-  }
-  for (int64_t k = (int64_t)blockIdx.y * kBlock + threadIdx.x; k < v.Lr; k += step) {
-    float s = 0.0f;
-    for (int ct = 0; ct < v.n_ct; ++ct) s += rowpart[v.rp_off + (int64_t)ct * v.Lr + k];
-    row_out[v.row_off + k] = s;
-  }
-}
-
 inline unsigned flat_grid(int64_t n4) {
   const int64_t tile = (int64_t)kBlock * kFlatUnroll;
   int64_t tiles = (n4 + tile - 1) / tile;
@@ -963,11 +825,6 @@ inline unsigned flat_grid(int64_t n4) {
 #endif
   if (tiles > 0x7FFFFFFF) tiles = 0x7FFFFFFF;
   return (unsigned)tiles;
-}
-
-template <typename T>
-inline T* ws_at(const shard_plan_t* p, size_t off) {
-  return reinterpret_cast<T*>(p->ws.base + off);
 }
 
 }  // namespace
@@ -1183,25 +1040,6 @@ hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, floa
   else if (vec) hipLaunchKernelGGL((lars_p2_kernel<true, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
   else if (o) hipLaunchKernelGGL((lars_p2_kernel<false, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
   else hipLaunchKernelGGL((lars_p2_kernel<false, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
-  return hipGetLastError();
-}
-
-hipError_t launch_rowcol_sumsq(shard_plan_t* p, int r, const float* x, float* row_out, float* col_out,
-                               hipStream_t stream) {
-  if (p->rc_items.empty()) return hipSuccess;
-  const RowColVar* vars = ws_at<RowColVar>(p, p->ws.rc_vars);
-  float* colpart = ws_at<float>(p, p->ws.rc_colpart);
-  float* rowpart = ws_at<float>(p, p->ws.rc_rowpart);
-  {
-    ProfScope ps(p, SHARD_K_ROWCOL_P1, stream);
-    hipLaunchKernelGGL(rowcol_p1_kernel, dim3((unsigned)p->rc_items.size()), dim3(kBlock), 0, stream, vars,
-                       ws_at<RowColItem>(p, p->ws.rc_items), x, colpart, rowpart, r);
-  }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  ProfScope ps(p, SHARD_K_ROWCOL_P2, stream);
-  hipLaunchKernelGGL(rowcol_p2_kernel, dim3((unsigned)p->V, 16), dim3(kBlock), 0, stream, vars, colpart, rowpart,
-                     row_out, col_out);
   return hipGetLastError();
 }
 

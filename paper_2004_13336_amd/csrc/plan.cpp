@@ -108,7 +108,6 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         rv.cols = cols[i];
         rv.Lr = cols[i] > 0 ? (numel[i] + N - 1) / N : 0;
         rv.vec = (cols[i] % 4 == 0 && p->off[i] % 4 == 0) ? 1 : 0;
-        rv.reserved = 0;
         const int64_t tile_cols = rv.vec ? 4 * kBlock : kBlock;
         const int64_t n_rb = (rv.Lr + kRowBlock - 1) / kRowBlock;
         const int64_t n_ct = (rv.cols + tile_cols - 1) / tile_cols;
@@ -119,6 +118,8 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         rv.col_off = col_off;
         rv.cp_off = cp;
         rv.rp_off = rp;
+        rv.first_item = (int32_t)p->rc_items.size();
+        rv.L = p->L[i];
         row_off += rv.Lr;
         col_off += rv.cols;
         cp += (n_rb * rv.cols + 3) / 4 * 4;                // keeps every variable's partials 16-byte aligned
@@ -153,6 +154,16 @@ size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
     ws->rc_items = pos;    pos = align_up(pos + p->rc_items.size() * sizeof(RowColItem), 256);
     ws->rc_colpart = pos;  pos = align_up(pos + (size_t)p->rc_colpart_elems * sizeof(float), 256);
     ws->rc_rowpart = pos;  pos = align_up(pos + (size_t)p->rc_rowpart_elems * sizeof(float), 256);
+    const size_t items = p->rc_items.size(), rows = (size_t)p->rc_total_rows, cols = (size_t)p->rc_total_cols;
+    ws->af_wpart = pos;    pos = align_up(pos + items * sizeof(float), 256);
+    ws->af_upart = pos;    pos = align_up(pos + items * sizeof(float), 256);
+    ws->af_sumr = pos;     pos = align_up(pos + V * sizeof(float), 256);
+    ws->af_inv_r = pos;    pos = align_up(pos + rows * sizeof(float), 256);
+    ws->af_inv_c = pos;    pos = align_up(pos + cols * sizeof(float), 256);
+    ws->af_rowsq = pos;    pos = align_up(pos + rows * sizeof(float), 256);
+    ws->af_colsq = pos;    pos = align_up(pos + cols * sizeof(float), 256);
+    ws->af_table = pos;    pos = align_up(pos + V * 2 * sizeof(float), 256);
+    ws->af_usq = pos;      pos = align_up(pos + V * sizeof(float), 256);
   }
   return pos < 256 ? 256 : pos;
 }
