@@ -238,6 +238,14 @@ int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard
                                                p->rc_items.size() * sizeof(RowColItem), hipMemcpyHostToDevice,
                                                s) != hipSuccess)
       return SHARD_EHIP;
+    if (!p->rc_col_items.empty() && hipMemcpyAsync(ws.base + ws.rc_col_items, p->rc_col_items.data(),
+                                                   p->rc_col_items.size() * sizeof(ColItem), hipMemcpyHostToDevice,
+                                                   s) != hipSuccess)
+      return SHARD_EHIP;
+    if (!p->rc_row_items.empty() && hipMemcpyAsync(ws.base + ws.rc_row_items, p->rc_row_items.data(),
+                                                   p->rc_row_items.size() * sizeof(RowItem), hipMemcpyHostToDevice,
+                                                   s) != hipSuccess)
+      return SHARD_EHIP;
   }
   p->ws = ws;
   for (int i = 0; i < kPtrSlots; ++i) p->slot_valid[i] = false;
@@ -472,7 +480,7 @@ int shard_update_adafactor_partials(shard_plan_t* p, int r, const float* w, cons
     return SHARD_EINVAL;
   if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK)) return rc;
   return hip_status(launch_adafactor_partials(p, r, w, g, R, nullptr, nullptr, row_sq_out, col_sq_out, table_out,
-                                              as_stream(stream)));
+                                              false, as_stream(stream)));
 }
 
 int shard_update_adafactor_moments(shard_plan_t* p, int r, const float* g, float* R, float* C, const float* row_sq,
@@ -489,7 +497,7 @@ int shard_update_adafactor_moments(shard_plan_t* p, int r, const float* g, float
       (p->rc_total_cols > 0 && (C == nullptr || col_sq_global == nullptr)))
     return SHARD_EINVAL;
   if (p->S > 0 && (rc = check_shard_ptr(g)) != SHARD_OK) return rc;
-  return hip_status(launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq_global, table_global, k, nullptr,
+  return hip_status(launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq_global, table_global, k, false, nullptr,
                                              u_sumsq_out, nullptr, as_stream(stream)));
 }
 
@@ -523,8 +531,8 @@ int shard_update_adafactor(shard_plan_t* p, int r, float* w, const float* g, flo
   float* col_sq = reinterpret_cast<float*>(p->ws.base + p->ws.af_colsq);
   float* table = reinterpret_cast<float*>(p->ws.base + p->ws.af_table);
   float* usq = reinterpret_cast<float*>(p->ws.base + p->ws.af_usq);
-  hipError_t e = launch_adafactor_partials(p, r, w, g, R, other_col_sq, other_table, row_sq, col_sq, table, s);
-  if (e == hipSuccess) e = launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq, table, k, other_u_sumsq, nullptr, usq, s);
+  hipError_t e = launch_adafactor_partials(p, r, w, g, R, other_col_sq, other_table, row_sq, col_sq, table, true, s);
+  if (e == hipSuccess) e = launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq, table, k, true, other_u_sumsq, nullptr, usq, s);
   if (e == hipSuccess) e = launch_adafactor_apply(p, r, w, g, table, usq, w_bf16_out, k, s);
   return hip_status(e);
 }

@@ -37,28 +37,43 @@ struct ChunkDesc {
 };
 static_assert(sizeof(ChunkDesc) == 16, "ChunkDesc layout");
 
-// Row plans only: one variable seen as a row-major rows x cols matrix whose rows are sharded, and
-// one work item of the row/column reduction: kRowBlock rows x one column tile.
+// Row plans only: one variable seen as a row-major rows x cols matrix whose rows are sharded, and the
+// work items of the kernels that keep rows and columns apart.
 struct RowColVar {
   int64_t off;        // piece offset in the packed shard
   int64_t rows;       // rows of the full matrix
   int64_t Lr;         // rows per replica
   int64_t cols;
-  int64_t row_off;    // this variable's place in the row-sum output  (sum of Lr of earlier variables)
-  int64_t col_off;    // and in the column-sum output                 (sum of cols of earlier variables)
+  int64_t row_off;    // this variable's place in per-row arrays    (sum of Lr of earlier variables)
+  int64_t col_off;    // and in per-column arrays                    (sum of cols of earlier variables)
   int64_t cp_off;     // column partials [n_rb][cols] in the workspace
   int64_t rp_off;     // row partials [n_ct][Lr] in the workspace
-  int32_t n_rb;       // row blocks
-  int32_t n_ct;       // column tiles
-  int32_t vec;        // 1: rows start on 16-byte boundaries, threads own 4 adjacent columns
-  int32_t first_item; // this variable's work items are [first_item, first_item + n_rb * n_ct)
   int64_t L;          // slots of the piece in the packed shard (>= Lr * cols: alignment tail)
+  int32_t n_rb;       // row blocks of kRowBlock rows
+  int32_t n_ct;       // column tiles of kBlock/4 * (vec ? 4 : 1) columns
+  int32_t vec;        // 1: rows start on 16-byte boundaries, threads own 4 adjacent columns
+  int32_t first_item; // this variable's tile items are [first_item, first_item + n_rb * n_ct)
+  int32_t first_col_item, n_col_items;   // its column items (kColTile columns each)
 };
-static_assert(sizeof(RowColVar) == 88, "RowColVar layout");
+static_assert(sizeof(RowColVar) == 96, "RowColVar layout");
+// One tile: kRowBlock rows x one column tile.  Wavefront w of the workgroup takes rows 8w .. 8w+7,
+// lane l the columns l*4 .. l*4+3 (or column l) of the tile.
 struct RowColItem {
   int32_t var, rb, ct, reserved;
 };
-constexpr int kRowBlock = 32;        // rows per work item of the row/column reduction
+// kColTile consecutive columns of one variable (per-column work: adding partials, state update).
+struct ColItem {
+  int32_t var, tile;
+};
+// Per-row work.  wide == 0: kBlock consecutive rows starting at first_row, one thread per row;
+// wide == 1: the single row first_row, the whole workgroup adds across its many column tiles.
+struct RowItem {
+  int32_t var, wide;
+  int64_t first_row;
+};
+constexpr int kRowBlock = 32;        // rows per tile
+constexpr int kColTile = 64;         // columns per column item
+constexpr int kWideTiles = 32;       // a variable with more column tiles than this gets one workgroup per row
 
 constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kPtrSlots = 4;         // cached device pointer tables per plan
@@ -92,6 +107,7 @@ struct Workspace {
   // byte offsets inside base
   size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
   size_t rc_vars = 0, rc_items = 0, rc_colpart = 0, rc_rowpart = 0;   // row plans only
+  size_t rc_col_items = 0, rc_row_items = 0, rc_colitem_part = 0;
   // Adafactor (row plans only): per-item partial sums, per-variable scalars, the factors of 1/sqrt(Vhat),
   // and the tables the fused call keeps between its phases
   size_t af_wpart = 0, af_upart = 0, af_sumr = 0, af_inv_r = 0, af_inv_c = 0;
@@ -115,6 +131,8 @@ struct shard_plan_s {
   bool row_plan = false;
   std::vector<su::RowColVar> rc_vars;      // row plans only
   std::vector<su::RowColItem> rc_items;
+  std::vector<su::ColItem> rc_col_items;
+  std::vector<su::RowItem> rc_row_items;
   int64_t rc_total_rows = 0, rc_total_cols = 0, rc_colpart_elems = 0, rc_rowpart_elems = 0;
 
   su::Workspace ws;
@@ -179,11 +197,12 @@ hipError_t launch_rowcol_sumsq(shard_plan_t* p, int r, const float* x, float* ro
 // {sum w^2, sum of the old row state}; other_* (nullable) are added (all-reduce stand-ins).
 hipError_t launch_adafactor_partials(shard_plan_t* p, int r, const float* w, const float* g, const float* R,
                                      const float* other_col, const float* other_table, float* row_sq, float* col_sq,
-                                     float* table, hipStream_t stream);
+                                     float* table, bool keep_column_item_sums, hipStream_t stream);
 // Phase 2: new row/column state, the factors of 1/sqrt(Vhat) (kept in the workspace), per-variable sum of U^2.
 hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, float* R, float* C, const float* row_sq,
                                     const float* col_sq_global, const float* table_global, const AdafactorK& k,
-                                    const float* other_usq, float* usq_local, float* usq_total, hipStream_t stream);
+                                    bool have_column_item_sums, const float* other_usq, float* usq_local,
+                                    float* usq_total, hipStream_t stream);
 // Phase 3: the weight update, from the factors phase 2 left in the workspace.
 hipError_t launch_adafactor_apply(shard_plan_t* p, int r, float* w, const float* g, const float* table_global,
                                   const float* usq_global, void* w16, const AdafactorK& k, hipStream_t stream);

@@ -97,9 +97,10 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
     p->row_plan = cols != nullptr;
     p->rc_vars.clear();
     p->rc_items.clear();
+    p->rc_col_items.clear();
+    p->rc_row_items.clear();
     if (cols) {
-      // work items of the row/column reduction: kRowBlock rows x one column tile (1024 columns
-      // where 128-bit accesses are possible, 256 otherwise)
+      const int64_t kMaxItems = (int64_t)std::numeric_limits<int32_t>::max() / 4;
       int64_t row_off = 0, col_off = 0, cp = 0, rp = 0;
       for (int i = 0; i < V; ++i) {
         RowColVar rv;
@@ -107,11 +108,15 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         rv.rows = numel[i];
         rv.cols = cols[i];
         rv.Lr = cols[i] > 0 ? (numel[i] + N - 1) / N : 0;
+        rv.L = p->L[i];
         rv.vec = (cols[i] % 4 == 0 && p->off[i] % 4 == 0) ? 1 : 0;
-        const int64_t tile_cols = rv.vec ? 4 * kBlock : kBlock;
+        const int64_t tile_cols = (kBlock / 4) * (rv.vec ? 4 : 1);      // one wavefront spans a tile's columns
         const int64_t n_rb = (rv.Lr + kRowBlock - 1) / kRowBlock;
-        const int64_t n_ct = (rv.cols + tile_cols - 1) / tile_cols;
-        if (n_rb * n_ct + (int64_t)p->rc_items.size() > (int64_t)std::numeric_limits<int32_t>::max()) return SHARD_EINVAL;
+        const int64_t n_ct = rv.Lr > 0 ? (rv.cols + tile_cols - 1) / tile_cols : 0;
+        const int64_t n_col = (rv.cols + kColTile - 1) / kColTile;   // also for a variable without rows: its column sums are 0
+        if (n_rb > kMaxItems || n_ct > kMaxItems || n_col > kMaxItems) return SHARD_EINVAL;
+        if (n_rb * n_ct + (int64_t)p->rc_items.size() > kMaxItems) return SHARD_EINVAL;
+        if (n_col + (int64_t)p->rc_col_items.size() > kMaxItems) return SHARD_EINVAL;
         rv.n_rb = (int32_t)n_rb;
         rv.n_ct = (int32_t)n_ct;
         rv.row_off = row_off;
@@ -119,7 +124,8 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         rv.cp_off = cp;
         rv.rp_off = rp;
         rv.first_item = (int32_t)p->rc_items.size();
-        rv.L = p->L[i];
+        rv.first_col_item = (int32_t)p->rc_col_items.size();
+        rv.n_col_items = (int32_t)n_col;
         row_off += rv.Lr;
         col_off += rv.cols;
         cp += (n_rb * rv.cols + 3) / 4 * 4;                // keeps every variable's partials 16-byte aligned
@@ -127,6 +133,11 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         p->rc_vars.push_back(rv);
         for (int64_t rb = 0; rb < n_rb; ++rb)
           for (int64_t ct = 0; ct < n_ct; ++ct) p->rc_items.push_back(RowColItem{i, (int32_t)rb, (int32_t)ct, 0});
+        for (int64_t t = 0; t < n_col; ++t) p->rc_col_items.push_back(ColItem{i, (int32_t)t});
+        const bool wide = n_ct > kWideTiles;
+        const int64_t row_step = wide ? 1 : kBlock;
+        if ((rv.Lr + row_step - 1) / row_step + (int64_t)p->rc_row_items.size() > kMaxItems) return SHARD_EINVAL;
+        for (int64_t k = 0; k < rv.Lr; k += row_step) p->rc_row_items.push_back(RowItem{i, wide ? 1 : 0, k});
       }
       p->rc_total_rows = row_off;
       p->rc_total_cols = col_off;
@@ -154,6 +165,9 @@ size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
     ws->rc_items = pos;    pos = align_up(pos + p->rc_items.size() * sizeof(RowColItem), 256);
     ws->rc_colpart = pos;  pos = align_up(pos + (size_t)p->rc_colpart_elems * sizeof(float), 256);
     ws->rc_rowpart = pos;  pos = align_up(pos + (size_t)p->rc_rowpart_elems * sizeof(float), 256);
+    ws->rc_col_items = pos;    pos = align_up(pos + p->rc_col_items.size() * sizeof(ColItem), 256);
+    ws->rc_row_items = pos;    pos = align_up(pos + p->rc_row_items.size() * sizeof(RowItem), 256);
+    ws->rc_colitem_part = pos; pos = align_up(pos + p->rc_col_items.size() * sizeof(float), 256);
     const size_t items = p->rc_items.size(), rows = (size_t)p->rc_total_rows, cols = (size_t)p->rc_total_cols;
     ws->af_wpart = pos;    pos = align_up(pos + items * sizeof(float), 256);
     ws->af_upart = pos;    pos = align_up(pos + items * sizeof(float), 256);
