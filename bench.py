@@ -332,8 +332,46 @@ def table(args, torch, su, cfgs, path):
             wb.free()
             del wb
             torch.cuda.empty_cache()
+            if all(len(s) <= 2 for s in cfg.shapes) and cfg.total < 1_000_000_000:
+                rows.append(_adafactor_row(cfg, N, torch, su))
+                print("table:", rows[-1], file=sys.stderr, flush=True)
     with open(path, "w") as f:
         json.dump(rows, f, indent=1)
+
+
+def _adafactor_row(cfg, N, torch, su):
+    """Adafactor on the row plan of the same variables (matrices by rows, vectors as n x 1): 24 B/slot
+    (g and w read by the reductions, g by the clipping sum, g and w read and w written by the update)."""
+    shapes = [(s[0], s[1]) if len(s) == 2 else (s[0], 1) for s in cfg.shapes]
+    plan = su.shard_plan_bind(su.shard_plan_rows([s[0] for s in shapes], [s[1] for s in shapes], N, 8))
+    _, _, total_rows, total_cols = su.shard_plan_rowcol_layout(plan)
+    S = plan.S
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    w = _device_normal(S, cfg.weight_std, gen, torch)
+    g = _device_normal(S, cfg.grad_std, gen, torch)
+    R = torch.zeros(max(total_rows, 1), dtype=torch.float32, device="cuda")
+    C = torch.zeros(max(total_cols, 1), dtype=torch.float32, device="cuda")
+    hp = {"eps1": 1e-30, "eps2": 1e-3, "clip_threshold": 1.0, "decay_exponent": 0.8, "max_rho": 1e-2}
+    for t in range(1, 6):
+        su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
+    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+    iters = 50
+    for t in range(6, 6 + iters):
+        su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
+    torch.cuda.synchronize()
+    us = 0.0
+    for k in ("rowcol_p1", "rowcol_p2", "adafactor_state", "adafactor_usq", "adafactor_apply"):
+        n, ms = su.shard_profile_read(plan, k)
+        us += 1e3 * ms / iters
+    su.shard_profile_enable(plan, False)
+    real = sum(plan.real_count(0))
+    nbytes = 24 * S
+    row = {"config": cfg.name, "N": N, "stage": "adafactor (row plan)", "S": S, "kernel_us": round(us, 2),
+           "params_per_s": real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+           "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cache_resident": nbytes < 256e6}
+    plan.free()
+    return row
 
 
 def main():

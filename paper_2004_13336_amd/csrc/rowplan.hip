@@ -15,11 +15,15 @@
 // All sums are taken in an order fixed by the plan: results are run-to-run identical.
 #include "device_common.hpp"
 
+// Cache policies, measured on MI355X.  A tensor that is reduced once and not needed again is loaded
+// non-temporally; Adafactor's gradient is read by three kernels in a row and stays cacheable (one
+// replica's piece fits the 256 MB memory-side cache), its weights are loaded non-temporally and stored
+// non-temporally by the last kernel.
 #ifndef SU_NT_ROWCOL
-#define SU_NT_ROWCOL 1     // 1: non-temporal loads of the tensor that is only reduced
+#define SU_NT_ROWCOL 1     // 1: non-temporal loads in shard_reduce_sq_rows_cols
 #endif
 #ifndef SU_NT_ADAFACTOR
-#define SU_NT_ADAFACTOR 0  // cache policy mask of the Adafactor kernels (4: g, 2: w loads, 1: stores)
+#define SU_NT_ADAFACTOR 3  // mask of the Adafactor kernels (4: g loads, 2: w loads, 1: stores)
 #endif
 
 namespace su {
@@ -130,10 +134,10 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
     if (j < t.live_here && t.col_ok) {
       const int64_t o = (int64_t)j * t.v.cols;
       if (t.vec) {
-        val[j] = ld4<SU_NT_ROWCOL != 0>(base + o);
+        val[j] = ld4<(SU_NT_ROWCOL != 0) && !WITH_W>(base + o);
         if constexpr (WITH_W) wv[j] = ld4<false>(ybase + o);
       } else {
-        val[j].x = ld<SU_NT_ROWCOL != 0>(base + o);
+        val[j].x = ld<(SU_NT_ROWCOL != 0) && !WITH_W>(base + o);
         if constexpr (WITH_W) wv[j].x = ybase[o];
       }
     }
