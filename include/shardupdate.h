@@ -36,6 +36,12 @@
  *    stream) and are asynchronous; errors reported are argument and launch errors.
  *  - A plan is not thread-safe, and calls that use one plan must be ordered on one
  *    stream (or otherwise synchronised by the caller): they share the plan's workspace.
+ *  - HIP graphs: the formatting and update calls only launch kernels (no allocation, no
+ *    synchronisation, no memset), so a step can be recorded with stream capture.  Scalars passed by
+ *    value (replica id, step, hyper-parameters) are frozen into the graph.  The device tables of
+ *    full-tensor pointers are cached in the plan's workspace (the 4 most recently used lists); a
+ *    recorded graph reads the tables that were resident at capture time, so between capture and the
+ *    last replay do not pass more than 3 OTHER lists of full tensors to the same plan.
  */
 #ifndef SHARDUPDATE_H
 #define SHARDUPDATE_H

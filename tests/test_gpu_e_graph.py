@@ -1,0 +1,76 @@
+"""The whole step (format, LAMB, unshard) recorded in a HIP graph: every replay must equal the eager
+step bit for bit, with eager work and synchronisations between the replays.  The library's step path
+allocates nothing, synchronises nothing and records no memset, so it can be captured as it is."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2004_13336_amd as su
+from helpers import DEV, f32_hp, same_bits, to_dev, to_host
+from workloads import CONFIGS, normal_f32
+
+pytestmark = pytest.mark.gpu
+
+LAMB = f32_hp({"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-6, "weight_decay": 0.01})
+
+
+class State:
+    def __init__(self, plan, cfg, r, seed):
+        S, N = plan.S, plan.N
+        self.full_g = [to_dev(normal_f32(seed, i, "g", n, 1e-2, 1)) for i, n in enumerate(cfg.numel)]
+        self.full_w = [torch.zeros(n, dtype=torch.float32, device=DEV) for n in cfg.numel]
+        ws = [normal_f32(seed, i, "w", n, 0.02) for i, n in enumerate(cfg.numel)]
+        oplan = oracle.make_plan(cfg.numel, N, 8)
+        self.gathered = to_dev(np.stack([oracle.shard_format(oplan, q, ws) for q in range(N)]))
+        self.g = torch.zeros(S, dtype=torch.float32, device=DEV)
+        self.m = torch.zeros(S, dtype=torch.float32, device=DEV)
+        self.v = torch.zeros(S, dtype=torch.float32, device=DEV)
+        self.w16 = torch.zeros(S, dtype=torch.bfloat16, device=DEV)
+        self.other = torch.full((plan.V, 2), 0.25, dtype=torch.float32, device=DEV)
+        self.r = r
+
+    def step(self, plan):
+        r = self.r
+        su.shard_format(plan, r, self.full_g, self.g)
+        su.shard_update_lamb(plan, r, self.gathered[r], self.g, self.m, self.v, LAMB, 5, other_replicas_sumsq=self.other,
+                             w_bf16_out=self.w16)
+        su.unshard_format(plan, self.gathered, self.full_w)
+
+    def snapshot(self):
+        return [to_host(t) for t in (self.gathered, self.m, self.v, self.w16, torch.cat(self.full_w))]
+
+
+def test_step_captured_in_a_graph_replays_like_eager():
+    cfg = [c for c in CONFIGS if c.name == "tiny"][0]
+    N, r = 4, 1
+    plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8))
+    eager, graphed = State(plan, cfg, r, 91), State(plan, cfg, r, 91)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graphed.step(plan)                      # warm-up on the capture stream: pointer tables become resident
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        graphed.step(plan)
+    torch.cuda.synchronize()
+    # both states restart from the same point: the warm-up and the capture pass moved `graphed`
+    fresh = State(plan, cfg, r, 91)
+    for dst, src in ((graphed, fresh), (eager, fresh)):
+        dst.gathered.copy_(src.gathered); dst.m.zero_(); dst.v.zero_(); dst.w16.zero_(); dst.g.zero_()
+        for a in dst.full_w:
+            a.zero_()
+    torch.cuda.synchronize()
+    previous = None
+    for k in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        eager.step(plan)                        # eager work of the same library between the replays
+        torch.cuda.synchronize()
+        a, b = graphed.snapshot(), eager.snapshot()
+        assert all(same_bits(x, y) for x, y in zip(a, b)), "replay %d differs from the eager step" % k
+        if previous is not None:
+            assert not same_bits(a[0], previous[0])          # the state does move from replay to replay
+        previous = a
+    plan.free()
