@@ -209,3 +209,42 @@ def test_peak_memory_matches_oracle():
     assert lib().shard_plan_peak_bytes(p.handle, 4, 8, -1, None, None) == -1
     assert lib().shard_plan_peak_bytes(None, 4, 8, 0, None, None) == -1
     p.free()
+
+
+def _declarations():
+    """name -> number of parameters, parsed from the header's prototypes."""
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    out = {}
+    for m in re.finditer(r"\b(shard_[a-z_0-9]+|unshard_format)\s*\(([^;{}]*?)\)\s*;", text, flags=re.S):
+        params = m.group(2).strip()
+        out[m.group(1)] = 0 if params in ("", "void") else params.count(",") + 1
+    return out
+
+
+def test_binding_signatures_have_the_headers_parameter_counts():
+    decl = _declarations()
+    assert set(decl) == set(SIGNATURES)
+    for name, (_, argtypes) in SIGNATURES.items():
+        assert len(argtypes) == decl[name], name
+
+
+def test_adafactor_argument_checks_without_touching_the_gpu():
+    EINVAL, ESTATE = -1, -5
+    from paper_2004_13336_amd._lib import AdafactorHP
+    hp = AdafactorHP(1e-30, 1e-3, 1.0, 0.8, 1e-2)
+    fake = C.c_void_p(0x1000)
+    rows = su.shard_plan_rows([16, 5], [8, 1], 2)                  # never bound
+    call = lib().shard_update_adafactor
+    assert call(rows.handle, 0, fake, fake, fake, fake, None, C.byref(hp), 1, None, None, None, None) == ESTATE
+    assert call(rows.handle, 2, fake, fake, fake, fake, None, C.byref(hp), 1, None, None, None, None) == EINVAL
+    assert lib().shard_update_adafactor_partials(rows.handle, 0, fake, fake, fake, fake, fake, fake, None) == ESTATE
+    assert lib().shard_update_adafactor_moments(rows.handle, 0, fake, fake, fake, fake, fake, fake, C.byref(hp), 1, fake,
+                                                None) == ESTATE
+    assert lib().shard_update_adafactor_apply(rows.handle, 0, fake, fake, fake, fake, None, C.byref(hp), 1, None) == ESTATE
+    ro, co, tr, tc = su.shard_plan_rowcol_layout(rows)
+    assert (ro, co, tr, tc) == ((0, 8), (0, 8), 11, 9)             # Lr = 8 and 3 rows per replica; 8 + 1 columns
+    rows.free()
+    flat = su.shard_plan([64], 2)
+    assert lib().shard_plan_rowcol_layout(flat.handle, None, None, None, None) == EINVAL
+    flat.free()
