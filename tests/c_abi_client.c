@@ -1,0 +1,103 @@
+/* A plain C client of libshardupdate.so: no PyTorch, no C++.  It shows that the boundary is usable
+ * from C with nothing but the HIP runtime for device memory, and checks one pass of the path
+ * (plan -> bind -> format -> momentum update with mu = 0 -> unshard) against the closed form
+ * w' = w - lr (g + wd w), evaluated here in double.  Exit status 0 = pass.
+ *
+ * Built by __graft_entry__.build() with gcc; run by tests/test_gpu_f_c_client.py on a GPU machine. */
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "shardupdate.h"
+
+#define CHECK_HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { \
+  fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); return 2; } } while (0)
+#define CHECK_SU(x) do { int s_ = (x); if (s_ != SHARD_OK) { \
+  fprintf(stderr, "shardupdate error '%s' at line %d\n", shard_strerror(s_), __LINE__); return 3; } } while (0)
+
+enum { V = 3, N = 3, R = 1 };
+
+static float pattern(int var, long k, int kind) {          /* deterministic, sign-alternating values */
+  unsigned long x = (unsigned long)(var + 1) * 2654435761ul + (unsigned long)k * 40503ul + (unsigned long)kind * 977ul;
+  x ^= x >> 13; x *= 0x9E3779B1ul; x ^= x >> 16;
+  return ((float)(x % 20001ul) - 10000.0f) * (kind == 0 ? 2e-6f : 1e-7f);
+}
+
+int main(void) {
+  const int64_t numel[V] = {1000, 37, 4099};
+  const float lr = 0.1f, wd = 5e-5f;
+  shard_plan_t* plan = NULL;
+  int64_t S = 0, total = 0, seg_off[V], seg_len[V], real[V];
+  size_t ws_bytes = 0;
+  void *ws = NULL, *w = NULL, *g = NULL, *m = NULL, *gathered = NULL;
+  void* full_w[V]; void* full_g[V]; void* full_out[V];
+  float* host[V]; float* hostg[V];
+  int i, failures = 0;
+  int devices = 0;
+  CHECK_HIP(hipGetDeviceCount(&devices));
+  if (devices < 1) { fprintf(stderr, "no GPU\n"); return 2; }
+
+  CHECK_SU(shard_plan(V, numel, N, 8, NULL, 0, &plan));
+  CHECK_SU(shard_plan_info(plan, &S, &total, NULL, NULL, &ws_bytes));
+  CHECK_SU(shard_plan_segments(plan, seg_off, seg_len));
+  CHECK_SU(shard_plan_real_count(plan, R, real));
+  CHECK_HIP(hipMalloc(&ws, ws_bytes));
+  CHECK_SU(shard_plan_bind(plan, ws, ws_bytes, NULL));
+
+  for (i = 0; i < V; ++i) {
+    long k;
+    host[i] = (float*)malloc(sizeof(float) * (size_t)numel[i]);
+    hostg[i] = (float*)malloc(sizeof(float) * (size_t)numel[i]);
+    for (k = 0; k < numel[i]; ++k) { host[i][k] = pattern(i, k, 0); hostg[i][k] = pattern(i, k, 1); }
+    CHECK_HIP(hipMalloc(&full_w[i], sizeof(float) * (size_t)numel[i]));
+    CHECK_HIP(hipMalloc(&full_g[i], sizeof(float) * (size_t)numel[i]));
+    CHECK_HIP(hipMalloc(&full_out[i], sizeof(float) * (size_t)numel[i]));
+    CHECK_HIP(hipMemcpy(full_w[i], host[i], sizeof(float) * (size_t)numel[i], hipMemcpyHostToDevice));
+    CHECK_HIP(hipMemcpy(full_g[i], hostg[i], sizeof(float) * (size_t)numel[i], hipMemcpyHostToDevice));
+    CHECK_HIP(hipMemset(full_out[i], 0xFF, sizeof(float) * (size_t)numel[i]));
+  }
+  CHECK_HIP(hipMalloc(&gathered, sizeof(float) * (size_t)(N * S)));
+  CHECK_HIP(hipMemset(gathered, 0, sizeof(float) * (size_t)(N * S)));
+  w = (char*)gathered + sizeof(float) * (size_t)(R * S);      /* replica R's row of the gathered buffer */
+  CHECK_HIP(hipMalloc(&g, sizeof(float) * (size_t)S));
+  CHECK_HIP(hipMalloc(&m, sizeof(float) * (size_t)S));
+  CHECK_HIP(hipMemset(m, 0, sizeof(float) * (size_t)S));
+
+  CHECK_SU(shard_format(plan, R, (const void* const*)full_w, SHARD_F32, w, SHARD_F32, NULL));
+  CHECK_SU(shard_format(plan, R, (const void* const*)full_g, SHARD_F32, g, SHARD_F32, NULL));
+  {
+    shard_momentum_hp hp;
+    hp.lr = lr; hp.mu = 0.0f; hp.weight_decay = wd;
+    CHECK_SU(shard_update_momentum(plan, R, (float*)w, (const float*)g, (float*)m, NULL, &hp, NULL));
+  }
+  CHECK_SU(unshard_format(plan, gathered, 0, SHARD_F32, full_out, SHARD_F32, NULL));
+  CHECK_HIP(hipDeviceSynchronize());
+
+  for (i = 0; i < V; ++i) {
+    long k;
+    float* got = (float*)malloc(sizeof(float) * (size_t)numel[i]);
+    CHECK_HIP(hipMemcpy(got, full_out[i], sizeof(float) * (size_t)numel[i], hipMemcpyDeviceToHost));
+    for (k = 0; k < numel[i]; ++k) {
+      const long first = (long)R * (long)seg_len[i];
+      const int mine = k >= first && k < first + (long)real[i];
+      /* rows of the other replicas were zero, so their elements come back as +0.0 */
+      const double want = mine ? (double)host[i][k] - (double)lr * ((double)hostg[i][k] + (double)wd * (double)host[i][k]) : 0.0;
+      if (fabs((double)got[k] - want) > 1e-6 * (1.0 + fabs(want))) {
+        if (failures < 5) fprintf(stderr, "var %d elem %ld: got %.9g want %.9g\n", i, k, (double)got[k], want);
+        ++failures;
+      }
+    }
+    free(got);
+  }
+  /* an error path: replica id out of range */
+  if (shard_format(plan, N, (const void* const*)full_w, SHARD_F32, w, SHARD_F32, NULL) != SHARD_EINVAL) ++failures;
+
+  shard_plan_free(plan);
+  for (i = 0; i < V; ++i) { hipFree(full_w[i]); hipFree(full_g[i]); hipFree(full_out[i]); free(host[i]); free(hostg[i]); }
+  hipFree(gathered); hipFree(g); hipFree(m); hipFree(ws);
+  if (failures) { fprintf(stderr, "c_abi_client: %d mismatches\n", failures); return 1; }
+  printf("c_abi_client ok: S=%ld total=%ld workspace=%zu bytes\n", (long)S, (long)total, ws_bytes);
+  return 0;
+}

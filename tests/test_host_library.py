@@ -248,3 +248,13 @@ def test_adafactor_argument_checks_without_touching_the_gpu():
     flat = su.shard_plan([64], 2)
     assert lib().shard_plan_rowcol_layout(flat.handle, None, None, None, None) == EINVAL
     flat.free()
+
+
+def test_header_is_valid_c99_and_the_c_client_builds():
+    import subprocess
+    proc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
+                          capture_output=True, text=True)
+    assert proc.returncode == 0, proc.stderr
+    import __graft_entry__
+    lib()                                               # the library the client links against exists
+    assert os.path.exists(__graft_entry__.build_c_client())
