@@ -254,11 +254,9 @@ def cpu_baseline(cfg, N, r):
     plan = oracle.make_plan(cfg.numel, N, 8)
     gs = [normal_f32(cfg.seed, i, "g", n, cfg.grad_std, 1) for i, n in enumerate(cfg.numel)]
     gathered = np.zeros((N, plan.S), np.float32)
-    rng = np.random.default_rng(cfg.seed)
     gathered[r] = oracle.shard_format(plan, r, [normal_f32(cfg.seed, i, "w", n, cfg.weight_std)
                                                 for i, n in enumerate(cfg.numel)])
     m = np.zeros(plan.S, np.float32); v = np.zeros(plan.S, np.float32)
-    del rng
     real = sum(plan.real_count(i, r) for i in range(plan.V))
     steps, t0 = 0, time.perf_counter()
     while True:                                   # whole steps until about 12 s of CPU work are done

@@ -49,22 +49,30 @@ struct RowColVar {
   int64_t cp_off;     // column partials [n_rb][cols] in the workspace
   int64_t rp_off;     // row partials [n_ct][Lr] in the workspace
   int64_t L;          // slots of the piece in the packed shard (>= Lr * cols: alignment tail)
-  int32_t n_rb;       // row blocks of kRowBlock rows
-  int32_t n_ct;       // column tiles of kBlock/4 * (vec ? 4 : 1) columns
-  int32_t vec;        // 1: rows start on 16-byte boundaries, threads own 4 adjacent columns
+  int32_t n_rb;       // row blocks: kRowBlock rows (tall tiles) or kRowBlock/4 rows (flat tiles)
+  int32_t n_ct;       // column tiles: one wavefront's span of columns (tall) or four of them (flat)
+  int32_t shape;      // kRcVec: rows start on 16-byte boundaries, threads own 4 adjacent columns;
+                      // kRcFlat: at most kRowBlock/4 rows per replica, the four wavefronts sit side by side
   int32_t first_item; // this variable's tile items are [first_item, first_item + n_rb * n_ct)
-  int32_t first_col_item, n_col_items;   // its column items (kColTile columns each)
+  int32_t first_col_item, n_col_items;   // its column items (col_span(n_rb) columns each)
 };
 static_assert(sizeof(RowColVar) == 96, "RowColVar layout");
-// One tile: kRowBlock rows x one column tile.  Wavefront w of the workgroup takes rows 8w .. 8w+7,
-// lane l the columns l*4 .. l*4+3 (or column l) of the tile.
+// One tile.  Tall (the usual case): kRowBlock rows x one wavefront's span of columns; wavefront w of
+// the workgroup takes rows 8w .. 8w+7, lane l the columns l*4 .. l*4+3 (or column l) of the tile.
+// Flat (pieces of at most 8 rows, e.g. a [3,3,Cin,Cout] kernel's 9 rows over 8 replicas): 8 rows x
+// four spans; wavefront w takes the w-th span, so no wavefront idles on rows that do not exist.
+constexpr int kRcVec = 1, kRcFlat = 2;
 struct RowColItem {
   int32_t var, rb, ct, reserved;
 };
-// kColTile consecutive columns of one variable (per-column work: adding partials, state update).
+// col_span consecutive columns of one variable (per-column work: adding partials, state update).
+// A variable with many row blocks gets 64-column items whose four wavefronts share the row blocks;
+// one with few gets 256-column items with a thread per column.
 struct ColItem {
   int32_t var, tile;
 };
+constexpr int kDeepRowBlocks = 8;
+inline __host__ __device__ int col_span(int n_rb) { return n_rb > kDeepRowBlocks ? 64 : 256; }
 // Per-row work.  wide == 0: kBlock consecutive rows starting at first_row, one thread per row;
 // wide == 1: the single row first_row, the whole workgroup adds across its many column tiles.
 struct RowItem {
@@ -72,7 +80,6 @@ struct RowItem {
   int64_t first_row;
 };
 constexpr int kRowBlock = 32;        // rows per tile
-constexpr int kColTile = 64;         // columns per column item
 constexpr int kWideTiles = 32;       // a variable with more column tiles than this gets one workgroup per row
 
 constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)

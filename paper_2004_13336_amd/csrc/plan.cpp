@@ -109,11 +109,16 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
         rv.cols = cols[i];
         rv.Lr = cols[i] > 0 ? (numel[i] + N - 1) / N : 0;
         rv.L = p->L[i];
-        rv.vec = (cols[i] % 4 == 0 && p->off[i] % 4 == 0) ? 1 : 0;
-        const int64_t tile_cols = (kBlock / 4) * (rv.vec ? 4 : 1);      // one wavefront spans a tile's columns
-        const int64_t n_rb = (rv.Lr + kRowBlock - 1) / kRowBlock;
+        const bool vec = cols[i] % 4 == 0 && p->off[i] % 4 == 0;
+        const bool flat = rv.Lr <= kRowBlock / 4;
+        rv.shape = (vec ? kRcVec : 0) | (flat ? kRcFlat : 0);
+        const int64_t span = (kBlock / 4) * (vec ? 4 : 1);              // columns one wavefront covers
+        const int64_t tile_cols = flat ? 4 * span : span;
+        const int64_t tile_rows = flat ? kRowBlock / 4 : kRowBlock;
+        const int64_t n_rb = (rv.Lr + tile_rows - 1) / tile_rows;
         const int64_t n_ct = rv.Lr > 0 ? (rv.cols + tile_cols - 1) / tile_cols : 0;
-        const int64_t n_col = (rv.cols + kColTile - 1) / kColTile;   // also for a variable without rows: its column sums are 0
+        const int64_t span_c = col_span((int)(n_rb > kMaxItems ? kMaxItems : n_rb));
+        const int64_t n_col = (rv.cols + span_c - 1) / span_c;   // also for a variable without rows: its column sums are 0
         if (n_rb > kMaxItems || n_ct > kMaxItems || n_col > kMaxItems) return SHARD_EINVAL;
         if (n_rb * n_ct + (int64_t)p->rc_items.size() > kMaxItems) return SHARD_EINVAL;
         if (n_col + (int64_t)p->rc_col_items.size() > kMaxItems) return SHARD_EINVAL;

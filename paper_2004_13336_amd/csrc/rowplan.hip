@@ -8,10 +8,12 @@
 // (named in Section 3 as an optimizer with such reduces) needs exactly these two reductions of the
 // squared gradient, plus two scalars per variable.
 //
-// Work items are (variable, row block, column tile) triples from the plan: kRowBlock rows x one
-// column tile.  Every thread owns 4 adjacent columns (1 where rows do not start on 16-byte
-// boundaries) and walks down the rows in batches of kRowBatch independent 128-bit loads, so the
-// reductions along rows stay in registers and those along columns go through LDS once per item.
+// Work items of the streaming kernels are (variable, row block, column tile) triples from the plan.
+// Every thread owns 4 adjacent columns (1 where rows do not start on 16-byte boundaries) of 8 rows and
+// issues its 8 independent 128-bit loads at once; a workgroup's four wavefronts are stacked along the
+// rows (32 rows x 256 columns) or, for pieces of at most 8 rows, laid side by side (8 rows x 1024
+// columns).  The small per-column and per-row kernels run over item tables of their own, so that a
+// matrix with millions of columns and two rows spreads over the chip like one with the opposite shape.
 // All sums are taken in an order fixed by the plan: results are run-to-run identical.
 #include "device_common.hpp"
 
@@ -33,8 +35,9 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kRowsPerWave = kRowBlock / kWaves;     // 8 rows per wavefront: one batch of independent loads
 typedef Policy<SU_NT_ADAFACTOR> PolAf;
 
-// This thread's part of a tile item: wavefront w takes rows 8w .. 8w+7 of the tile, lane l the columns
-// 4l .. 4l+3 (or the single column l) of the tile.
+// This thread's part of a tile item.  Tall tile: wavefront w takes rows 8w .. 8w+7, lane l the columns
+// 4l .. 4l+3 (or the single column l).  Flat tile: all wavefronts take the same 8 rows, wavefront w the
+// w-th span of columns.
 struct Tile {
   RowColVar v;
   int64_t col0;      // first column this thread owns
@@ -44,7 +47,7 @@ struct Tile {
   int live_here;     // leading ones of those that exist in the full matrix (position = replica offset
                      // + index, compared with the full row count)
   int var, rb, ct;
-  bool vec, col_ok;
+  bool vec, flat, col_ok;
 };
 
 __device__ __forceinline__ int64_t real_rows_of(const RowColVar& v, int r) {
@@ -61,11 +64,17 @@ __device__ __forceinline__ Tile tile_of(const RowColVar* __restrict__ vars, cons
   t.rb = it.rb;
   t.ct = it.ct;
   t.v = vars[it.var];
-  t.vec = t.v.vec != 0;
+  t.vec = (t.v.shape & kRcVec) != 0;
+  t.flat = (t.v.shape & kRcFlat) != 0;
   const int w = t.vec ? 4 : 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  t.col0 = (int64_t)it.ct * (64 * w) + (int64_t)lane * w;
-  t.wrow0 = (int64_t)it.rb * kRowBlock + (int64_t)wave * kRowsPerWave;
+  if (t.flat) {
+    t.col0 = ((int64_t)it.ct * kWaves + wave) * (64 * w) + (int64_t)lane * w;
+    t.wrow0 = (int64_t)it.rb * kRowsPerWave;
+  } else {
+    t.col0 = (int64_t)it.ct * (64 * w) + (int64_t)lane * w;
+    t.wrow0 = (int64_t)it.rb * kRowBlock + (int64_t)wave * kRowsPerWave;
+  }
   t.rows_here = clamp8(t.v.Lr - t.wrow0);
   const int live = clamp8(real_rows_of(t.v, r) - t.wrow0);
   t.live_here = live < t.rows_here ? live : t.rows_here;
@@ -111,9 +120,9 @@ __device__ __forceinline__ double block_sum_f64(double a) {
 
 // ---- row / column sums of squares -------------------------------------------------------------------
 // One pass over x.  Per tile: every thread loads its 8 rows x 4 columns at once; the tile's column
-// sums (over its live rows) are combined across the four wavefronts in LDS, its row sums (over the
-// tile's columns) across the 64 lanes with shuffles; both go to the workspace as partial results that
-// rowcol_p2_kernel adds.  WITH_W: the same pass also reads a second tensor y at the same positions and
+// sums (over its live rows) and row sums (over the tile's columns) are formed with shuffles across the
+// 64 lanes and combined across the four wavefronts in LDS along whichever direction the wavefronts
+// share; both go to the workspace as partial results that rowcol_p2_kernel adds.  WITH_W: the same pass also reads a second tensor y at the same positions and
 // leaves the tile's sum of y^2 over real elements in ypart (Adafactor's RMS of the weights).
 template <bool WITH_W>
 __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __restrict__ vars,
@@ -151,22 +160,43 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
     rs[j] = (a + b) + (c + d);
     if constexpr (WITH_W) sy += (wv[j].x * wv[j].x + wv[j].y * wv[j].y) + (wv[j].z * wv[j].z + wv[j].w * wv[j].w);
   }
-  col_lds[wave][lane][0] = c0; col_lds[wave][lane][1] = c1; col_lds[wave][lane][2] = c2; col_lds[wave][lane][3] = c3;
+  __shared__ float row_lds[kWaves][kRowsPerWave];
+  float* cp = colpart + t.v.cp_off + (int64_t)t.rb * t.v.cols + t.col0;
+  float* rp = rowpart + t.v.rp_off + (int64_t)t.ct * t.v.Lr + t.wrow0;
+  if (t.flat) {
+    // the wavefronts hold different columns of the same rows: column sums are final, row sums are
+    // combined across the wavefronts
+    if (t.col_ok) {
+      if (t.vec) st4<false>(cp, F4{c0, c1, c2, c3});
+      else cp[0] = c0;
+    }
 #pragma unroll
-  for (int j = 0; j < kRowsPerWave; ++j) {
-    const float s = wave_sum(rs[j]);
-    if (lane == 0 && j < t.rows_here) rowpart[t.v.rp_off + (int64_t)t.ct * t.v.Lr + t.wrow0 + j] = s;
-  }
-  __syncthreads();
-  if (wave == 0 && t.col_ok) {
-    F4 tot;
-    tot.x = (col_lds[0][lane][0] + col_lds[1][lane][0]) + (col_lds[2][lane][0] + col_lds[3][lane][0]);
-    tot.y = (col_lds[0][lane][1] + col_lds[1][lane][1]) + (col_lds[2][lane][1] + col_lds[3][lane][1]);
-    tot.z = (col_lds[0][lane][2] + col_lds[1][lane][2]) + (col_lds[2][lane][2] + col_lds[3][lane][2]);
-    tot.w = (col_lds[0][lane][3] + col_lds[1][lane][3]) + (col_lds[2][lane][3] + col_lds[3][lane][3]);
-    float* cp = colpart + t.v.cp_off + (int64_t)t.rb * t.v.cols + t.col0;
-    if (t.vec) st4<false>(cp, tot);
-    else cp[0] = tot.x;
+    for (int j = 0; j < kRowsPerWave; ++j) {
+      const float s = wave_sum(rs[j]);
+      if (lane == 0) row_lds[wave][j] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < t.rows_here)
+      rp[threadIdx.x] = (row_lds[0][threadIdx.x] + row_lds[1][threadIdx.x]) + (row_lds[2][threadIdx.x] + row_lds[3][threadIdx.x]);
+  } else {
+    // the wavefronts hold different rows of the same columns: row sums are final, column sums are
+    // combined across the wavefronts
+    col_lds[wave][lane][0] = c0; col_lds[wave][lane][1] = c1; col_lds[wave][lane][2] = c2; col_lds[wave][lane][3] = c3;
+#pragma unroll
+    for (int j = 0; j < kRowsPerWave; ++j) {
+      const float s = wave_sum(rs[j]);
+      if (lane == 0 && j < t.rows_here) rp[j] = s;
+    }
+    __syncthreads();
+    if (wave == 0 && t.col_ok) {
+      F4 tot;
+      tot.x = (col_lds[0][lane][0] + col_lds[1][lane][0]) + (col_lds[2][lane][0] + col_lds[3][lane][0]);
+      tot.y = (col_lds[0][lane][1] + col_lds[1][lane][1]) + (col_lds[2][lane][1] + col_lds[3][lane][1]);
+      tot.z = (col_lds[0][lane][2] + col_lds[1][lane][2]) + (col_lds[2][lane][2] + col_lds[3][lane][2]);
+      tot.w = (col_lds[0][lane][3] + col_lds[1][lane][3]) + (col_lds[2][lane][3] + col_lds[3][lane][3]);
+      if (t.vec) st4<false>(cp, tot);
+      else cp[0] = tot.x;
+    }
   }
   if constexpr (WITH_W) {
     sy = block_sum1(sy);
@@ -175,9 +205,10 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
 }
 
 // Adds the partial results of phase 1 in a fixed order.  The grid holds, in this order,
-//   one workgroup per column item: 64 columns; wavefront w adds the row blocks w, w+4, ..., the four
-//     results are combined in LDS; other_col (nullable, laid out like col_out) is added; with
-//     colitem_part the item's sum over its columns is kept too (for sum(R) of Adafactor);
+//   one workgroup per column item: 64 columns whose row blocks the four wavefronts share (results
+//     combined in LDS), or 256 columns with a thread each where row blocks are few; other_col
+//     (nullable, laid out like col_out) is added; with colitem_part the item's sum over its columns
+//     is kept too (for sum(R) of Adafactor);
 //   one workgroup per row item: 256 rows with a thread each, or one row of a variable with very many
 //     column tiles, added by the whole workgroup;
 //   with table_out, one workgroup per variable:
@@ -201,24 +232,40 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
   if (b < n_col_items) {
     const ColItem it = col_items[b];
     const RowColVar v = vars[it.var];
-    const int64_t c = (int64_t)it.tile * kColTile + lane;
-    const bool ok = c < v.cols;
-    float s = 0.0f;
-    if (ok)
-      for (int rb = wave; rb < v.n_rb; rb += kWaves) s += colpart[v.cp_off + (int64_t)rb * v.cols + c];
-    lds[wave][lane] = s;
-    __syncthreads();
-    if (wave == 0) {
-      float tot = (lds[0][lane] + lds[1][lane]) + (lds[2][lane] + lds[3][lane]);
-      if (ok) {
+    if (col_span(v.n_rb) == 64) {
+      // many row blocks: 64 columns, wavefront w adds the row blocks w, w+4, ...
+      const int64_t c = (int64_t)it.tile * 64 + lane;
+      const bool ok = c < v.cols;
+      float s = 0.0f;
+      if (ok)
+        for (int rb = wave; rb < v.n_rb; rb += kWaves) s += colpart[v.cp_off + (int64_t)rb * v.cols + c];
+      lds[wave][lane] = s;
+      __syncthreads();
+      if (wave == 0) {
+        float tot = (lds[0][lane] + lds[1][lane]) + (lds[2][lane] + lds[3][lane]);
+        if (ok) {
+          if (other_col) tot += other_col[v.col_off + c];
+          col_out[v.col_off + c] = tot;
+        } else {
+          tot = 0.0f;
+        }
+        if (colitem_part) {
+          tot = wave_sum(tot);
+          if (lane == 0) colitem_part[b] = tot;
+        }
+      }
+    } else {
+      // few row blocks: 256 columns, a thread per column
+      const int64_t c = (int64_t)it.tile * 256 + threadIdx.x;
+      float tot = 0.0f;
+      if (c < v.cols) {
+        for (int rb = 0; rb < v.n_rb; ++rb) tot += colpart[v.cp_off + (int64_t)rb * v.cols + c];
         if (other_col) tot += other_col[v.col_off + c];
         col_out[v.col_off + c] = tot;
-      } else {
-        tot = 0.0f;
       }
       if (colitem_part) {
-        tot = wave_sum(tot);
-        if (lane == 0) colitem_part[b] = tot;
+        tot = block_sum1(tot);
+        if (threadIdx.x == 0) colitem_part[b] = tot;
       }
     }
     return;
@@ -268,17 +315,18 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
 // sum(R) over all replicas' rows follows from all-reduced quantities:
 //   sum(R) = beta2 * (all-reduced sum of the old R) + (1-beta2) * (sum_j all-reduced column sums + rows cols eps1).
 
-// One wavefront per column item: the item's sum of the all-reduced column sums (when phase 1 ran
+// One workgroup per column item: the item's sum of the all-reduced column sums (when phase 1 ran
 // elsewhere and rowcol_p2_kernel could not leave it).
-__global__ __launch_bounds__(64) void adafactor_colsum_kernel(const RowColVar* __restrict__ vars,
-                                                              const ColItem* __restrict__ col_items,
-                                                              const float* __restrict__ col_sq_global,
-                                                              float* __restrict__ colitem_part) {
+__global__ __launch_bounds__(kBlock) void adafactor_colsum_kernel(const RowColVar* __restrict__ vars,
+                                                                  const ColItem* __restrict__ col_items,
+                                                                  const float* __restrict__ col_sq_global,
+                                                                  float* __restrict__ colitem_part) {
   const ColItem it = col_items[blockIdx.x];
   const RowColVar v = vars[it.var];
-  const int64_t c = (int64_t)it.tile * kColTile + threadIdx.x;
-  float s = c < v.cols ? col_sq_global[v.col_off + c] : 0.0f;
-  s = wave_sum(s);
+  const int span = col_span(v.n_rb);
+  const int64_t c = (int64_t)it.tile * span + threadIdx.x;
+  float s = ((int)threadIdx.x < span && c < v.cols) ? col_sq_global[v.col_off + c] : 0.0f;
+  s = block_sum1(s);
   if (threadIdx.x == 0) colitem_part[blockIdx.x] = s;
 }
 
@@ -312,8 +360,9 @@ __global__ __launch_bounds__(kBlock) void adafactor_state_kernel(const RowColVar
   if (b < n_col_items) {
     const ColItem it = col_items[b];
     const RowColVar v = vars[it.var];
-    const int64_t c = (int64_t)it.tile * kColTile + threadIdx.x;
-    if (threadIdx.x >= kColTile || c >= v.cols || v.rows == 0) return;    // no rows: the state stays as it is
+    const int span = col_span(v.n_rb);
+    const int64_t c = (int64_t)it.tile * span + threadIdx.x;
+    if ((int)threadIdx.x >= span || c >= v.cols || v.rows == 0) return;    // no rows: the state stays as it is
     if (v.cols == 1) {
       inv_c[v.col_off] = 1.0f;                     // vector: Vhat = R, no column state
       return;
@@ -541,7 +590,7 @@ hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, floa
   {
     ProfScope ps(p, SHARD_K_ADAFACTOR_STATE, stream);
     if (!have_column_item_sums && n_col > 0)
-      hipLaunchKernelGGL(adafactor_colsum_kernel, dim3((unsigned)n_col), dim3(64), 0, stream, vars, col_items,
+      hipLaunchKernelGGL(adafactor_colsum_kernel, dim3((unsigned)n_col), dim3(kBlock), 0, stream, vars, col_items,
                          col_sq_global, colitem_part);
     hipLaunchKernelGGL(adafactor_sumr_kernel, dim3((unsigned)p->V), dim3(kBlock), 0, stream, vars,
                        (const float*)colitem_part, table_global, sum_r, k);

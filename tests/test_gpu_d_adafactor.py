@@ -119,9 +119,6 @@ def test_every_phase_against_the_sharded_oracle_and_the_result_against_the_unsha
             su.shard_update_adafactor_moments(plan, r, G[r], st.R[r], st.C[r], row_sq[r], col_g, tab_g, HP, t, usq[r])
             o2.append(oracle.adafactor_shard_moments(oplan, r, G_host[r], st.rows_of(r, R_before[r]),
                                                      st.cols_of(C_before[r]), o1[r][0], o_col_g, o_tab_g, HP, t))
-            # phase 3 must follow phase 2 of the same replica: the factors live in the plan's workspace
-            if r == 0:
-                usq_all = None
         R_h, C_h, usq_h = to_host(st.R), to_host(st.C), to_host(usq)
         for r in range(N):
             for i in range(V):
@@ -283,19 +280,14 @@ def test_bert_large_shaped_full_size_sampled_variables(r):
 
 
 def test_argument_errors():
+    import ctypes as C
+    from paper_2004_13336_amd._lib import AdafactorHP
     flat = su.shard_plan_bind(su.shard_plan([64, 8], 2))
     t = torch.zeros(64, dtype=torch.float32, device=DEV)
-    with pytest.raises(su.ShardError) as e:
-        su.lib().shard_update_adafactor  # the symbol exists
-        import ctypes as C
-        from paper_2004_13336_amd._lib import AdafactorHP
-        hp = AdafactorHP(1e-30, 1e-3, 1.0, 0.8, 1e-2)
-        rc = su.lib().shard_update_adafactor(flat.handle, 0, C.c_void_p(t.data_ptr()), C.c_void_p(t.data_ptr()),
-                                             C.c_void_p(t.data_ptr()), C.c_void_p(t.data_ptr()), None, C.byref(hp), 1,
-                                             None, None, None, None)
-        if rc != 0:
-            raise su.ShardError(rc, "shard_update_adafactor")
-    assert e.value.status == -1                                       # a flat plan has no rows and columns
+    p = C.c_void_p(t.data_ptr())
+    hp = AdafactorHP(1e-30, 1e-3, 1.0, 0.8, 1e-2)
+    # a flat plan has no rows and columns
+    assert su.lib().shard_update_adafactor(flat.handle, 0, p, p, p, p, None, C.byref(hp), 1, None, None, None, None) == -1
     flat.free()
     plan = su.shard_plan_bind(su.shard_plan_rows([16], [8], 2))
     W = torch.zeros(plan.S, dtype=torch.float32, device=DEV)
