@@ -279,10 +279,13 @@ def table(args, torch, su, cfgs, path):
     """Every config x stage, kernel time from the library's event pairs; written as JSON."""
     rows = []
     for cfg in cfgs:
-        for N in cfg.replicas:
+        # N = 1 is the replicated update the paper compares against (every replica updates the whole
+        # model); where a configuration does not list it, only its update stage is timed
+        for N in sorted(set(cfg.replicas) | {1}):
             r = 0
             big = cfg.total > 1_000_000_000
-            wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=not (big and N == 1))
+            extra = N not in cfg.replicas
+            wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=not ((big and N == 1) or extra))
             plan, hp, S = wb.plan, wb.hp(), wb.S
             if cfg.mixed_bf16:
                 wb.w16 = torch.zeros(S, dtype=torch.bfloat16, device="cuda")
@@ -322,7 +325,8 @@ def table(args, torch, su, cfgs, path):
                     us += 1e3 * ms / max(n, 1)
                 su.shard_profile_enable(plan, False)
                 state_bytes = nbytes
-                rows.append({"config": cfg.name, "N": N, "stage": name, "S": S, "kernel_us": round(us, 2),
+                rows.append({"config": cfg.name, "N": N, "stage": name + (" (replicated)" if extra else ""), "S": S,
+                             "kernel_us": round(us, 2),
                              "params_per_s": wb.real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                              "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                              "cache_resident": state_bytes < 256e6})
@@ -330,7 +334,7 @@ def table(args, torch, su, cfgs, path):
             wb.free()
             del wb
             torch.cuda.empty_cache()
-            if all(len(s) <= 2 for s in cfg.shapes) and cfg.total < 1_000_000_000:
+            if all(len(s) <= 2 for s in cfg.shapes) and cfg.total < 1_000_000_000 and not extra:
                 rows.append(_adafactor_row(cfg, N, torch, su))
                 print("table:", rows[-1], file=sys.stderr, flush=True)
     with open(path, "w") as f:
