@@ -62,7 +62,8 @@ enum {
   SHARD_ENOMEM = -2,   /* host allocation failed, or workspace too small */
   SHARD_EALIGN = -3,   /* a packed-shard device pointer is not 16-byte aligned */
   SHARD_EHIP = -4,     /* the HIP runtime reported an error (no device, launch failure) */
-  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one */
+  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one, or the workspace holds the
+                          intermediate results of another call (shard_update_adafactor_apply) */
 };
 
 enum { SHARD_F32 = 0, SHARD_BF16 = 1 };   /* element types of formatted buffers */
@@ -291,8 +292,9 @@ int shard_reduce_sq_rows_cols(shard_plan_t* plan, int r, const float* x, float* 
  *     col_sq_global and table_global, keeps the factors of 1/sqrt(Vhat) in the plan's workspace and
  *     writes u_sumsq_out [V] = this replica's sum of U^2 over real elements.  The caller all-reduces it.
  *   shard_update_adafactor_apply: updates w (and writes bf16(w') to w_bf16_out, if not NULL) from the
- *     factors phase 2 left in the workspace; must follow the moments call of the same step on the same
- *     plan, with the same hp and step.
+ *     factors phase 2 left in the workspace; must follow the moments call of the same replica and step
+ *     on the same plan, with the same hp (SHARD_ESTATE if the last moments call on this plan was for
+ *     another replica or step: one plan holds one replica's factors at a time).
  *   shard_update_adafactor: all three; other_col_sq [total_cols], other_table [V][2], other_u_sumsq [V]
  *     (each may be NULL = zeros) are added to the local results in place of the all-reduces.
  * Requirements: a bound row plan; eps1 > 0, eps2 >= 0, clip_threshold > 0, decay_exponent > 0,

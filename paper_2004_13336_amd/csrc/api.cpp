@@ -144,7 +144,7 @@ const char* shard_strerror(int status) {
     case SHARD_ENOMEM: return "out of memory or workspace too small";
     case SHARD_EALIGN: return "packed-shard pointer not 16-byte aligned";
     case SHARD_EHIP: return "HIP runtime error";
-    case SHARD_ESTATE: return "plan has no bound workspace";
+    case SHARD_ESTATE: return "plan has no bound workspace, or its workspace holds another call's intermediate results";
     default: return "unknown status";
   }
 }
@@ -497,6 +497,8 @@ int shard_update_adafactor_moments(shard_plan_t* p, int r, const float* g, float
       (p->rc_total_cols > 0 && (C == nullptr || col_sq_global == nullptr)))
     return SHARD_EINVAL;
   if (p->S > 0 && (rc = check_shard_ptr(g)) != SHARD_OK) return rc;
+  p->af_r = r;
+  p->af_step = step;
   return hip_status(launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq_global, table_global, k, false, nullptr,
                                              u_sumsq_out, nullptr, as_stream(stream)));
 }
@@ -512,6 +514,7 @@ int shard_update_adafactor_apply(shard_plan_t* p, int r, float* w, const float* 
   if (table_global == nullptr || u_sumsq_global == nullptr) return SHARD_EINVAL;
   if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK) return rc;
   if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  if (p->af_r != r || p->af_step != step) return SHARD_ESTATE;   // the workspace holds another call's factors
   return hip_status(launch_adafactor_apply(p, r, w, g, table_global, u_sumsq_global, w_bf16_out, k, as_stream(stream)));
 }
 
@@ -531,6 +534,7 @@ int shard_update_adafactor(shard_plan_t* p, int r, float* w, const float* g, flo
   float* col_sq = reinterpret_cast<float*>(p->ws.base + p->ws.af_colsq);
   float* table = reinterpret_cast<float*>(p->ws.base + p->ws.af_table);
   float* usq = reinterpret_cast<float*>(p->ws.base + p->ws.af_usq);
+  p->af_r = -1;                                                  // the fused call leaves nothing for a later apply
   hipError_t e = launch_adafactor_partials(p, r, w, g, R, other_col_sq, other_table, row_sq, col_sq, table, true, s);
   if (e == hipSuccess) e = launch_adafactor_moments(p, r, g, R, C, row_sq, col_sq, table, k, true, other_u_sumsq, nullptr, usq, s);
   if (e == hipSuccess) e = launch_adafactor_apply(p, r, w, g, table, usq, w_bf16_out, k, s);

@@ -151,6 +151,10 @@ struct shard_plan_s {
   bool slot_valid[su::kPtrSlots] = {false, false, false, false};
   uint64_t clock = 0;
 
+  // Adafactor: which (replica, step) the factors in the workspace belong to; -1 = none yet
+  int af_r = -1;
+  int64_t af_step = -1;
+
   bool prof = false;
   std::vector<su::ProfRecord> prof_live;   // recorded, not yet read
   std::vector<su::ProfRecord> prof_free;   // event pairs ready for reuse

@@ -300,6 +300,20 @@ def test_argument_errors():
         su.shard_update_adafactor(plan, 0, W, W.clone(), R, Cst, HP, 0)
     with pytest.raises(su.ShardError):
         su.shard_update_adafactor(plan, 2, W, W.clone(), R, Cst, HP, 1)
+    # apply needs the factors of the same replica and step in the workspace
+    tab = torch.ones((1, 2), dtype=torch.float32, device=DEV); usq = torch.ones(1, dtype=torch.float32, device=DEV)
+    rows_sq = torch.zeros(8, dtype=torch.float32, device=DEV); col_sq = torch.ones(8, dtype=torch.float32, device=DEV)
+    with pytest.raises(su.ShardError) as e:
+        su.shard_update_adafactor_apply(plan, 0, W, W.clone(), tab, usq, HP, 1)
+    assert e.value.status == -5
+    su.shard_update_adafactor_moments(plan, 1, W.clone(), R.clone(), Cst.clone(), rows_sq, col_sq, tab, HP, 1, usq.clone())
+    with pytest.raises(su.ShardError) as e:
+        su.shard_update_adafactor_apply(plan, 0, W, W.clone(), tab, usq, HP, 1)
+    assert e.value.status == -5
+    with pytest.raises(su.ShardError) as e:
+        su.shard_update_adafactor_apply(plan, 1, W, W.clone(), tab, usq, HP, 2)
+    assert e.value.status == -5
+    su.shard_update_adafactor_apply(plan, 1, W.clone(), W.clone(), tab, usq, HP, 1)
     # zero gradient: eps1 keeps everything finite and the weights stay
     W.normal_(0.0, 0.02)
     before = W.clone()
