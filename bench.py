@@ -52,6 +52,10 @@ def parse_args():
     ap.add_argument("--chunk", type=int, default=0, help="chunk_elems of the plan (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", default=None, help="also time every config x stage and write a JSON table here")
+    ap.add_argument("--stage", default=None,
+                    help="instead of the headline step, run ONE stage of --config at --replicas for --steps launches "
+                         "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all) "
+                         "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run one plain device copy of 1 GiB (2^28 float32), so that a rocprofv3 --pmc run "
                          "has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -341,7 +345,60 @@ def table(args, torch, su, cfgs, path):
         json.dump(rows, f, indent=1)
 
 
-def _adafactor_row(cfg, N, torch, su):
+def one_stage(args, torch, su, cfgs):
+    """One stage of one configuration, --warmup + --steps launches; a small JSON line of its own."""
+    cfg = [c for c in cfgs if c.name == args.config][0]
+    N, r, name = args.replicas, args.replica_id, args.stage
+    if name == "adafactor":
+        row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
+        print(json.dumps(row))
+        return
+    needs_full = name in ("shard_format", "unshard_format", "shard_format_all")
+    wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full)
+    plan, S = wb.plan, wb.S
+    hp = wb.hp()
+    adam_hp = hp if cfg.optimizer == "adam" else {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8, "weight_decay": 0.0}
+    lamb_hp = hp if cfg.optimizer == "lamb" else {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-6, "weight_decay": 0.01}
+    mom_hp = hp if cfg.optimizer == "momentum" else {"lr": 0.1, "mu": 0.9, "weight_decay": 5e-5}
+    lars_hp = dict(mom_hp, trust_coeff=0.001, eps=0.0)
+    if cfg.mixed_bf16:
+        wb.w16 = torch.zeros(S, dtype=torch.bfloat16, device="cuda")
+    stages = {
+        "adam": (lambda t: su.shard_update_adam(plan, r, wb.w, wb.g, wb.m, wb.v, adam_hp, t, w_bf16_out=wb.w16),
+                 ["adam"], (30 if cfg.mixed_bf16 else 28) * S),
+        "momentum": (lambda t: su.shard_update_momentum(plan, r, wb.w, wb.g, wb.m, mom_hp), ["momentum"], 20 * S),
+        "lars": (lambda t: su.shard_update_lars(plan, r, wb.w, wb.g, wb.m, lars_hp, other_replicas_sumsq=wb.other),
+                 ["lars_p1", "norm_reduce", "lars_p2"], 28 * S),
+        "lamb": (lambda t: su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, lamb_hp, t, other_replicas_sumsq=wb.other),
+                 ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S),
+    }
+    if needs_full:
+        stages["shard_format"] = (lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S)
+        stages["unshard_format"] = (lambda t: su.unshard_format(plan, wb.gathered, wb.full_w), ["unshard"],
+                                    4 * N * S + 4 * cfg.total)
+        stages["shard_format_all"] = (lambda t: su.shard_format_all(plan, wb.full_g, wb.gathered), ["format"],
+                                      4 * N * S + 4 * cfg.total)
+    if name not in stages:
+        raise SystemExit("unknown --stage %s" % name)
+    fn, kernels, nbytes = stages[name]
+    for t in range(1, 1 + max(args.warmup, 1)):
+        fn(t)
+    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+    for t in range(100, 100 + args.steps):
+        fn(t)
+    torch.cuda.synchronize()
+    per = {}
+    for k in kernels:
+        n, ms = su.shard_profile_read(plan, k)
+        per[k] = round(1e3 * ms / max(n, 1), 2)
+    us = sum(per.values())
+    print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
+                      "total_us": round(us, 2), "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                      "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}))
+    wb.free()
+
+
+def _adafactor_row(cfg, N, torch, su, warmup=5, iters=50):
     """Adafactor on the row plan of the same variables (matrices by rows, vectors as n x 1): 24 B/slot
     (g and w read by the reductions, g by the clipping sum, g and w read and w written by the update)."""
     shapes = [(s[0], s[1]) if len(s) == 2 else (s[0], 1) for s in cfg.shapes]
@@ -355,11 +412,10 @@ def _adafactor_row(cfg, N, torch, su):
     R = torch.zeros(max(total_rows, 1), dtype=torch.float32, device="cuda")
     C = torch.zeros(max(total_cols, 1), dtype=torch.float32, device="cuda")
     hp = {"eps1": 1e-30, "eps2": 1e-3, "clip_threshold": 1.0, "decay_exponent": 0.8, "max_rho": 1e-2}
-    for t in range(1, 6):
+    for t in range(1, 1 + max(warmup, 1)):
         su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
     su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
-    iters = 50
-    for t in range(6, 6 + iters):
+    for t in range(100, 100 + iters):
         su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
     torch.cuda.synchronize()
     us = 0.0
@@ -397,6 +453,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    if args.stage:
+        one_stage(args, torch, su, CONFIGS)
+        return
     out = headline(args, torch, su, CONFIGS)
     if args.table:
         table(args, torch, su, CONFIGS, args.table)
