@@ -286,10 +286,13 @@ def shard_update_lars(plan: Plan, r: int, w, g, m, hp, other_replicas_sumsq=None
 
 def shard_plan_rowcol_layout(plan: Plan):
     """(row_off[V], col_off[V], total_rows, total_cols) of a row plan's row-sum and column-sum outputs."""
-    ro = (C.c_int64 * max(plan.V, 1))(); co = (C.c_int64 * max(plan.V, 1))()
-    tr, tc = C.c_int64(), C.c_int64()
-    _check(lib().shard_plan_rowcol_layout(plan.handle, ro, co, C.byref(tr), C.byref(tc)), "shard_plan_rowcol_layout")
-    return tuple(ro[: plan.V]), tuple(co[: plan.V]), tr.value, tc.value
+    cached = getattr(plan, "_rowcol_layout", None)          # a plan never changes: asked of the library once
+    if cached is None:
+        ro = (C.c_int64 * max(plan.V, 1))(); co = (C.c_int64 * max(plan.V, 1))()
+        tr, tc = C.c_int64(), C.c_int64()
+        _check(lib().shard_plan_rowcol_layout(plan.handle, ro, co, C.byref(tr), C.byref(tc)), "shard_plan_rowcol_layout")
+        cached = plan._rowcol_layout = (tuple(ro[: plan.V]), tuple(co[: plan.V]), tr.value, tc.value)
+    return cached
 
 
 def shard_reduce_sq_rows_cols(plan: Plan, r: int, x, row_out, col_out, stream=None):
