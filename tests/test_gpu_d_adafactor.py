@@ -320,3 +320,50 @@ def test_argument_errors():
     su.shard_update_adafactor(plan, 0, W, torch.zeros_like(W), R, Cst, HP, 1)
     assert torch.equal(W, before) and bool(torch.isfinite(R).all()) and bool((R > 0).all())
     plan.free()
+
+
+def test_late_step_with_a_warm_state():
+    # t = 250000: rho = 1/sqrt(t) = 0.002 (below max_rho), beta2 = 1 - t^-0.8 within 5e-5 of 1, and a row/column
+    # state that does not come from zero (row and column totals differ, as after loading an old checkpoint)
+    shapes, N, t = [(40, 64), (33, 1), (9, 260)], 4, 250000
+    st = Replicas(shapes, N, 8, 63)
+    plan, oplan, V = st.plan, st.oplan, st.V
+    rng = np.random.default_rng(5)
+    st.o_R = [rng.uniform(0.5e-6, 2e-6, s[0]).astype(np.float32) * max(s[1], 1) for s in shapes]
+    st.o_C = [rng.uniform(0.5e-6, 2e-6, s[1]).astype(np.float32) * s[0] for s in shapes]
+    R_host = np.zeros((N, st.total_rows), np.float32)
+    C_host = np.zeros(st.total_cols, np.float32)
+    for i, (rows, cols) in enumerate(shapes):
+        C_host[st.col_off[i]:st.col_off[i] + cols] = st.o_C[i]
+        for r in range(N):
+            real = oplan.real_rows(i, r)
+            R_host[r, st.row_off[i]:st.row_off[i] + real] = st.o_R[i][r * oplan.Lr[i]:r * oplan.Lr[i] + real]
+    st.R = to_dev(R_host)
+    st.C = to_dev(np.tile(C_host, (N, 1)))
+    gs, G_host = st.grads(1)
+    G = Rows(G_host)
+    f = dict(dtype=torch.float32, device=DEV)
+    row_sq = torch.zeros((N, st.total_rows), **f); col_sq = torch.zeros((N, st.total_cols), **f)
+    table = torch.zeros((N, V, 2), **f); usq = torch.zeros((N, V), **f)
+    for r in range(N):
+        su.shard_update_adafactor_partials(plan, r, st.W[r], G[r], st.R[r], row_sq[r], col_sq[r], table[r])
+    col_g, tab_g = col_sq.sum(dim=0), table.sum(dim=0)
+    R0 = st.R.clone(); C0 = st.C.clone()
+    for r in range(N):
+        su.shard_update_adafactor_moments(plan, r, G[r], st.R[r], st.C[r], row_sq[r], col_g, tab_g, HP, t, usq[r])
+    usq_g = usq.sum(dim=0)
+    for r in range(N):
+        Rr, Cr = R0[r].clone(), C0[r].clone()
+        su.shard_update_adafactor_moments(plan, r, G[r], Rr, Cr, row_sq[r], col_g, tab_g, HP, t, torch.empty(V, **f))
+        su.shard_update_adafactor_apply(plan, r, st.W[r], G[r], tab_g, usq_g, HP, t)
+    want_w, want_R, want_C = oracle.adafactor_unsharded_step(shapes, st.ws, gs, st.o_R, st.o_C, HP, t)
+    full = oracle.unshard_format(oplan, st.W.host())
+    R_h, C_h = to_host(st.R), to_host(st.C)
+    for i, (rows, cols) in enumerate(shapes):
+        assert_weights_close(full[i], want_w[i], "var %d" % i)
+        assert np.abs(full[i] - st.ws[i]).max() > 0                   # it moved
+        R_all = np.concatenate([st.rows_of(r, R_h[r])[i] for r in range(N)])[:rows]
+        np.testing.assert_allclose(R_all, want_R[i], rtol=4e-6)
+        if cols > 1:
+            np.testing.assert_allclose(st.cols_of(C_h[0])[i], want_C[i], rtol=4e-6)
+    plan.free()
