@@ -230,6 +230,10 @@ int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard
   if (!p->chunks.empty() && hipMemcpyAsync(ws.base + ws.chunks, p->chunks.data(), p->chunks.size() * sizeof(ChunkDesc),
                                            hipMemcpyHostToDevice, s) != hipSuccess)
     return SHARD_EHIP;
+  if (!p->full_chunks.empty() && hipMemcpyAsync(ws.base + ws.full_chunks, p->full_chunks.data(),
+                                                p->full_chunks.size() * sizeof(FullChunk), hipMemcpyHostToDevice,
+                                                s) != hipSuccess)
+    return SHARD_EHIP;
   if (p->row_plan) {
     if (!p->rc_vars.empty() && hipMemcpyAsync(ws.base + ws.rc_vars, p->rc_vars.data(), p->rc_vars.size() * sizeof(RowColVar),
                                               hipMemcpyHostToDevice, s) != hipSuccess)

@@ -37,6 +37,20 @@ struct ChunkDesc {
 };
 static_assert(sizeof(ChunkDesc) == 16, "ChunkDesc layout");
 
+// Flat plans only: one work item of the whole-model copies (unshard_format, shard_format_all).
+// With stride == L, replica r's piece of variable i is the slots [r*L_i, (r+1)*L_i) of the variable
+// padded to N*L_i slots, so the gathered buffer is an [N][L_i] view of that padded variable.  An item
+// is `len` consecutive slots of it starting at p0; items are listed variable by variable, so the
+// number of workgroups depends on the model size and not on how many (and how small) the pieces are.
+// Used when pieces are small (plan_build decides, shard_plan_s::flat_copies); with few large pieces
+// the replica-by-replica walk over ChunkDesc items measures 7 % faster.
+struct FullChunk {
+  int64_t p0;       // first padded slot (= flat index in the full tensor)
+  int32_t var;
+  int32_t len;
+};
+static_assert(sizeof(FullChunk) == 16, "FullChunk layout");
+
 // Row plans only: one variable seen as a row-major rows x cols matrix whose rows are sharded, and the
 // work items of the kernels that keep rows and columns apart.
 struct RowColVar {
@@ -113,6 +127,7 @@ struct Workspace {
   size_t bytes = 0;
   // byte offsets inside base
   size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
+  size_t full_chunks = 0;                                             // flat plans only
   size_t rc_vars = 0, rc_items = 0, rc_colpart = 0, rc_rowpart = 0;   // row plans only
   size_t rc_col_items = 0, rc_row_items = 0, rc_colitem_part = 0;
   // Adafactor (row plans only): per-item partial sums, per-variable scalars, the factors of 1/sqrt(Vhat),
@@ -135,6 +150,8 @@ struct shard_plan_s {
   std::vector<uint32_t> flags;
   std::vector<su::VarDesc> vars;
   std::vector<su::ChunkDesc> chunks;
+  std::vector<su::FullChunk> full_chunks;  // flat plans only
+  bool flat_copies = false;                // whole-model copies walk full_chunks instead of (replica, chunk)
   bool row_plan = false;
   std::vector<su::RowColVar> rc_vars;      // row plans only
   std::vector<su::RowColItem> rc_items;

@@ -311,6 +311,128 @@ __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, 
   }
 }
 
+// ---- whole-model copies on a flat plan, variable by variable ---------------------------------------
+// unshard_format and shard_format_all move every variable between its full tensor and the N rows of
+// the gathered buffer.  On a flat plan the gathered buffer holds, for variable i, an [N][L_i] view of
+// the variable padded to N*L_i slots: padded slot p lives in row p / L_i at off_i + p % L_i, and
+// the full tensor is the first n_i padded slots.  Work items are chunks of padded slots (FullChunk),
+// cut into tiles like the items above: the full-tensor side of a tile is one contiguous span, the
+// gathered side consists of runs of L_i slots.  The number of workgroups follows the model size, so
+// thousands of replicas with pieces of a few slots cost no more launches' worth of work than eight.
+// Units (4 or 8 slots) never straddle two pieces because L_i is a multiple of 8 on the VEC path.
+
+// Slot `d` counted from the start of piece r0 (d < L + 16384): which piece and where in it.
+__device__ __forceinline__ void locate(int64_t d, int64_t L, int64_t r0, int64_t& r, int64_t& k) {
+  if (L >= (int64_t)1 << 30) {               // a tile can reach into the next piece at most
+    const bool next = d >= L;
+    r = r0 + (next ? 1 : 0);
+    k = next ? d - L : d;
+  } else {                                    // d < 2^30 + 2^14: 32-bit division
+    const uint32_t q = (uint32_t)d / (uint32_t)L;
+    r = r0 + q;
+    k = (int64_t)((uint32_t)d - q * (uint32_t)L);
+  }
+}
+
+// TO_FULL: gathered -> full tensors (unshard_format), padding dropped.
+// otherwise: full tensors -> gathered rows (shard_format_all), padding written as zeros.
+template <typename Pol, int SRC, int DST, int U, bool VEC, bool TO_FULL>
+__device__ __forceinline__ void reformat_flat_body(const VarDesc* __restrict__ vars,
+                                                   const FullChunk* __restrict__ fchunks,
+                                                   const void* const* __restrict__ ptrs, void* packed,
+                                                   int64_t row_stride, int tiles_per_chunk) {
+  typedef typename ElemOf<SRC>::type SrcT;
+  typedef typename ElemOf<DST>::type DstT;
+  typedef typename ElemOf<TO_FULL ? DST : SRC>::type FullT;
+  typedef typename ElemOf<TO_FULL ? SRC : DST>::type PackT;
+  constexpr int UNIT = UnitOf<SRC, DST>::n;
+  constexpr int TILE = kCopyBlock * U * UNIT;
+  const int item = blockIdx.x / tiles_per_chunk;
+  const int tile = blockIdx.x - item * tiles_per_chunk;
+  const FullChunk fc = fchunks[item];
+  const int base = tile * TILE;
+  if (base >= fc.len) return;
+  const VarDesc vd = vars[fc.var];
+  const int64_t p_tile = fc.p0 + base;                       // first padded slot of the tile = flat index
+  if (TO_FULL && p_tile >= vd.n) return;                     // a tile of padding: nothing to restore
+  const int here = fc.len - base < TILE ? fc.len - base : TILE;
+  const int64_t r0 = p_tile / vd.L;
+  const int64_t k0 = p_tile - r0 * vd.L;
+  const void* ptr = ptrs[fc.var];
+  FullT* full = (FullT*)const_cast<void*>(ptr) + p_tile;     // not dereferenced past the variable's end
+  PackT* rows = (PackT*)packed + vd.off;
+  const bool vec = VEC && (reinterpret_cast<uintptr_t>(full) & 15u) == 0;
+  const int64_t real = vd.n - p_tile;                        // slots of the tile that exist in the full tensor (may exceed it)
+  if (vec) {
+    uint32_t x[U][UNIT];
+    int64_t po[U];                                           // offset of the unit in the gathered buffer, -1: none
+    const bool single = k0 + here <= vd.L;                   // the whole tile lies in piece r0
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
+      po[i] = -1;
+      if (e < here) {
+        int64_t r = r0, k = k0 + e;
+        if (!single) locate(k0 + e, vd.L, r0, r, k);
+        po[i] = r * row_stride + k;
+        if (TO_FULL) {
+          if (e + UNIT <= real) load_unit<Pol, SRC, UNIT>((const SrcT*)rows + po[i], x[i]);
+        } else {
+          if (e + UNIT <= real) load_unit<Pol, SRC, UNIT>((const SrcT*)full + e, x[i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
+      if (po[i] < 0) continue;
+      if (e + UNIT <= real) {
+#pragma unroll
+        for (int j = 0; j < UNIT; ++j) x[i][j] = convert<SRC, DST>(x[i][j]);
+        if (TO_FULL) store_unit<Pol, DST, UNIT>((DstT*)full + e, x[i]);
+        else store_unit<Pol, DST, UNIT>((DstT*)rows + po[i], x[i]);
+      } else if (TO_FULL) {
+        // the unit that straddles the end of the variable: its real slots one by one
+        for (int j = 0; j < UNIT; ++j)
+          if (e + j < real) ((DstT*)full)[e + j] = (DstT)convert<SRC, DST>((uint32_t)((const SrcT*)rows)[po[i] + j]);
+      } else {
+        // past (or across) the end of the variable: real slots, then zeros
+#pragma unroll
+        for (int j = 0; j < UNIT; ++j)
+          x[i][j] = (e + j < real) ? convert<SRC, DST>((uint32_t)((const SrcT*)full)[e + j]) : 0u;
+        store_unit<Pol, DST, UNIT>((DstT*)rows + po[i], x[i]);
+      }
+    }
+  } else {
+    for (int e = threadIdx.x; e < here; e += kCopyBlock) {
+      const int64_t p = p_tile + e;
+      const int64_t r = p / vd.L, k = p - r * vd.L;
+      const int64_t o = r * row_stride + k;
+      if (TO_FULL) {
+        if (e < real) ((DstT*)full)[e] = (DstT)convert<SRC, DST>((uint32_t)((const SrcT*)rows)[o]);
+      } else {
+        ((DstT*)rows)[o] = (DstT)((e < real) ? convert<SRC, DST>((uint32_t)((const SrcT*)full)[e]) : 0u);
+      }
+    }
+  }
+}
+
+template <int SRC, int DST, bool VEC>
+__global__ __launch_bounds__(kCopyBlock) void unshard_flat_kernel(const VarDesc* __restrict__ vars,
+                                                              const FullChunk* __restrict__ fchunks,
+                                                              const void* const* __restrict__ ptrs, void* gathered,
+                                                              int64_t row_stride, int tiles_per_chunk) {
+  reformat_flat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, fchunks, ptrs, gathered, row_stride, tiles_per_chunk);
+}
+
+template <int SRC, int DST, bool VEC>
+__global__ __launch_bounds__(kCopyBlock) void format_all_flat_kernel(const VarDesc* __restrict__ vars,
+                                                                 const FullChunk* __restrict__ fchunks,
+                                                                 const void* const* __restrict__ ptrs, void* out,
+                                                                 int64_t row_stride, int tiles_per_chunk) {
+  reformat_flat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, fchunks, ptrs, out, row_stride, tiles_per_chunk);
+}
+
 template <int SRC, int DST, bool VEC>
 __global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __restrict__ vars,
                                                         const ChunkDesc* __restrict__ chunks,
@@ -877,6 +999,19 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kCopyBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
+  if (MODE != 0 && p->flat_copies) {
+    // flat plan: variable by variable over the padded variables (same tiles, another item table)
+    const FullChunk* fchunks = ws_at<FullChunk>(p, p->ws.full_chunks);
+    const dim3 gf((unsigned)((int64_t)p->full_chunks.size() * tiles_per_chunk));
+    if constexpr (MODE == 2) {
+      if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+      else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+    } else if constexpr (MODE == 1) {
+      if (vec) hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+      else hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+    }
+    return;
+  }
   if constexpr (MODE == 2) {
     if (vec)
       hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride,

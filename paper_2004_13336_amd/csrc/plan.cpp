@@ -94,6 +94,26 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
     }
     for (int s = 0; s < kPtrSlots; ++s) p->slot_ptrs[s].assign(V, nullptr);
 
+    p->full_chunks.clear();
+    if (!cols) {
+      // items of the whole-model copies: the padded variables cut into chunks, variable by variable;
+      // their number is at most N * (number of chunks), which the check above keeps below 2^31
+      for (int i = 0; i < V; ++i) {
+        const int64_t padded = (int64_t)N * p->L[i];
+        for (int64_t p0 = 0; p0 < padded; p0 += chunk) {
+          FullChunk fc;
+          fc.p0 = p0;
+          fc.var = i;
+          fc.len = (int32_t)((padded - p0 < chunk) ? (padded - p0) : chunk);
+          p->full_chunks.push_back(fc);
+        }
+      }
+      // The replica-by-replica walk launches N * (chunks per shard) items; when more than a fifth of
+      // them are fragments (pieces much shorter than a chunk), the variable-by-variable walk wins.
+      p->flat_copies = (int64_t)N * (int64_t)p->chunks.size() * 4 > (int64_t)p->full_chunks.size() * 5;
+      if (!p->flat_copies) std::vector<FullChunk>().swap(p->full_chunks);     // not needed: keep the workspace small
+    }
+
     p->row_plan = cols != nullptr;
     p->rc_vars.clear();
     p->rc_items.clear();
@@ -165,6 +185,7 @@ size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
   ws->ptrs = pos;        pos = align_up(pos + (size_t)kPtrSlots * V * sizeof(void*), 256);
   ws->chunk_sums = pos;  pos = align_up(pos + C * 2 * sizeof(float), 256);
   ws->var_sums = pos;    pos = align_up(pos + V * 2 * sizeof(float), 256);
+  ws->full_chunks = pos; pos = align_up(pos + p->full_chunks.size() * sizeof(FullChunk), 256);
   if (p->row_plan) {
     ws->rc_vars = pos;     pos = align_up(pos + p->rc_vars.size() * sizeof(RowColVar), 256);
     ws->rc_items = pos;    pos = align_up(pos + p->rc_items.size() * sizeof(RowColItem), 256);
