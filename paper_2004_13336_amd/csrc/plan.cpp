@@ -13,6 +13,10 @@ namespace su {
 
 namespace {
 constexpr int kDefaultChunk = 2048;   // measured best on MI355X for the formatting kernels
+#ifndef SU_FLAT_WALK_PERCENT
+#define SU_FLAT_WALK_PERCENT 107     // measured cross-over on MI355X (BERT-shaped: between 32 and 64 replicas)
+#endif
+constexpr int kFlatWalkPercent = SU_FLAT_WALK_PERCENT;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 }  // namespace
@@ -108,9 +112,10 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
           p->full_chunks.push_back(fc);
         }
       }
-      // The replica-by-replica walk launches N * (chunks per shard) items; when more than a fifth of
-      // them are fragments (pieces much shorter than a chunk), the variable-by-variable walk wins.
-      p->flat_copies = (int64_t)N * (int64_t)p->chunks.size() * 4 > (int64_t)p->full_chunks.size() * 5;
+      // The replica-by-replica walk launches N * (chunks per shard) items, the variable-by-variable
+      // one a number that does not grow with N; where pieces are large the former is the faster (7 %
+      // at 8 replicas), so the latter is taken once fragments make the former's item count 7 % larger.
+      p->flat_copies = (int64_t)N * (int64_t)p->chunks.size() * 100 > (int64_t)p->full_chunks.size() * kFlatWalkPercent;
       if (!p->flat_copies) std::vector<FullChunk>().swap(p->full_chunks);     // not needed: keep the workspace small
     }
 
