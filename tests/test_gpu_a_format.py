@@ -306,3 +306,36 @@ def test_format_all_full_size_transformer():
     for o, f in zip(back, flats):
         assert same_bits(to_host(o), f)
     plan.free()
+
+
+def test_random_plans_whole_model_copies():
+    """Seeded random variable lists and replica counts, small pieces and large: shard_format_all against the
+    oracle's shards (every row, or a sample of rows where there are thousands) and unshard_format back."""
+    rnd = random.Random(2024)
+    sizes = [0, 1, 2, 7, 8, 9, 63, 64, 65, 500, 1023, 1024, 1025, 4096, 4100, 30000, 65536, 100003]
+    for case in range(24):
+        N = rnd.choice([1, 2, 3, 5, 8, 31, 64, 100, 257, 1000, 3001])
+        align = rnd.choice([8, 8, 8, 16, 64, 1, 4])
+        numel = [rnd.choice(sizes) for _ in range(rnd.randint(1, 7))]
+        dtype = rnd.choice(["f32", "bf16"])
+        print("random plan", case, N, align, numel, dtype, flush=True)
+        oplan = oracle.make_plan(numel, N, align)
+        plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+        flats = _bit_tensors(300 + case, numel, dtype)
+        dev_full = [to_dev(f) for f in flats]
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        if align % 8 == 0:
+            rows = su.gathered_empty(plan, tdt)
+        else:
+            rows = torch.empty((N, max(oplan.S, 1)), dtype=tdt, device=DEV)[:, :oplan.S]
+        rows.fill_(3.0)
+        su.shard_format_all(plan, dev_full, rows)
+        got = to_host(rows.contiguous())
+        check = range(N) if N <= 100 else sorted({0, 1, N // 3, N // 2, N - 2, N - 1} | {rnd.randrange(N) for _ in range(10)})
+        for r in check:
+            assert same_bits(got[r], oracle.shard_format(oplan, r, flats)), (case, r)
+        back = [torch.full((n,), 5.0, dtype=tdt, device=DEV) for n in numel]
+        su.unshard_format(plan, rows, back)
+        for i, (o, f) in enumerate(zip(back, flats)):
+            assert same_bits(to_host(o), f), (case, i)
+        plan.free()
