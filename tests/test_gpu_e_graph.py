@@ -74,3 +74,34 @@ def test_step_captured_in_a_graph_replays_like_eager():
             assert not same_bits(a[0], previous[0])          # the state does move from replay to replay
         previous = a
     plan.free()
+
+
+def test_two_plans_on_two_streams_do_not_disturb_each_other():
+    # the library keeps no state outside a plan: two plans driven from two streams, launches interleaved
+    # without synchronisation in between, give what each gives alone
+    cfg = [c for c in CONFIGS if c.name == "tiny"][0]
+    plans = [su.shard_plan_bind(su.shard_plan(cfg.numel, 4, 8)), su.shard_plan_bind(su.shard_plan(cfg.numel[::-1], 3, 8))]
+
+    class Cfg:                                   # the second plan sees the variables in reverse order
+        def __init__(self, numel):
+            self.numel = numel
+    cfgs = [Cfg(list(cfg.numel)), Cfg(list(cfg.numel[::-1]))]
+    alone = []
+    for plan, c, r in zip(plans, cfgs, (1, 2)):
+        st = State(plan, c, r, 93)
+        for _ in range(3):
+            st.step(plan)
+        torch.cuda.synchronize()
+        alone.append(st.snapshot())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    states = [State(plan, c, r, 93) for plan, c, r in zip(plans, cfgs, (1, 2))]
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for st, plan, s in zip(states, plans, streams):
+            with torch.cuda.stream(s):
+                st.step(plan)
+    torch.cuda.synchronize()
+    for st, want in zip(states, alone):
+        assert all(same_bits(a, b) for a, b in zip(st.snapshot(), want))
+    for plan in plans:
+        plan.free()
