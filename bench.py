@@ -279,6 +279,58 @@ def cpu_baseline(cfg, N, r):
             "seconds": round(dt, 2)}
 
 
+def _cpu_worker(job):
+    """One worker of the all-cores baseline: whole steps of the same oracle on a subset of the variables."""
+    name, N, r, indices, seconds = job
+    import numpy as np
+    import oracle
+    from workloads import CONFIGS, normal_f32
+    cfg = [c for c in CONFIGS if c.name == name][0]
+    hp = {k: float(np.float32(v)) for k, v in cfg.hyper.items()}
+    numel = [cfg.numel[i] for i in indices]
+    plan = oracle.make_plan(numel, N, 8)
+    gs = [normal_f32(cfg.seed, i, "g", cfg.numel[i], cfg.grad_std, 1) for i in indices]
+    gathered = np.zeros((N, plan.S), np.float32)
+    gathered[r] = oracle.shard_format(plan, r, [normal_f32(cfg.seed, i, "w", cfg.numel[i], cfg.weight_std) for i in indices])
+    m = np.zeros(plan.S, np.float32); v = np.zeros(plan.S, np.float32)
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        steps += 1
+        g = oracle.shard_format(plan, r, gs)
+        m, v, u, part = oracle.lamb_shard_partials(plan, r, gathered[r], g, m, v, hp, steps)
+        gathered[r] = oracle.lamb_shard_apply(plan, gathered[r], u, part * N, hp)
+        oracle.unshard_format(plan, gathered)
+        dt = time.perf_counter() - t0
+        if dt >= seconds or steps >= 64:
+            break
+    return steps / dt
+
+
+def cpu_baseline_all_cores(cfg, N, r, workers):
+    """The same oracle with the variables dealt out to `workers` processes (every variable is independent
+    of the others in this path); a whole step is done when the slowest worker is, so the rate is the
+    shard's parameters times the lowest steps/s.  Must run before this process touches the GPU."""
+    import multiprocessing as mp
+    import oracle
+    order = sorted(range(len(cfg.numel)), key=lambda i: -cfg.numel[i])
+    groups, load = [[] for _ in range(workers)], [0] * workers
+    for i in order:                                   # largest first onto the least loaded worker
+        k = load.index(min(load))
+        groups[k].append(i)
+        load[k] += cfg.numel[i]
+    groups = [sorted(g) for g in groups if g]
+    plan = oracle.make_plan(cfg.numel, N, 8)
+    real = sum(plan.real_count(i, r) for i in range(plan.V))
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(len(groups)) as pool:
+        rates = pool.map(_cpu_worker, [(cfg.name, N, r, g, 10.0) for g in groups])
+    dt = time.perf_counter() - t0
+    return {"value": real * min(rates), "unit": "params/s", "cores": len(groups), "kind": "oracle",
+            "sample": "the same whole steps with the %d variables dealt out to %d processes (numpy itself is "
+                      "single-threaded), about 10 s each; rate = shard parameters x the slowest process's steps/s"
+                      % (plan.V, len(groups)), "seconds": round(dt, 2)}
+
+
 def table(args, torch, su, cfgs, path):
     """Every config x stage, kernel time from the library's event pairs; written as JSON."""
     rows = []
@@ -439,6 +491,16 @@ def main():
               "(the cross-replica collectives are outside this library)" % args.gpus, file=sys.stderr)
         raise SystemExit(2)
     import torch
+    if torch.cuda.device_count() < 1:           # counting devices does not initialise the GPU
+        print("bench.py needs a GPU", file=sys.stderr)
+        raise SystemExit(2)
+    cpu = None
+    if not args.no_cpu_baseline and not args.stage:
+        # the oracle legs first: the all-cores one forks workers, which must happen before the GPU is touched
+        from workloads import CONFIGS as _CFGS
+        cfg0 = [c for c in _CFGS if c.name == args.config][0]
+        cpu = (cpu_baseline(cfg0, args.replicas, args.replica_id),
+               cpu_baseline_all_cores(cfg0, args.replicas, args.replica_id, min(16, os.cpu_count() or 1)))
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         raise SystemExit(2)
@@ -459,12 +521,8 @@ def main():
     out = headline(args, torch, su, CONFIGS)
     if args.table:
         table(args, torch, su, CONFIGS, args.table)
-    if not args.no_cpu_baseline:
-        torch.cuda.empty_cache()
-        cfg = [c for c in CONFIGS if c.name == args.config][0]
-        out["cpu_baseline"] = cpu_baseline(cfg, args.replicas, args.replica_id)
-    else:
-        out["cpu_baseline"] = None
+    out["cpu_baseline"] = cpu[0] if cpu else None
+    out["cpu_baseline_all_cores"] = cpu[1] if cpu else None
     print(json.dumps(out))
 
 
