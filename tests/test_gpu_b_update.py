@@ -475,6 +475,94 @@ def test_lars_fused_call_and_partials():
     plan.free()
 
 
+# ----------------------------------------------------------------------------- random plans
+
+def _random_plan_case(seed):
+    """A seeded random variable list (empty, tiny, chunk-sized and multi-chunk variables), replica count,
+    alignment, chunk size and flags."""
+    rng = np.random.default_rng(7000 + seed)
+    nv = int(rng.integers(1, 13))
+    kinds = rng.integers(0, 5, nv)
+    numel = []
+    for k in kinds:
+        if k == 0:
+            numel.append(int(rng.integers(0, 3)))
+        elif k == 1:
+            numel.append(int(rng.integers(1, 40)))
+        elif k == 2:
+            numel.append(int(rng.integers(1000, 5000)))
+        elif k == 3:
+            numel.append(int(rng.choice([1024, 2048, 4096, 8192])) + int(rng.integers(-1, 2)))
+        else:
+            numel.append(int(rng.integers(9000, 40000)))
+    N = int(rng.choice([1, 2, 3, 5, 8, 17]))
+    align = int(rng.choice([1, 2, 4, 8, 16, 64]))
+    chunk = int(rng.choice([0, 1024, 2048, 4096, 16384]))
+    flags = [int(x) for x in rng.integers(0, 4, nv)]
+    return numel, N, align, chunk, flags
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_plans_every_update_against_the_unsharded_oracle(seed):
+    """Two steps of each optimizer on all replicas of a random plan, put back together and compared
+    with the unsharded oracle; padding stays +0.0 throughout."""
+    numel, N, align, chunk, flags = _random_plan_case(seed)
+    print("random plan", seed, numel, "N", N, "align", align, "chunk", chunk, "flags", flags, flush=True)
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align, flags, chunk))
+    ws, _ = gen_weights_grads(500 + seed, numel, 0.02, 1e-3)
+    W0 = shards_of(oplan, ws)
+
+    def grads(t):
+        gs = [normal_f32(500 + seed, i, "g", n, 1e-3, t) for i, n in enumerate(numel)]
+        return gs, dev_rows(shards_of(oplan, gs))
+
+    def check(uw, W, what, t):
+        Wh = host_rows(W)
+        for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, Wh))):
+            assert_weights_close(b, a, "%s w var %d t=%d" % (what, i, t))
+        for r in range(N):
+            assert pads_are_zero(oplan, r, Wh[r]), what
+
+    # Adam and momentum: flat kernels, no table
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]; uv = [np.zeros_like(w) for w in ws]
+    W = dev_rows(W0); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    for t in (1, 2):
+        gs, G = grads(t)
+        for i in range(len(numel)):
+            uw[i], um[i], uv[i] = oracle.adam_step(uw[i], gs[i], um[i], uv[i], ADAM, t)
+        for r in range(N):
+            su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], ADAM, t)
+        check(uw, W, "adam", t)
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]
+    W = dev_rows(W0); M = zeros_like_rows(W)
+    for t in (1, 2):
+        gs, G = grads(t)
+        for i in range(len(numel)):
+            uw[i], um[i] = oracle.momentum_step(uw[i], gs[i], um[i], MOM)
+        for r in range(N):
+            su.shard_update_momentum(plan, r, W[r], G[r], M[r], MOM)
+        check(uw, W, "momentum", t)
+    # LAMB and LARS: chunk table, masked partial sums, per-variable flags
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]; uv = [np.zeros_like(w) for w in ws]
+    W = dev_rows(W0); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    for t in (1, 2):
+        gs, G = grads(t)
+        uw, um, uv, usums = oracle.lamb_unsharded_step(uw, gs, um, uv, LAMB, t, flags)
+        _, total = _lamb_all_replicas(plan, oplan, W, G, M, V, LAMB, t)
+        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        check(uw, W, "lamb", t)
+    uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]
+    W = dev_rows(W0); M = zeros_like_rows(W)
+    for t in (1, 2):
+        gs, G = grads(t)
+        uw, um, usums = oracle.lars_unsharded_step(uw, gs, um, LARS, flags)
+        _, total = _lars_all_replicas(plan, oplan, W, G, M, LARS)
+        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        check(uw, W, "lars", t)
+    plan.free()
+
+
 # ------------------------------------------------------------------------- beyond 2^31 elements
 
 def test_shard_longer_than_2_31_slots():
