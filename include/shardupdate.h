@@ -246,6 +246,51 @@ int shard_update_lars(shard_plan_t* plan, int r, float* w, const float* g, float
                       void* w_bf16_out, const shard_lars_hp* hp, const float* other_replicas_sumsq,
                       float* local_sumsq_out, shard_stream_t stream);
 
+/* The updates with the formatting of the gradient fused into them (Section 5.1: the formatting steps
+ * are fused into the operators around them, so that no replica reads and writes the full data just
+ * to pad and slice it).  full_g: host array [V] of device pointers to the FULL gradient tensors, the
+ * argument shard_format takes (g_dtype SHARD_F32 or SHARD_BF16; any alignment: 16-byte aligned
+ * float32 and 8-byte aligned bfloat16 pieces are read with vector loads, the others element by
+ * element).  Every kernel that needs the gradient reads replica r's piece of each tensor in place,
+ * with +0.0 for the padded slots, so the result is bit for bit that of
+ *     shard_format(full_g -> g, float32) followed by the function of the same name without
+ *     _full_grads on g,
+ * without the 8 bytes per slot of writing g and reading it back.  The pointer list is cached like
+ * shard_format's.  All of them need a bound plan (Adam and momentum too: reading in place needs the
+ * chunk table).  Other arguments, state and errors as in the plain functions; the second phase of
+ * LAMB does not read the gradient and is shard_update_lamb_apply.
+ */
+int shard_update_adam_full_grads(shard_plan_t* plan, int r, float* w, const void* const* full_g,
+                                 int g_dtype, float* m, float* v, void* w_bf16_out,
+                                 const shard_adam_hp* hp, int64_t step, shard_stream_t stream);
+
+int shard_update_momentum_full_grads(shard_plan_t* plan, int r, float* w, const void* const* full_g,
+                                     int g_dtype, float* m, void* w_bf16_out,
+                                     const shard_momentum_hp* hp, shard_stream_t stream);
+
+int shard_update_lamb_partials_full_grads(shard_plan_t* plan, int r, const float* w,
+                                          const void* const* full_g, int g_dtype, float* m, float* v,
+                                          const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out,
+                                          shard_stream_t stream);
+
+int shard_update_lamb_full_grads(shard_plan_t* plan, int r, float* w, const void* const* full_g,
+                                 int g_dtype, float* m, float* v, void* w_bf16_out,
+                                 const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq,
+                                 float* local_sumsq_out, shard_stream_t stream);
+
+int shard_update_lars_partials_full_grads(shard_plan_t* plan, int r, const float* w,
+                                          const void* const* full_g, int g_dtype, float* local_sumsq_out,
+                                          shard_stream_t stream);
+
+int shard_update_lars_apply_full_grads(shard_plan_t* plan, int r, float* w, const void* const* full_g,
+                                       int g_dtype, float* m, void* w_bf16_out, const shard_lars_hp* hp,
+                                       const float* global_sumsq, shard_stream_t stream);
+
+int shard_update_lars_full_grads(shard_plan_t* plan, int r, float* w, const void* const* full_g,
+                                 int g_dtype, float* m, void* w_bf16_out, const shard_lars_hp* hp,
+                                 const float* other_replicas_sumsq, float* local_sumsq_out,
+                                 shard_stream_t stream);
+
 /* Reductions that keep a dimension, on a row plan (Section 4.1, "Non-elementwise operators": the
  * format may not merge a collapsed dimension with a passed-through one; with rows sharded, a reduce
  * over columns is complete on the owning replica and a reduce over rows gives per-replica partial

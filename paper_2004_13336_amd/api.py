@@ -255,6 +255,32 @@ def shard_update_lamb(plan: Plan, r: int, w, g, m, v, hp, step: int, other_repli
                                    _stream(stream)), "shard_update_lamb")
 
 
+def shard_update_lamb_partials_full_grads(plan: Plan, r: int, w, full_grads, m, v, hp, step: int, local_sumsq_out,
+                                          stream=None):
+    """Phase 1 with the gradient read in place from the full tensors (list or FullTensors)."""
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_lamb_partials_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                                       _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                                       C.byref(_hp(LambHP, hp)), int(step),
+                                                       _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                                       _stream(stream)), "shard_update_lamb_partials_full_grads")
+
+
+def shard_update_lamb_full_grads(plan: Plan, r: int, w, full_grads, m, v, hp, step: int, other_replicas_sumsq=None,
+                                 local_sumsq_out=None, w_bf16_out=None, stream=None):
+    """shard_update_lamb with the gradient read in place from the full tensors (list or FullTensors)."""
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_lamb_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                              _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                              _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                              C.byref(_hp(LambHP, hp)), int(step),
+                                              _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
+                                              _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                              _stream(stream)), "shard_update_lamb_full_grads")
+
+
 def shard_update_lars_partials(plan: Plan, r: int, w, g, local_sumsq_out, stream=None):
     f = torch.float32
     _check(lib().shard_update_lars_partials(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
@@ -282,6 +308,61 @@ def shard_update_lars(plan: Plan, r: int, w, g, m, hp, other_replicas_sumsq=None
                                    _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
                                    _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
                                    _stream(stream)), "shard_update_lars")
+
+
+# ---- the same updates with the gradient read in place from the full tensors (list or FullTensors) ----
+
+def shard_update_adam_full_grads(plan: Plan, r: int, w, full_grads, m, v, hp, step: int, w_bf16_out=None, stream=None):
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_adam_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                              _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                              _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                              C.byref(_hp(AdamHP, hp)), int(step), _stream(stream)),
+           "shard_update_adam_full_grads")
+
+
+def shard_update_momentum_full_grads(plan: Plan, r: int, w, full_grads, m, hp, w_bf16_out=None, stream=None):
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_momentum_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                                  _dev(m, plan.S, f, "m"),
+                                                  _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                                  C.byref(_hp(MomentumHP, hp)), _stream(stream)),
+           "shard_update_momentum_full_grads")
+
+
+def shard_update_lars_partials_full_grads(plan: Plan, r: int, w, full_grads, local_sumsq_out, stream=None):
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_lars_partials_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                                       _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                                       _stream(stream)), "shard_update_lars_partials_full_grads")
+
+
+def shard_update_lars_apply_full_grads(plan: Plan, r: int, w, full_grads, m, hp, global_sumsq, w_bf16_out=None,
+                                       stream=None):
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_lars_apply_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                                    _dev(m, plan.S, f, "m"),
+                                                    _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                                    C.byref(_hp(LarsHP, hp)),
+                                                    _dev(global_sumsq, 2 * plan.V, f, "global_sumsq"),
+                                                    _stream(stream)), "shard_update_lars_apply_full_grads")
+
+
+def shard_update_lars_full_grads(plan: Plan, r: int, w, full_grads, m, hp, other_replicas_sumsq=None,
+                                 local_sumsq_out=None, w_bf16_out=None, stream=None):
+    f = torch.float32
+    arr, src = _full_ptrs(plan, full_grads, "full_grads")
+    _check(lib().shard_update_lars_full_grads(plan.handle, int(r), _dev(w, plan.S, f, "w"), arr, _DTYPES[src],
+                                              _dev(m, plan.S, f, "m"),
+                                              _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                              C.byref(_hp(LarsHP, hp)),
+                                              _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
+                                              _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                              _stream(stream)), "shard_update_lars_full_grads")
 
 
 def shard_plan_rowcol_layout(plan: Plan):

@@ -347,21 +347,197 @@ int shard_update_momentum(shard_plan_t* p, int r, float* w, const float* g, floa
   return hip_status(launch_momentum(p, w, g, m, w_bf16_out, k, as_stream(stream)));
 }
 
-int shard_update_lamb_partials(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v,
-                               const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
+namespace {
+
+// The gradient argument of an update: a packed shard, or the list of full tensors the shard would have
+// been formatted from (the *_full_grads entry points).
+struct GradArg {
+  const float* shard;
+  const void* const* full;
+  int dtype;
+  bool from_full;
+};
+inline GradArg shard_grad(const float* g) { return GradArg{g, nullptr, SHARD_F32, false}; }
+inline GradArg full_grads(const void* const* ptrs, int dtype) { return GradArg{nullptr, ptrs, dtype, true}; }
+
+int check_grad(const shard_plan_t* p, const GradArg& g) {
+  if (!g.from_full) return p->S > 0 ? check_shard_ptr(g.shard) : SHARD_OK;
+  if (!dtype_ok(g.dtype)) return SHARD_EINVAL;
+  return check_full_ptrs(p, g.full);
+}
+
+// g_source of the launchers (0 shard, 1 full float32, 2 full bfloat16) and, for full tensors, the device
+// table of their pointers.
+int resolve_grad(shard_plan_t* p, const GradArg& g, hipStream_t s, int* source, const void*** table) {
+  *source = 0;
+  *table = nullptr;
+  if (!g.from_full) return SHARD_OK;
+  *source = g.dtype == SHARD_F32 ? 1 : 2;
+  return resident_ptr_table(p, g.full, s, table);
+}
+
+int lamb_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* m, float* v,
+                      const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
   int rc = check_plan_r(p, r, true);
   if (rc != SHARD_OK) return rc;
   if (hp == nullptr) return SHARD_EINVAL;
   AdamK k;
   if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
   if (p->V == 0) return SHARD_OK;
   if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
                    (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
     return rc;
-  hipError_t e = launch_lamb_p1(p, r, w, g, m, v, k, as_stream(stream));
-  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, as_stream(stream));
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
   return hip_status(e);
+}
+
+int lamb_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, float* v, void* w_bf16_out,
+             const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq, float* local_sumsq_out,
+             shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
+int lars_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* local_sumsq_out,
+                      shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK)) return rc;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
+  return hip_status(e);
+}
+
+int lars_apply_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out,
+                   const shard_lars_hp* hp, const float* global_sumsq, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
+      (rc = check_grad(p, g)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  return hip_status(launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, global_sumsq, s));
+}
+
+int lars_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out, const shard_lars_hp* hp,
+             const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
+}  // namespace
+
+int shard_update_adam_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype, float* m,
+                                 float* v, void* w_bf16_out, const shard_adam_hp* hp, int64_t step,
+                                 shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  const GradArg g = full_grads(full_g, g_dtype);
+  if ((rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK ||
+      (rc = check_shard_ptr(v)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  return hip_status(launch_adam_full_grads(p, r, w, source, table, m, v, w_bf16_out, k, s));
+}
+
+int shard_update_momentum_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype,
+                                     float* m, void* w_bf16_out, const shard_momentum_hp* hp, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr || !std::isfinite(hp->lr) || !std::isfinite(hp->mu) || !std::isfinite(hp->weight_decay))
+    return SHARD_EINVAL;
+  const GradArg g = full_grads(full_g, g_dtype);
+  if ((rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK) return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  MomentumK k{hp->mu, hp->lr, hp->weight_decay};
+  return hip_status(launch_momentum_full_grads(p, r, w, source, table, m, w_bf16_out, k, s));
+}
+
+int shard_update_lamb_partials(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v,
+                               const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
+  return lamb_partials_any(p, r, w, shard_grad(g), m, v, hp, step, local_sumsq_out, stream);
+}
+
+int shard_update_lamb_partials_full_grads(shard_plan_t* p, int r, const float* w, const void* const* full_g,
+                                          int g_dtype, float* m, float* v, const shard_lamb_hp* hp, int64_t step,
+                                          float* local_sumsq_out, shard_stream_t stream) {
+  return lamb_partials_any(p, r, w, full_grads(full_g, g_dtype), m, v, hp, step, local_sumsq_out, stream);
 }
 
 int shard_update_lamb_apply(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w_bf16_out,
@@ -382,72 +558,48 @@ int shard_update_lamb_apply(shard_plan_t* p, int r, float* w, const float* m, co
 int shard_update_lamb(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,
                       const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq,
                       float* local_sumsq_out, shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  if (hp == nullptr) return SHARD_EINVAL;
-  AdamK k;
-  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
-    return SHARD_EALIGN;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
-                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  hipStream_t s = as_stream(stream);
-  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
-  hipError_t e = launch_lamb_p1(p, r, w, g, m, v, k, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
-  if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
-  return hip_status(e);
+  return lamb_any(p, r, w, shard_grad(g), m, v, w_bf16_out, hp, step, other_replicas_sumsq, local_sumsq_out, stream);
+}
+
+int shard_update_lamb_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype, float* m,
+                                 float* v, void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
+                                 const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream) {
+  return lamb_any(p, r, w, full_grads(full_g, g_dtype), m, v, w_bf16_out, hp, step, other_replicas_sumsq,
+                  local_sumsq_out, stream);
 }
 
 int shard_update_lars_partials(shard_plan_t* p, int r, const float* w, const float* g, float* local_sumsq_out,
                                shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK)) return rc;
-  hipError_t e = launch_lars_p1(p, r, w, g, as_stream(stream));
-  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, as_stream(stream));
-  return hip_status(e);
+  return lars_partials_any(p, r, w, shard_grad(g), local_sumsq_out, stream);
+}
+
+int shard_update_lars_partials_full_grads(shard_plan_t* p, int r, const float* w, const void* const* full_g,
+                                          int g_dtype, float* local_sumsq_out, shard_stream_t stream) {
+  return lars_partials_any(p, r, w, full_grads(full_g, g_dtype), local_sumsq_out, stream);
 }
 
 int shard_update_lars_apply(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w_bf16_out,
                             const shard_lars_hp* hp, const float* global_sumsq, shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  LarsK k;
-  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
-  if (p->S == 0) return SHARD_OK;
-  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
-      (rc = check_shard_ptr(g)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK)
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  return hip_status(launch_lars_p2(p, r, w, g, m, w_bf16_out, k, global_sumsq, as_stream(stream)));
+  return lars_apply_any(p, r, w, shard_grad(g), m, w_bf16_out, hp, global_sumsq, stream);
+}
+
+int shard_update_lars_apply_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype,
+                                       float* m, void* w_bf16_out, const shard_lars_hp* hp, const float* global_sumsq,
+                                       shard_stream_t stream) {
+  return lars_apply_any(p, r, w, full_grads(full_g, g_dtype), m, w_bf16_out, hp, global_sumsq, stream);
 }
 
 int shard_update_lars(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w_bf16_out,
                       const shard_lars_hp* hp, const float* other_replicas_sumsq, float* local_sumsq_out,
                       shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  LarsK k;
-  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
-    return SHARD_EALIGN;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
-                   (rc = check_shard_ptr(m)) != SHARD_OK))
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  hipStream_t s = as_stream(stream);
-  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
-  hipError_t e = launch_lars_p1(p, r, w, g, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
-  if (e == hipSuccess) e = launch_lars_p2(p, r, w, g, m, w_bf16_out, k, sums, s);
-  return hip_status(e);
+  return lars_any(p, r, w, shard_grad(g), m, w_bf16_out, hp, other_replicas_sumsq, local_sumsq_out, stream);
+}
+
+int shard_update_lars_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype, float* m,
+                                 void* w_bf16_out, const shard_lars_hp* hp, const float* other_replicas_sumsq,
+                                 float* local_sumsq_out, shard_stream_t stream) {
+  return lars_any(p, r, w, full_grads(full_g, g_dtype), m, w_bf16_out, hp, other_replicas_sumsq, local_sumsq_out,
+                  stream);
 }
 
 int shard_plan_rowcol_layout(const shard_plan_t* p, int64_t* row_off, int64_t* col_off, int64_t* total_rows,

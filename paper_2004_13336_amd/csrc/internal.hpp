@@ -201,8 +201,10 @@ hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, floa
 hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, void* w16, const MomentumK& k,
                            hipStream_t stream);
 
-hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v, const AdamK& k,
-                          hipStream_t stream);
+// g_source 0: g is the packed shard gradient; 1 / 2: g_full is the device table of full float32 /
+// bfloat16 gradient tensors and g is unused.
+hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
+                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream);
 // Sums each variable's chunk partials in a fixed order, adds `other` (nullable), writes the totals to
 // `sums_out` (nullable) and `local_out` (nullable, without `other`).
 hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_out, float* local_out,
@@ -212,9 +214,16 @@ hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, cons
 
 hipError_t launch_format_all(shard_plan_t* p, const void* const* dev_ptr_table, int src_dtype, void* out,
                              int64_t row_stride, int dst_dtype, bool vec, hipStream_t stream);
-hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, hipStream_t stream);
-hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w16, const LarsK& k,
-                          const float* sums, hipStream_t stream);
+hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
+                          const void* const* g_full, hipStream_t stream);
+hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, int g_source, const void* const* g_full,
+                          float* m, void* w16, const LarsK& k, const float* sums, hipStream_t stream);
+// Chunk-table versions of the Adam and momentum updates that read the gradient from full tensors
+// (g_source 1: float32, 2: bfloat16).
+hipError_t launch_adam_full_grads(shard_plan_t* p, int r, float* w, int g_source, const void* const* g_full, float* m,
+                                  float* v, void* w16, const AdamK& k, hipStream_t stream);
+hipError_t launch_momentum_full_grads(shard_plan_t* p, int r, float* w, int g_source, const void* const* g_full,
+                                      float* m, void* w16, const MomentumK& k, hipStream_t stream);
 
 // Row/column sums of squares on a row plan: phase 1 writes per-item partials, phase 2 adds them in
 // a fixed order into row_out [sum Lr] and col_out [sum cols].

@@ -144,6 +144,77 @@ __device__ __forceinline__ void block_sum2(float& a, float& b) {
   }
 }
 
+// ---- where the gradient comes from -----------------------------------------------------------------
+// GS 0: the packed shard gradient.  GS 1 / 2: straight from the full float32 / bfloat16 tensors (the
+// *_full_grads entry points): the formatting of the gradient is fused into its consumer (Section 5.1)
+// and no shard gradient is ever written.  Slots at or beyond the chunk's `valid` then read as +0.0,
+// exactly what shard_format would have stored, so both routes give the same bits.
+template <int GS>
+struct GradChunk {
+  static constexpr int SIZE = GS == 2 ? 2 : 4;     // bytes per gradient element
+  const char* base;                                // the element that belongs to the chunk's first slot
+  bool aligned;                                    // four elements from `base` can be one vector load
+  __device__ __forceinline__ const void* tile(int first_slot) const { return base + (int64_t)first_slot * SIZE; }
+  // every slot of a tile that exists (`lim`) is real and the source can be read with vector loads
+  __device__ __forceinline__ bool fast(int lim, int valid) const { return GS == 0 || (aligned && valid >= lim); }
+};
+
+template <int GS>
+__device__ __forceinline__ GradChunk<GS> grad_chunk(const float* g_shard, const void* const* __restrict__ g_full,
+                                                    const ChunkView& cv) {
+  GradChunk<GS> gc;
+  if constexpr (GS == 0) {
+    gc.base = (const char*)(g_shard + cv.shard0);
+    gc.aligned = true;
+  } else {
+    // only dereferenced for slots below cv.valid, i.e. inside the tensor
+    gc.base = (const char*)g_full[cv.var] + cv.flat0 * GradChunk<GS>::SIZE;
+    gc.aligned = (reinterpret_cast<uintptr_t>(gc.base) & (4 * GradChunk<GS>::SIZE - 1)) == 0;
+  }
+  return gc;
+}
+
+__device__ __forceinline__ float bf16_up(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// One gradient element of a chunk (the element-by-element paths).
+template <int GS>
+__device__ __forceinline__ float load_g1(const GradChunk<GS>& gc, int e, int valid) {
+  if constexpr (GS == 0) return ((const float*)gc.base)[e];
+  else if constexpr (GS == 1) return (e < valid) ? ((const float*)gc.base)[e] : 0.0f;
+  else return (e < valid) ? bf16_up(((const uint16_t*)gc.base)[e]) : 0.0f;
+}
+
+// Four gradient values at offset o of a tile that starts at g.  NT0: cache policy of the shard gradient;
+// full tensors are read once and always non-temporally.  GFAST: see GradChunk::fast.
+template <int GS, bool GFAST, bool NT0>
+__device__ __forceinline__ F4 load_g4(const void* g, int o, int valid) {
+  if constexpr (GS == 0) {
+    return ld4<NT0>((const float*)g + o);
+  } else if constexpr (GS == 1) {
+    const float* p = (const float*)g + o;
+    if constexpr (GFAST) return ld4<true>(p);
+    F4 x;
+    x.x = (o + 0 < valid) ? ld<true>(p + 0) : 0.0f;
+    x.y = (o + 1 < valid) ? ld<true>(p + 1) : 0.0f;
+    x.z = (o + 2 < valid) ? ld<true>(p + 2) : 0.0f;
+    x.w = (o + 3 < valid) ? ld<true>(p + 3) : 0.0f;
+    return x;
+  } else {
+    const uint16_t* p = (const uint16_t*)g + o;
+    if constexpr (GFAST) {
+      const u2 t = ld<true>((const u2*)p);
+      return F4{__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u), __uint_as_float(t.y << 16),
+                __uint_as_float(t.y & 0xFFFF0000u)};
+    }
+    F4 x;
+    x.x = (o + 0 < valid) ? bf16_up(ld<true>(p + 0)) : 0.0f;
+    x.y = (o + 1 < valid) ? bf16_up(ld<true>(p + 1)) : 0.0f;
+    x.z = (o + 2 < valid) ? bf16_up(ld<true>(p + 2)) : 0.0f;
+    x.w = (o + 3 < valid) ? bf16_up(ld<true>(p + 3)) : 0.0f;
+    return x;
+  }
+}
+
 // ---- pointer table --------------------------------------------------------------------------------
 // Device pointer tables are written by a kernel that carries the pointers as launch arguments:
 // stream-ordered, no host staging buffer whose lifetime would have to be tracked.
@@ -610,8 +681,8 @@ __global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float*
 // One tile of phase 1: `lim` = slots of the tile that exist, `valid` = leading slots that hold real
 // elements (may be negative or exceed the tile).  FULL tiles run without branches; the mask on the
 // sums is a select.
-template <bool FULL>
-__device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const float* __restrict__ g, float* m,
+template <bool FULL, int GS, bool GFAST>
+__device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const void* __restrict__ g, float* m,
                                              float* v, int lim, int valid, float wd, const AdamK& k, float& sw,
                                              float& su) {
   const int t4 = threadIdx.x * 4;
@@ -620,7 +691,7 @@ __device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const 
   for (int i = 0; i < kUnroll; ++i) {
     const int o = i * kBlock * 4 + t4;
     if (FULL || o < lim) {
-      rg[i] = ld4<PolLamb::RO>(g + o);
+      rg[i] = load_g4<GS, GFAST, PolLamb::RO>(g, o, valid);
       rw[i] = ld4<PolLamb::RO>(w + o);
       rm[i] = ld4<PolLamb::RW>(m + o);
       rv[i] = ld4<PolLamb::RW>(v + o);
@@ -649,30 +720,39 @@ __device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const 
   }
 }
 
-template <bool VEC>
+template <bool VEC, int GS>
 __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const float* __restrict__ w, const float* __restrict__ g,
-                                                         float* m, float* v, float* __restrict__ chunk_sums, int r,
-                                                         AdamK k) {
+                                                         const void* const* __restrict__ g_full, float* m, float* v,
+                                                         float* __restrict__ chunk_sums, int r, AdamK k) {
   const int c = SU_P1_REVERSE ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
   const ChunkView cv = chunk_view(vars, chunks, c, r);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
+  const GradChunk<GS> gc = grad_chunk<GS>(g, g_full, cv);
   float sw = 0.0f, su = 0.0f;
   if constexpr (VEC) {
     for (int base = 0; base < cv.len; base += kTileElems) {
       const int64_t s0 = cv.shard0 + base;
-      if (base + kTileElems <= cv.len)
-        lamb_p1_tile<true>(w + s0, g + s0, m + s0, v + s0, kTileElems, cv.valid - base, wd, k, sw, su);
-      else
-        lamb_p1_tile<false>(w + s0, g + s0, m + s0, v + s0, cv.len - base, cv.valid - base, wd, k, sw, su);
+      const int lim = cv.len - base, valid = cv.valid - base;
+      if (lim >= kTileElems) {
+        if (gc.fast(kTileElems, valid))
+          lamb_p1_tile<true, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
+        else
+          lamb_p1_tile<true, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
+      } else {
+        if (gc.fast(lim, valid))
+          lamb_p1_tile<false, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
+        else
+          lamb_p1_tile<false, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
+      }
     }
   } else {
     for (int e = threadIdx.x; e < cv.len; e += kBlock) {
       const int64_t s = cv.shard0 + e;
       float mm = m[s], vv = v[s];
       const float ww = w[s];
-      lamb_moments(g[s], mm, vv, k);
+      lamb_moments(load_g1<GS>(gc, e, cv.valid), mm, vv, k);
       float d = lamb_dir(ww, mm, vv, wd, k);
       d = (e < cv.valid) ? d : 0.0f;
       const float wm = (e < cv.valid) ? ww : 0.0f;
@@ -809,8 +889,8 @@ __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restri
 // Phase 1 only reads: masked sums of w^2 and g^2 per chunk.  Phase 2 is the momentum update with a
 // per-variable learning-rate scale.
 
-template <bool FULL>
-__device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const float* __restrict__ g, int lim,
+template <bool FULL, int GS, bool GFAST>
+__device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const void* __restrict__ g, int lim,
                                              int valid, float& sw, float& sg) {
   const int t4 = threadIdx.x * 4;
   F4 rw[kUnroll], rg[kUnroll];
@@ -818,7 +898,7 @@ __device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const 
   for (int i = 0; i < kUnroll; ++i) {
     const int o = i * kBlock * 4 + t4;
     if (FULL || o < lim) {
-      rg[i] = ld4<PolLars::RO>(g + o);
+      rg[i] = load_g4<GS, GFAST, PolLars::RO>(g, o, valid);
       rw[i] = ld4<PolLars::RO>(w + o);
     }
   }
@@ -841,24 +921,32 @@ __device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const 
   }
 }
 
-template <bool VEC>
+template <bool VEC, int GS>
 __global__ __launch_bounds__(kBlock) void lars_p1_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const float* __restrict__ w, const float* __restrict__ g,
+                                                         const void* const* __restrict__ g_full,
                                                          float* __restrict__ chunk_sums, int r) {
   const int c = blockIdx.x;
   const ChunkView cv = chunk_view(vars, chunks, c, r);
+  const GradChunk<GS> gc = grad_chunk<GS>(g, g_full, cv);
   float sw = 0.0f, sg = 0.0f;
   if constexpr (VEC) {
     for (int base = 0; base < cv.len; base += kTileElems) {
       const int64_t s0 = cv.shard0 + base;
-      if (base + kTileElems <= cv.len) lars_p1_tile<true>(w + s0, g + s0, kTileElems, cv.valid - base, sw, sg);
-      else lars_p1_tile<false>(w + s0, g + s0, cv.len - base, cv.valid - base, sw, sg);
+      const int lim = cv.len - base, valid = cv.valid - base;
+      if (lim >= kTileElems) {
+        if (gc.fast(kTileElems, valid)) lars_p1_tile<true, GS, true>(w + s0, gc.tile(base), kTileElems, valid, sw, sg);
+        else lars_p1_tile<true, GS, false>(w + s0, gc.tile(base), kTileElems, valid, sw, sg);
+      } else {
+        if (gc.fast(lim, valid)) lars_p1_tile<false, GS, true>(w + s0, gc.tile(base), lim, valid, sw, sg);
+        else lars_p1_tile<false, GS, false>(w + s0, gc.tile(base), lim, valid, sw, sg);
+      }
     }
   } else {
     for (int e = threadIdx.x; e < cv.len; e += kBlock) {
       const float a = (e < cv.valid) ? w[cv.shard0 + e] : 0.0f;
-      const float b = (e < cv.valid) ? g[cv.shard0 + e] : 0.0f;
+      const float b = (e < cv.valid) ? load_g1<GS>(gc, e, cv.valid) : 0.0f;
       sw = fmaf(a, a, sw);
       sg = fmaf(b, b, sg);
     }
@@ -876,16 +964,17 @@ __device__ __forceinline__ void lars_elem(float& w, float g, float& m, float wd,
   w = w - m;
 }
 
-template <bool FULL, bool BF16>
-__device__ __forceinline__ void lars_p2_tile(float* w, const float* __restrict__ g, float* m,
-                                             uint16_t* __restrict__ w16, int lim, float wd, float scale, float mu) {
+template <bool FULL, bool BF16, int GS, bool GFAST>
+__device__ __forceinline__ void lars_p2_tile(float* w, const void* __restrict__ g, float* m,
+                                             uint16_t* __restrict__ w16, int lim, int valid, float wd, float scale,
+                                             float mu) {
   const int t4 = threadIdx.x * 4;
   F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
     const int o = i * kBlock * 4 + t4;
     if (FULL || o < lim) {
-      rg[i] = ld4<PolLars::RO>(g + o);
+      rg[i] = load_g4<GS, GFAST, PolLars::RO>(g, o, valid);
       rw[i] = ld4<PolLars::RW>(w + o);
       rm[i] = ld4<PolLars::RW>(m + o);
     }
@@ -905,14 +994,16 @@ __device__ __forceinline__ void lars_p2_tile(float* w, const float* __restrict__
   }
 }
 
-template <bool VEC, bool BF16>
+template <bool VEC, bool BF16, int GS>
 __global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks, float* w,
-                                                         const float* __restrict__ g, float* m,
+                                                         const float* __restrict__ g,
+                                                         const void* const* __restrict__ g_full, float* m,
                                                          uint16_t* __restrict__ w16, const float* __restrict__ sums,
-                                                         LarsK k) {
+                                                         int r, LarsK k) {
   const int c = (int)(gridDim.x - 1 - blockIdx.x);          // opposite direction to phase 1
-  const ChunkView cv = chunk_view(vars, chunks, c, 0);
+  const ChunkView cv = chunk_view(vars, chunks, c, r);
+  const GradChunk<GS> gc = grad_chunk<GS>(g, g_full, cv);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
   float local_lr = 1.0f;
   if (!(cv.flags & SHARD_VAR_NO_ADAPT)) {
@@ -923,16 +1014,160 @@ __global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restri
   if constexpr (VEC) {
     for (int base = 0; base < cv.len; base += kTileElems) {
       const int64_t s0 = cv.shard0 + base;
-      if (base + kTileElems <= cv.len) lars_p2_tile<true, BF16>(w + s0, g + s0, m + s0, w16 + s0, kTileElems, wd, scale, k.mu);
-      else lars_p2_tile<false, BF16>(w + s0, g + s0, m + s0, w16 + s0, cv.len - base, wd, scale, k.mu);
+      const int lim = cv.len - base, valid = cv.valid - base;
+      if (lim >= kTileElems) {
+        if (gc.fast(kTileElems, valid))
+          lars_p2_tile<true, BF16, GS, true>(w + s0, gc.tile(base), m + s0, w16 + s0, kTileElems, valid, wd, scale, k.mu);
+        else
+          lars_p2_tile<true, BF16, GS, false>(w + s0, gc.tile(base), m + s0, w16 + s0, kTileElems, valid, wd, scale, k.mu);
+      } else {
+        if (gc.fast(lim, valid))
+          lars_p2_tile<false, BF16, GS, true>(w + s0, gc.tile(base), m + s0, w16 + s0, lim, valid, wd, scale, k.mu);
+        else
+          lars_p2_tile<false, BF16, GS, false>(w + s0, gc.tile(base), m + s0, w16 + s0, lim, valid, wd, scale, k.mu);
+      }
     }
   } else {
     for (int e = threadIdx.x; e < cv.len; e += kBlock) {
       const int64_t s = cv.shard0 + e;
       float ww = w[s], mm = m[s];
-      lars_elem(ww, g[s], mm, wd, scale, k.mu);
+      lars_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, wd, scale, k.mu);
       w[s] = ww;
       m[s] = mm;
+      if constexpr (BF16) w16[s] = (uint16_t)bf16_of(ww);
+    }
+  }
+}
+
+// ---- Adam and momentum with the gradient read from the full tensors ---------------------------------
+// The flat kernels above need no table; reading the gradient in place does (which tensor, which
+// offset, how many real slots), so these walk the chunk table like the LAMB kernels.  Per element the
+// arithmetic is the flat kernels', and a padded slot sees g = +0.0: the same bits as shard_format
+// followed by the flat kernel.
+template <bool FULL, bool BF16, int GS, bool GFAST>
+__device__ __forceinline__ void adam_chunk_tile(float* w, const void* __restrict__ g, float* m, float* v,
+                                                uint16_t* __restrict__ w16, int lim, int valid, const AdamK& k) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rg[i] = load_g4<GS, GFAST, true>(g, o, valid);
+      rw[i] = ld4<PolAdam::RW>(w + o);
+      rm[i] = ld4<PolAdam::RW>(m + o);
+      rv[i] = ld4<PolAdam::RW>(v + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
+      adam_elem(rw[i].y, rg[i].y, rm[i].y, rv[i].y, k);
+      adam_elem(rw[i].z, rg[i].z, rm[i].z, rv[i].z, k);
+      adam_elem(rw[i].w, rg[i].w, rm[i].w, rv[i].w, k);
+      st4<PolAdam::ST>(w + o, rw[i]);
+      st4<PolAdam::ST>(m + o, rm[i]);
+      st4<PolAdam::ST>(v + o, rv[i]);
+      if constexpr (BF16) store_bf16x4<PolAdam::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
+template <bool VEC, bool BF16, int GS>
+__global__ __launch_bounds__(kBlock) void adam_chunk_kernel(const VarDesc* __restrict__ vars,
+                                                            const ChunkDesc* __restrict__ chunks, float* w,
+                                                            const void* const* __restrict__ g_full, float* m, float* v,
+                                                            uint16_t* __restrict__ w16, int r, AdamK k) {
+  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, r);
+  const GradChunk<GS> gc = grad_chunk<GS>(nullptr, g_full, cv);
+  if constexpr (VEC) {
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      const int lim = cv.len - base, valid = cv.valid - base;
+      if (lim >= kTileElems) {
+        if (gc.fast(kTileElems, valid))
+          adam_chunk_tile<true, BF16, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, w16 + s0, kTileElems, valid, k);
+        else
+          adam_chunk_tile<true, BF16, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, w16 + s0, kTileElems, valid, k);
+      } else {
+        if (gc.fast(lim, valid))
+          adam_chunk_tile<false, BF16, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, w16 + s0, lim, valid, k);
+        else
+          adam_chunk_tile<false, BF16, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, w16 + s0, lim, valid, k);
+      }
+    }
+  } else {
+    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+      const int64_t s = cv.shard0 + e;
+      float ww = w[s], mm = m[s], vv = v[s];
+      adam_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, vv, k);
+      w[s] = ww; m[s] = mm; v[s] = vv;
+      if constexpr (BF16) w16[s] = (uint16_t)bf16_of(ww);
+    }
+  }
+}
+
+template <bool FULL, bool BF16, int GS, bool GFAST>
+__device__ __forceinline__ void momentum_chunk_tile(float* w, const void* __restrict__ g, float* m,
+                                                    uint16_t* __restrict__ w16, int lim, int valid,
+                                                    const MomentumK& k) {
+  const int t4 = threadIdx.x * 4;
+  F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      rg[i] = load_g4<GS, GFAST, true>(g, o, valid);
+      rw[i] = ld4<PolMomentum::RW>(w + o);
+      rm[i] = ld4<PolMomentum::RW>(m + o);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int o = i * kBlock * 4 + t4;
+    if (FULL || o < lim) {
+      momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
+      momentum_elem(rw[i].y, rg[i].y, rm[i].y, k);
+      momentum_elem(rw[i].z, rg[i].z, rm[i].z, k);
+      momentum_elem(rw[i].w, rg[i].w, rm[i].w, k);
+      st4<PolMomentum::ST>(w + o, rw[i]);
+      st4<PolMomentum::ST>(m + o, rm[i]);
+      if constexpr (BF16) store_bf16x4<PolMomentum::ST>(w16 + o, rw[i]);
+    }
+  }
+}
+
+template <bool VEC, bool BF16, int GS>
+__global__ __launch_bounds__(kBlock) void momentum_chunk_kernel(const VarDesc* __restrict__ vars,
+                                                                const ChunkDesc* __restrict__ chunks, float* w,
+                                                                const void* const* __restrict__ g_full, float* m,
+                                                                uint16_t* __restrict__ w16, int r, MomentumK k) {
+  const ChunkView cv = chunk_view(vars, chunks, blockIdx.x, r);
+  const GradChunk<GS> gc = grad_chunk<GS>(nullptr, g_full, cv);
+  if constexpr (VEC) {
+    for (int base = 0; base < cv.len; base += kTileElems) {
+      const int64_t s0 = cv.shard0 + base;
+      const int lim = cv.len - base, valid = cv.valid - base;
+      if (lim >= kTileElems) {
+        if (gc.fast(kTileElems, valid))
+          momentum_chunk_tile<true, BF16, GS, true>(w + s0, gc.tile(base), m + s0, w16 + s0, kTileElems, valid, k);
+        else
+          momentum_chunk_tile<true, BF16, GS, false>(w + s0, gc.tile(base), m + s0, w16 + s0, kTileElems, valid, k);
+      } else {
+        if (gc.fast(lim, valid))
+          momentum_chunk_tile<false, BF16, GS, true>(w + s0, gc.tile(base), m + s0, w16 + s0, lim, valid, k);
+        else
+          momentum_chunk_tile<false, BF16, GS, false>(w + s0, gc.tile(base), m + s0, w16 + s0, lim, valid, k);
+      }
+    }
+  } else {
+    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+      const int64_t s = cv.shard0 + e;
+      float ww = w[s], mm = m[s];
+      momentum_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, k);
+      w[s] = ww; m[s] = mm;
       if constexpr (BF16) w16[s] = (uint16_t)bf16_of(ww);
     }
   }
@@ -1105,18 +1340,25 @@ hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, 
   return hipGetLastError();
 }
 
-hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, float* m, float* v, const AdamK& k,
-                          hipStream_t stream) {
+hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
+                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_LAMB_P1, stream);
   const dim3 grid((unsigned)p->chunks.size());
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   float* cs = ws_at<float>(p, p->ws.chunk_sums);
-  if (p->align % 4 == 0)
-    hipLaunchKernelGGL((lamb_p1_kernel<true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, v, cs, r, k);
-  else
-    hipLaunchKernelGGL((lamb_p1_kernel<false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, v, cs, r, k);
+  const bool vec = p->align % 4 == 0;
+#define SU_LAUNCH_P1(VEC, GS) \
+  hipLaunchKernelGGL((lamb_p1_kernel<VEC, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, m, v, cs, r, k)
+  if (g_source == 0) {
+    if (vec) SU_LAUNCH_P1(true, 0); else SU_LAUNCH_P1(false, 0);
+  } else if (g_source == 1) {
+    if (vec) SU_LAUNCH_P1(true, 1); else SU_LAUNCH_P1(false, 1);
+  } else {
+    if (vec) SU_LAUNCH_P1(true, 2); else SU_LAUNCH_P1(false, 2);
+  }
+#undef SU_LAUNCH_P1
   return hipGetLastError();
 }
 
@@ -1147,23 +1389,26 @@ hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, cons
   return hipGetLastError();
 }
 
-hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, hipStream_t stream) {
+hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
+                          const void* const* g_full, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_LARS_P1, stream);
   const dim3 grid((unsigned)p->chunks.size());
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   float* cs = ws_at<float>(p, p->ws.chunk_sums);
-  if (p->align % 4 == 0)
-    hipLaunchKernelGGL((lars_p1_kernel<true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, cs, r);
-  else
-    hipLaunchKernelGGL((lars_p1_kernel<false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, cs, r);
+  const bool vec = p->align % 4 == 0;
+#define SU_LAUNCH(VEC, GS) \
+  hipLaunchKernelGGL((lars_p1_kernel<VEC, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, cs, r)
+  if (g_source == 0) { if (vec) SU_LAUNCH(true, 0); else SU_LAUNCH(false, 0); }
+  else if (g_source == 1) { if (vec) SU_LAUNCH(true, 1); else SU_LAUNCH(false, 1); }
+  else { if (vec) SU_LAUNCH(true, 2); else SU_LAUNCH(false, 2); }
+#undef SU_LAUNCH
   return hipGetLastError();
 }
 
-hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, float* m, void* w16, const LarsK& k,
-                          const float* sums, hipStream_t stream) {
-  (void)r;
+hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, int g_source, const void* const* g_full,
+                          float* m, void* w16, const LarsK& k, const float* sums, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_LARS_P2, stream);
   const dim3 grid((unsigned)p->chunks.size());
@@ -1171,10 +1416,57 @@ hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, floa
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   const bool vec = p->align % 4 == 0;
   uint16_t* o = (uint16_t*)w16;
-  if (vec && o) hipLaunchKernelGGL((lars_p2_kernel<true, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
-  else if (vec) hipLaunchKernelGGL((lars_p2_kernel<true, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
-  else if (o) hipLaunchKernelGGL((lars_p2_kernel<false, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
-  else hipLaunchKernelGGL((lars_p2_kernel<false, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, m, o, sums, k);
+#define SU_LAUNCH(VEC, BF16, GS)                                                                                     \
+  hipLaunchKernelGGL((lars_p2_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, m, o, \
+                     sums, r, k)
+#define SU_LAUNCH_GS(GS)                     \
+  do {                                       \
+    if (vec && o) SU_LAUNCH(true, true, GS);   \
+    else if (vec) SU_LAUNCH(true, false, GS);  \
+    else if (o) SU_LAUNCH(false, true, GS);    \
+    else SU_LAUNCH(false, false, GS);          \
+  } while (0)
+  if (g_source == 0) SU_LAUNCH_GS(0);
+  else if (g_source == 1) SU_LAUNCH_GS(1);
+  else SU_LAUNCH_GS(2);
+#undef SU_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_adam_full_grads(shard_plan_t* p, int r, float* w, int g_source, const void* const* g_full, float* m,
+                                  float* v, void* w16, const AdamK& k, hipStream_t stream) {
+  if (p->chunks.empty()) return hipSuccess;
+  ProfScope ps(p, SHARD_K_ADAM, stream);
+  const dim3 grid((unsigned)p->chunks.size());
+  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
+  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
+  const bool vec = p->align % 4 == 0;
+  uint16_t* o = (uint16_t*)w16;
+#define SU_LAUNCH(VEC, BF16, GS)                                                                                       \
+  hipLaunchKernelGGL((adam_chunk_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g_full, m, v, \
+                     o, r, k)
+  if (g_source == 1) SU_LAUNCH_GS(1);
+  else SU_LAUNCH_GS(2);
+#undef SU_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_momentum_full_grads(shard_plan_t* p, int r, float* w, int g_source, const void* const* g_full,
+                                      float* m, void* w16, const MomentumK& k, hipStream_t stream) {
+  if (p->chunks.empty()) return hipSuccess;
+  ProfScope ps(p, SHARD_K_MOMENTUM, stream);
+  const dim3 grid((unsigned)p->chunks.size());
+  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
+  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
+  const bool vec = p->align % 4 == 0;
+  uint16_t* o = (uint16_t*)w16;
+#define SU_LAUNCH(VEC, BF16, GS)                                                                                        \
+  hipLaunchKernelGGL((momentum_chunk_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g_full, m, \
+                     o, r, k)
+  if (g_source == 1) SU_LAUNCH_GS(1);
+  else SU_LAUNCH_GS(2);
+#undef SU_LAUNCH
+#undef SU_LAUNCH_GS
   return hipGetLastError();
 }
 

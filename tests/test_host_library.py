@@ -250,6 +250,31 @@ def test_adafactor_argument_checks_without_touching_the_gpu():
     flat.free()
 
 
+def test_full_gradient_updates_check_arguments_without_touching_the_gpu():
+    """The *_full_grads entry points all need a bound plan (they read the chunk table)."""
+    EINVAL, ESTATE = -1, -5
+    from paper_2004_13336_amd._lib import AdamHP, LambHP, LarsHP, MomentumHP
+    adam, mom = AdamHP(1e-3, 0.9, 0.999, 1e-8, 0.0), MomentumHP(0.1, 0.9, 0.0)
+    lamb, lars = LambHP(1e-3, 0.9, 0.999, 1e-6, 0.01), LarsHP(0.1, 0.9, 0.0, 0.001, 0.0)
+    fake = C.c_void_p(0x1000)
+    ptrs = (C.c_void_p * 2)(0x2000, 0x3000)
+    plan = su.shard_plan([64, 5], 2)                               # never bound
+    h, L = plan.handle, lib()
+    calls = [
+        lambda r: L.shard_update_adam_full_grads(h, r, fake, ptrs, 0, fake, fake, None, C.byref(adam), 1, None),
+        lambda r: L.shard_update_momentum_full_grads(h, r, fake, ptrs, 0, fake, None, C.byref(mom), None),
+        lambda r: L.shard_update_lamb_partials_full_grads(h, r, fake, ptrs, 0, fake, fake, C.byref(lamb), 1, fake, None),
+        lambda r: L.shard_update_lamb_full_grads(h, r, fake, ptrs, 1, fake, fake, None, C.byref(lamb), 1, None, None, None),
+        lambda r: L.shard_update_lars_partials_full_grads(h, r, fake, ptrs, 0, fake, None),
+        lambda r: L.shard_update_lars_apply_full_grads(h, r, fake, ptrs, 0, fake, None, C.byref(lars), fake, None),
+        lambda r: L.shard_update_lars_full_grads(h, r, fake, ptrs, 1, fake, None, C.byref(lars), None, None, None),
+    ]
+    for call in calls:
+        assert call(0) == ESTATE
+        assert call(2) == EINVAL and call(-1) == EINVAL
+    plan.free()
+
+
 def test_header_is_valid_c99_and_the_c_client_builds():
     import subprocess
     proc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
