@@ -54,7 +54,8 @@ def parse_args():
     ap.add_argument("--table", default=None, help="also time every config x stage and write a JSON table here")
     ap.add_argument("--stage", default=None,
                     help="instead of the headline step, run ONE stage of --config at --replicas for --steps launches "
-                         "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all) "
+                         "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
+                         "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run one plain device copy of 1 GiB (2^28 float32), so that a rocprofv3 --pmc run "
@@ -227,6 +228,22 @@ def headline(args, torch, su, cfgs):
                    "what": "float32 LAMB update that also writes bf16(w'), bfloat16 gathered buffer and full tensors"}
     del g16, flat16, full16
 
+    # The same float32 step with the formatting of the gradient fused into the update (Section 5.1): phase 1
+    # reads replica r's pieces of the full gradients in place and no shard gradient is written.  Same
+    # result bit for bit; reported beside the headline, never as `value`.
+    def one_step_fused():
+        state["t"] += 1
+        su.shard_update_lamb_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v, hp, state["t"],
+                                        other_replicas_sumsq=wb.other)
+        su.unshard_format(plan, wb.gathered, wb.full_w)
+
+    for _ in range(3):
+        one_step_fused()
+    msf, _ = _time_region(torch, one_step_fused, args.steps)
+    fused_format = {"ms_per_step": round(msf, 5), "params_per_s": wb.real / (msf * 1e-3),
+                    "what": "shard_update_lamb_full_grads (gradient read in place from the full tensors, no "
+                            "shard_format launch) + unshard_format(w)"}
+
     out = {
         "metric": "shard weight-update params/s (340M LAMB, N=8, one replica's shard)",
         "value": wb.real / (ms_step * 1e-3),
@@ -243,6 +260,7 @@ def headline(args, torch, su, cfgs):
         "kernels": rooflines,
         "update_only": update_only,
         "bf16_gather": bf16_gather,
+        "fused_format": fused_format,
         "wall_ms_per_step": round(wall_ms, 5),
     }
     wb.free()
@@ -362,6 +380,25 @@ def table(args, torch, su, cfgs, path):
                                                                       other_replicas_sumsq=wb.other),
                                ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S))
             if wb.full_g is not None:
+                # the same update with the gradient read in place from the full tensors (no shard_format)
+                if cfg.optimizer == "adam":
+                    stages.append(("adam_full_grads",
+                                   lambda t: su.shard_update_adam_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v, hp, t,
+                                                                             w_bf16_out=wb.w16),
+                                   ["adam"], (30 if cfg.mixed_bf16 else 28) * S))
+                elif cfg.optimizer == "momentum":
+                    stages.append(("momentum_full_grads",
+                                   lambda t: su.shard_update_momentum_full_grads(plan, r, wb.w, wb.full_g, wb.m, hp),
+                                   ["momentum"], 20 * S))
+                    stages.append(("lars_full_grads",
+                                   lambda t: su.shard_update_lars_full_grads(plan, r, wb.w, wb.full_g, wb.m, lars_hp,
+                                                                             other_replicas_sumsq=wb.other),
+                                   ["lars_p1", "norm_reduce", "lars_p2"], 28 * S))
+                else:
+                    stages.append(("lamb_full_grads",
+                                   lambda t: su.shard_update_lamb_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v, hp, t,
+                                                                             other_replicas_sumsq=wb.other),
+                                   ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S))
                 stages.append(("shard_format", lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S))
                 stages.append(("unshard_format", lambda t: su.unshard_format(plan, wb.gathered, wb.full_w),
                                ["unshard"], 4 * N * S + 4 * cfg.total))
@@ -405,7 +442,7 @@ def one_stage(args, torch, su, cfgs):
         row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
         print(json.dumps(row))
         return
-    needs_full = name in ("shard_format", "unshard_format", "shard_format_all")
+    needs_full = name in ("shard_format", "unshard_format", "shard_format_all") or name.endswith("_full_grads")
     wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full)
     plan, S = wb.plan, wb.S
     hp = wb.hp()
@@ -425,6 +462,19 @@ def one_stage(args, torch, su, cfgs):
                  ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S),
     }
     if needs_full:
+        # the updates that read the gradient in place from the full tensors: the bytes of the plain update
+        stages["adam_full_grads"] = (lambda t: su.shard_update_adam_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v,
+                                                                                adam_hp, t, w_bf16_out=wb.w16),
+                                     ["adam"], (30 if cfg.mixed_bf16 else 28) * S)
+        stages["momentum_full_grads"] = (lambda t: su.shard_update_momentum_full_grads(plan, r, wb.w, wb.full_g, wb.m,
+                                                                                        mom_hp), ["momentum"], 20 * S)
+        stages["lamb_full_grads"] = (lambda t: su.shard_update_lamb_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v,
+                                                                                lamb_hp, t,
+                                                                                other_replicas_sumsq=wb.other),
+                                     ["lamb_p1", "norm_reduce", "lamb_p2"], 40 * S)
+        stages["lars_full_grads"] = (lambda t: su.shard_update_lars_full_grads(plan, r, wb.w, wb.full_g, wb.m, lars_hp,
+                                                                                other_replicas_sumsq=wb.other),
+                                     ["lars_p1", "norm_reduce", "lars_p2"], 28 * S)
         stages["shard_format"] = (lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S)
         stages["unshard_format"] = (lambda t: su.unshard_format(plan, wb.gathered, wb.full_w), ["unshard"],
                                     4 * N * S + 4 * cfg.total)
