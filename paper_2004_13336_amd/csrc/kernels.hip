@@ -37,6 +37,10 @@
 #ifndef SU_NT_LAMB
 #define SU_NT_LAMB 6
 #endif
+#ifndef SU_NT_LAMB_P2
+#define SU_NT_LAMB_P2 5    // phase 2 of LAMB: w is loaded through the caches and stored past them (measured on the
+                           // whole step: the unshard that follows gains as much as phase 2 itself)
+#endif
 #ifndef SU_NT_LARS
 #define SU_NT_LARS 6
 #endif
@@ -84,6 +88,7 @@ constexpr int kCopyBlock = SU_COPY_BLOCK;
 typedef Policy<SU_NT_ADAM> PolAdam;
 typedef Policy<SU_NT_MOMENTUM> PolMomentum;
 typedef Policy<SU_NT_LAMB> PolLamb;
+typedef Policy<SU_NT_LAMB_P2> PolLambP2;
 typedef Policy<SU_NT_LARS> PolLars;
 typedef Policy<SU_NT_FORMAT> PolFormat;
 typedef Policy<SU_NT_UNSHARD> PolUnshard;
@@ -832,9 +837,9 @@ __device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__
   for (int i = 0; i < kUnroll; ++i) {
     const int o = i * kBlock * 4 + t4;
     if (FULL || o < lim) {
-      rw[i] = ld4<PolLamb::RW>(w + o);
-      rm[i] = ld4<PolLamb::RO>(m + o);
-      rv[i] = ld4<PolLamb::RO>(v + o);
+      rw[i] = ld4<PolLambP2::RW>(w + o);
+      rm[i] = ld4<PolLambP2::RO>(m + o);
+      rv[i] = ld4<PolLambP2::RO>(v + o);
     }
   }
 #pragma unroll
@@ -845,8 +850,8 @@ __device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__
       rw[i].y = fmaf(-step, lamb_dir(rw[i].y, rm[i].y, rv[i].y, wd, k), rw[i].y);
       rw[i].z = fmaf(-step, lamb_dir(rw[i].z, rm[i].z, rv[i].z, wd, k), rw[i].z);
       rw[i].w = fmaf(-step, lamb_dir(rw[i].w, rm[i].w, rv[i].w, wd, k), rw[i].w);
-      st4<PolLamb::ST>(w + o, rw[i]);
-      if constexpr (BF16) store_bf16x4<PolLamb::ST>(w16 + o, rw[i]);
+      st4<PolLambP2::ST>(w + o, rw[i]);
+      if constexpr (BF16) store_bf16x4<PolLambP2::ST>(w16 + o, rw[i]);
     }
   }
 }
