@@ -23,8 +23,11 @@
 #define SU_UNROLL 2        // chunk-table kernels: 128-bit accesses per thread per stream in flight; 2 makes a tile the
                            // default 2048-slot chunk, so that whole chunks run the branch-free path (4: phase 1 +5 %)
 #endif
-#ifndef SU_FLAT_UNROLL
-#define SU_FLAT_UNROLL 4   // Adam / momentum kernels: the same
+#ifndef SU_ADAM_UNROLL
+#define SU_ADAM_UNROLL 1       // flat Adam kernel: the same (1: -2 to -5 % against 4 on shards of 12 M to 1.5 G slots)
+#endif
+#ifndef SU_MOMENTUM_UNROLL
+#define SU_MOMENTUM_UNROLL 2   // flat momentum kernel
 #endif
 // Cache policy per kernel family, as a 3-bit mask: 4 = non-temporal loads of streams that are only
 // read, 2 = non-temporal loads of streams the same thread writes back in place, 1 = non-temporal
@@ -86,7 +89,8 @@ namespace su {
 namespace {
 
 constexpr int kUnroll = SU_UNROLL;
-constexpr int kFlatUnroll = SU_FLAT_UNROLL;
+constexpr int kAdamUnroll = SU_ADAM_UNROLL;
+constexpr int kMomentumUnroll = SU_MOMENTUM_UNROLL;
 constexpr int kCopyBlock = SU_COPY_BLOCK;
 
 typedef Policy<SU_NT_ADAM> PolAdam;
@@ -572,9 +576,10 @@ __device__ __forceinline__ float lamb_dir(float w, float m, float v, float wd, c
 // Padded slots are a fixed point of both updates (0 in, +0.0 out), so the packed shard is
 // processed as one flat array: no table, no masks.
 
-// One tile = kBlock * kFlatUnroll 128-bit accesses per stream.  FULL tiles (all but possibly the last)
+// One tile = kBlock * unroll 128-bit accesses per stream.  FULL tiles (all but possibly the last)
 // run without a single branch: every load of the tile is issued before the first use.
-constexpr int kFlatTileElems = kBlock * kFlatUnroll * 4;   // float32 elements per tile and stream
+constexpr int kAdamTileElems = kBlock * kAdamUnroll * 4;   // float32 elements per tile and stream
+constexpr int kMomentumTileElems = kBlock * kMomentumUnroll * 4;
 constexpr int kTileElems = kBlock * kUnroll * 4;           // the same for the LAMB kernels
 
 template <bool FULL, bool BF16>
@@ -582,9 +587,9 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
                                           uint16_t* __restrict__ w16, int lim4, const AdamK& k) {
   // w, g, m, v, w16 point at the tile; lim4 = 128-bit units of the tile that exist (FULL: all)
   const int t4 = threadIdx.x * 4;
-  F4 rw[kFlatUnroll], rg[kFlatUnroll], rm[kFlatUnroll], rv[kFlatUnroll];
+  F4 rw[kAdamUnroll], rg[kAdamUnroll], rm[kAdamUnroll], rv[kAdamUnroll];
 #pragma unroll
-  for (int i = 0; i < kFlatUnroll; ++i) {
+  for (int i = 0; i < kAdamUnroll; ++i) {
     if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
       const int o = i * kBlock * 4 + t4;
       rg[i] = ld4<PolAdam::RO>(g + o);
@@ -594,7 +599,7 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
     }
   }
 #pragma unroll
-  for (int i = 0; i < kFlatUnroll; ++i) {
+  for (int i = 0; i < kAdamUnroll; ++i) {
     if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
       const int o = i * kBlock * 4 + t4;
       adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
@@ -612,10 +617,10 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void adam_kernel(float* w, const float* __restrict__ g, float* m, float* v,
                                                       uint16_t* __restrict__ w16, int64_t n4, int tail, AdamK k) {
-  const int64_t tile4 = (int64_t)kBlock * kFlatUnroll;
+  const int64_t tile4 = (int64_t)kBlock * kAdamUnroll;
   const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t e0 = t * kFlatTileElems;
+    const int64_t e0 = t * kAdamTileElems;
     const int64_t left4 = n4 - t * tile4;
     if (left4 >= tile4)
       adam_tile<true, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)tile4, k);
@@ -635,9 +640,9 @@ template <bool FULL, bool BF16>
 __device__ __forceinline__ void momentum_tile(float* w, const float* __restrict__ g, float* m,
                                               uint16_t* __restrict__ w16, int lim4, const MomentumK& k) {
   const int t4 = threadIdx.x * 4;
-  F4 rw[kFlatUnroll], rg[kFlatUnroll], rm[kFlatUnroll];
+  F4 rw[kMomentumUnroll], rg[kMomentumUnroll], rm[kMomentumUnroll];
 #pragma unroll
-  for (int i = 0; i < kFlatUnroll; ++i) {
+  for (int i = 0; i < kMomentumUnroll; ++i) {
     if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
       const int o = i * kBlock * 4 + t4;
       rg[i] = ld4<PolMomentum::RO>(g + o);
@@ -646,7 +651,7 @@ __device__ __forceinline__ void momentum_tile(float* w, const float* __restrict_
     }
   }
 #pragma unroll
-  for (int i = 0; i < kFlatUnroll; ++i) {
+  for (int i = 0; i < kMomentumUnroll; ++i) {
     if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
       const int o = i * kBlock * 4 + t4;
       momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
@@ -664,10 +669,10 @@ template <bool BF16>
 __global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float* __restrict__ g, float* m,
                                                           uint16_t* __restrict__ w16, int64_t n4, int tail,
                                                           MomentumK k) {
-  const int64_t tile4 = (int64_t)kBlock * kFlatUnroll;
+  const int64_t tile4 = (int64_t)kBlock * kMomentumUnroll;
   const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t e0 = t * kFlatTileElems;
+    const int64_t e0 = t * kMomentumTileElems;
     const int64_t left4 = n4 - t * tile4;
     if (left4 >= tile4)
       momentum_tile<true, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)tile4, k);
@@ -1183,8 +1188,8 @@ __global__ __launch_bounds__(kBlock) void momentum_chunk_kernel(const VarDesc* _
   }
 }
 
-inline unsigned flat_grid(int64_t n4) {
-  const int64_t tile = (int64_t)kBlock * kFlatUnroll;
+inline unsigned flat_grid(int64_t n4, int unroll) {
+  const int64_t tile = (int64_t)kBlock * unroll;
   int64_t tiles = (n4 + tile - 1) / tile;
   if (tiles < 1) tiles = 1;
 #if SU_GRID_CAP > 0
@@ -1327,10 +1332,10 @@ hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, floa
   const int64_t n4 = p->S >> 2;
   const int tail = (int)(p->S & 3);
   if (w16)
-    hipLaunchKernelGGL((adam_kernel<true>), dim3(flat_grid(n4)), dim3(kBlock), 0, stream, w, g, m, v, (uint16_t*)w16,
+    hipLaunchKernelGGL((adam_kernel<true>), dim3(flat_grid(n4, kAdamUnroll)), dim3(kBlock), 0, stream, w, g, m, v, (uint16_t*)w16,
                        n4, tail, k);
   else
-    hipLaunchKernelGGL((adam_kernel<false>), dim3(flat_grid(n4)), dim3(kBlock), 0, stream, w, g, m, v,
+    hipLaunchKernelGGL((adam_kernel<false>), dim3(flat_grid(n4, kAdamUnroll)), dim3(kBlock), 0, stream, w, g, m, v,
                        (uint16_t*)nullptr, n4, tail, k);
   return hipGetLastError();
 }
@@ -1342,10 +1347,10 @@ hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, 
   const int64_t n4 = p->S >> 2;
   const int tail = (int)(p->S & 3);
   if (w16)
-    hipLaunchKernelGGL((momentum_kernel<true>), dim3(flat_grid(n4)), dim3(kBlock), 0, stream, w, g, m, (uint16_t*)w16,
+    hipLaunchKernelGGL((momentum_kernel<true>), dim3(flat_grid(n4, kMomentumUnroll)), dim3(kBlock), 0, stream, w, g, m, (uint16_t*)w16,
                        n4, tail, k);
   else
-    hipLaunchKernelGGL((momentum_kernel<false>), dim3(flat_grid(n4)), dim3(kBlock), 0, stream, w, g, m,
+    hipLaunchKernelGGL((momentum_kernel<false>), dim3(flat_grid(n4, kMomentumUnroll)), dim3(kBlock), 0, stream, w, g, m,
                        (uint16_t*)nullptr, n4, tail, k);
   return hipGetLastError();
 }
