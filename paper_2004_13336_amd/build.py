@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG_DIR, "libshardupdate.so")
 
-SOURCES = ["plan.cpp", "topology.cpp", "api.cpp", "kernels.hip", "rowplan.hip"]
+SOURCES = ["plan.cpp", "topology.cpp", "api.cpp", "profile.cpp", "copies.hip", "updates.hip", "rowplan.hip"]
 
 # -ffp-contract=off: fused multiply-adds only where the source writes fmaf(), so every kernel
 #   variant performs the same arithmetic per element.

@@ -1,5 +1,5 @@
 // The C-ABI layer: argument checks, host-side constant folding, pointer-table caching.
-// Every kernel launch lives in kernels.hip; nothing here computes on tensor data.
+// Every kernel launch lives in the .hip files; nothing here computes on tensor data.
 #include <cmath>
 #include <cstring>
 #include <new>

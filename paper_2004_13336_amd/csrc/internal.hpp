@@ -187,7 +187,8 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
                const uint32_t* flags, int chunk);
 size_t workspace_layout(const shard_plan_t* p, Workspace* ws);
 
-// kernels.hip: every launcher enqueues on `stream`, returns a hipError_t and never synchronises.
+// copies.hip, updates.hip, rowplan.hip: every launcher enqueues on `stream`, returns a hipError_t and never
+// synchronises.
 hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const void** dev_table, hipStream_t stream);
 
 hipError_t launch_format(shard_plan_t* p, int r, const void* const* dev_ptr_table, int src_dtype, void* out,

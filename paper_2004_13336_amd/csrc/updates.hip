@@ -1,23 +1,20 @@
-// HIP kernels for gfx950 (MI355X) and their launchers.
+// Optimizer kernels for gfx950 (MI355X) and their launchers: Adam, momentum, LAMB, LARS on a packed shard.
 //
 // Everything here is bound by HBM bandwidth (Section 2.2: the weight update reads the gradient,
 // the weight and the auxiliary variables and writes the weight and the auxiliaries back; the
 // arithmetic in between is a handful of element-wise operations).  The kernels therefore do
 // nothing clever with the arithmetic and everything they can for the memory system:
 //   * every lane moves 128 bits per access, a 64-lane wavefront covers 1 KiB of one stream;
-//   * each thread issues all the loads of its tile (kUnroll accesses per stream) before the
-//     first dependent instruction, so a workgroup keeps tens of KiB in flight;
-//   * one launch covers a whole shard: variables are addressed through a chunk table, so
-//     hundreds of small variables cost no launches of their own (the single-GPU analogue of
-//     the paper's batching of small tensors, Section 5.2);
+//   * each thread issues all the loads of its tile before the first dependent instruction, so a
+//     workgroup keeps tens of KiB in flight;
+//   * one launch covers a whole shard: the element-wise updates run flat over [S], the ones with
+//     per-variable reductions walk the chunk table;
 //   * the per-variable sums of squares are reduced with wavefront shuffles and LDS, in a fixed
 //     order, without atomics.
 // The file is compiled with -ffp-contract=off: fused multiply-adds appear only where fmaf() is
 // written, so every kernel (vector path, scalar path, sharded or not) performs bit-identical
 // arithmetic per element.
-#include <type_traits>
-
-#include "device_common.hpp"
+#include "chunk_view.hpp"
 
 #ifndef SU_UNROLL
 #define SU_UNROLL 2        // chunk-table kernels: 128-bit accesses per thread per stream in flight; 2 makes a tile the
@@ -51,30 +48,6 @@
 #ifndef SU_NT_LARS_P2
 #define SU_NT_LARS_P2 5    // phase 2 of LARS: as LAMB's (w and m loaded through the caches): 122 -> 116 us on 25.6 M slots
 #endif
-#ifndef SU_NT_FORMAT
-#define SU_NT_FORMAT 4
-#endif
-#ifndef SU_NT_FORMAT_ALL
-#define SU_NT_FORMAT_ALL 5    // all-replica formatting: the output goes to a collective, not to the next kernel
-#endif
-#ifndef SU_NT_UNSHARD
-#define SU_NT_UNSHARD 5
-#endif
-#ifndef SU_COPY_BLOCK
-#define SU_COPY_BLOCK 256     // threads per workgroup of the formatting kernels
-#endif
-// Units per thread of the formatting kernels, all loaded before the first store.  One replica's
-// formatting (a few hundred MB, partly served by the memory-side cache) measures fastest with 2;
-// the whole-model copies (unshard, all-replica formatting) with 1.
-#ifndef SU_FORMAT_UNROLL
-#define SU_FORMAT_UNROLL 2
-#endif
-#ifndef SU_UNSHARD_UNROLL
-#define SU_UNSHARD_UNROLL 1
-#endif
-#ifndef SU_FORMAT_ALL_UNROLL
-#define SU_FORMAT_ALL_UNROLL 1
-#endif
 #ifndef SU_P1_REVERSE
 #define SU_P1_REVERSE 0        // 1: LAMB phase 1 walks the chunk table from the end
 #endif
@@ -91,7 +64,6 @@ namespace {
 constexpr int kUnroll = SU_UNROLL;
 constexpr int kAdamUnroll = SU_ADAM_UNROLL;
 constexpr int kMomentumUnroll = SU_MOMENTUM_UNROLL;
-constexpr int kCopyBlock = SU_COPY_BLOCK;
 
 typedef Policy<SU_NT_ADAM> PolAdam;
 typedef Policy<SU_NT_MOMENTUM> PolMomentum;
@@ -99,37 +71,6 @@ typedef Policy<SU_NT_LAMB> PolLamb;
 typedef Policy<SU_NT_LAMB_P2> PolLambP2;
 typedef Policy<SU_NT_LARS> PolLars;
 typedef Policy<SU_NT_LARS_P2> PolLarsP2;
-typedef Policy<SU_NT_FORMAT> PolFormat;
-typedef Policy<SU_NT_UNSHARD> PolUnshard;
-typedef Policy<SU_NT_FORMAT_ALL> PolFormatAll;
-
-// ---- pieces shared by the table-driven kernels ----------------------------------------------------
-
-struct ChunkView {
-  int var;
-  int len;          // slots in this chunk
-  int valid;        // leading slots that hold real elements on replica r (Section 4.1: position
-                    // in the full variable = replica offset + index, compared with its length)
-  int64_t shard0;   // offset of the chunk inside a packed shard
-  int64_t flat0;    // offset of the chunk inside the flat variable
-  uint32_t flags;
-};
-
-__device__ __forceinline__ ChunkView chunk_view(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
-                                                int c, int r) {
-  const ChunkDesc cd = chunks[c];
-  const VarDesc vd = vars[cd.var];
-  ChunkView cv;
-  cv.var = cd.var;
-  cv.len = cd.len;
-  cv.flat0 = (int64_t)r * vd.stride + cd.k0;
-  int64_t rem = vd.n - cv.flat0;                            // up to the end of the variable ...
-  if (vd.stride - cd.k0 < rem) rem = vd.stride - cd.k0;     // ... and of the piece's real slots
-  cv.valid = rem <= 0 ? 0 : (rem < (int64_t)cd.len ? (int)rem : cd.len);
-  cv.shard0 = vd.off + cd.k0;
-  cv.flags = vd.flags;
-  return cv;
-}
 
 // Sum over the workgroup of two per-thread values, in a fixed order; the result is valid in
 // thread 0.  Wavefront step: xor shuffles; cross-wavefront step: LDS.
@@ -227,319 +168,6 @@ __device__ __forceinline__ F4 load_g4(const void* g, int o, int valid) {
     x.w = (o + 3 < valid) ? bf16_up(ld<true>(p + 3)) : 0.0f;
     return x;
   }
-}
-
-// ---- pointer table --------------------------------------------------------------------------------
-// Device pointer tables are written by a kernel that carries the pointers as launch arguments:
-// stream-ordered, no host staging buffer whose lifetime would have to be tracked.
-__global__ __launch_bounds__(kPtrBatch) void ptr_table_kernel(PtrBatch b, const void** dst, int count) {
-  const int i = threadIdx.x;
-  if (i < count) dst[i] = b.p[i];
-}
-
-// ---- shard_format / unshard_format ----------------------------------------------------------------
-// A unit is what one lane moves per access: 4 elements whenever float32 is involved (one 128-bit
-// access on the float32 side, 64 bits on the bfloat16 side), 8 elements for bfloat16 -> bfloat16
-// (128 bits on both sides).  Consecutive lanes take consecutive units, so every wavefront access
-// covers one contiguous span of memory.
-
-template <int DT> struct ElemOf;
-template <> struct ElemOf<SHARD_F32> { typedef uint32_t type; };
-template <> struct ElemOf<SHARD_BF16> { typedef uint16_t type; };
-
-template <int SRC, int DST>
-struct UnitOf {
-  static constexpr int n = (SRC == SHARD_BF16 && DST == SHARD_BF16) ? 8 : 4;
-};
-
-template <typename Pol, int DT, int UNIT>
-__device__ __forceinline__ void load_unit(const typename ElemOf<DT>::type* p, uint32_t (&x)[UNIT]) {
-  if constexpr (DT == SHARD_F32) {
-    static_assert(UNIT == 4, "float32 units are 4 elements");
-    const u4 a = ld<Pol::RO>((const u4*)p);
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-  } else if constexpr (UNIT == 8) {
-    const u4 a = ld<Pol::RO>((const u4*)p);
-    x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
-    x[4] = a.z & 0xFFFFu; x[5] = a.z >> 16; x[6] = a.w & 0xFFFFu; x[7] = a.w >> 16;
-  } else {
-    const u2 a = ld<Pol::RO>((const u2*)p);
-    x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
-  }
-}
-template <typename Pol, int DT, int UNIT>
-__device__ __forceinline__ void store_unit(typename ElemOf<DT>::type* p, const uint32_t (&x)[UNIT]) {
-  if constexpr (DT == SHARD_F32) {
-    static_assert(UNIT == 4, "float32 units are 4 elements");
-    u4 a;
-    a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
-    st<Pol::ST>((u4*)p, a);
-  } else if constexpr (UNIT == 8) {
-    u4 a;
-    a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16); a.z = x[4] | (x[5] << 16); a.w = x[6] | (x[7] << 16);
-    st<Pol::ST>((u4*)p, a);
-  } else {
-    u2 a;
-    a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16);
-    st<Pol::ST>((u2*)p, a);
-  }
-}
-template <int SRC, int DST>
-__device__ __forceinline__ uint32_t convert(uint32_t b) {
-  if constexpr (SRC == DST) return b;
-  else if constexpr (SRC == SHARD_F32) return bf16_from_f32_bits(b);
-  else return b << 16;
-}
-
-// Work items of the formatting kernels are (replica, chunk, tile) triples: a chunk is cut into
-// tiles of kCopyBlock * U units (U per thread) and every tile is one short-lived workgroup.  Many small workgroups,
-// dispatched in address order, keep the set of DRAM pages in flight compact, which measures
-// faster on MI355X than fewer workgroups that each loop over more data.  The table look-ups
-// (chunk -> variable -> pointer) of the tiles of one chunk hit the same cache lines.
-// VEC: pieces (and gathered rows) are 16-byte aligned and every chunk length is a multiple of 8;
-// whether a variable's full tensor is aligned too is tested per item.
-
-// One tile of a copy: consecutive lanes on consecutive units.
-// ALL: every unit of the tile holds real elements only; the tile moves without a branch.
-// Otherwise units that end at or before `whole` are moved whole, and (shard_format only) units
-// that start at or after `zero_from` and before `len` are written as zeros.  The one unit that
-// straddles the end of the variable, if any, is left to copy_tile's caller.
-template <typename Pol, int SRC, int DST, int U, bool ALL, bool UNSHARD>
-__device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src, typename ElemOf<DST>::type* dst,
-                                           int whole, int zero_from, int len) {
-  constexpr int UNIT = UnitOf<SRC, DST>::n;
-  uint32_t x[U][UNIT];
-#pragma unroll
-  for (int i = 0; i < U; ++i) {
-    const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
-    if (ALL || e + UNIT <= whole) load_unit<Pol, SRC, UNIT>(src + e, x[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < U; ++i) {
-    const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
-    if (ALL || e + UNIT <= whole) {
-#pragma unroll
-      for (int j = 0; j < UNIT; ++j) x[i][j] = convert<SRC, DST>(x[i][j]);
-      store_unit<Pol, DST, UNIT>(dst + e, x[i]);
-    } else if (!UNSHARD && e >= zero_from && e < len) {
-#pragma unroll
-      for (int j = 0; j < UNIT; ++j) x[i][j] = 0u;
-      store_unit<Pol, DST, UNIT>(dst + e, x[i]);
-    }
-  }
-}
-
-// Moves tile `t` of a chunk.  shard_format: zero-padded piece of the flat variable -> packed shard
-// (all `len` slots written).  unshard_format: the `valid` real elements of a gathered piece -> flat
-// variable (padding dropped).  src and dst point at the chunk's first slot.
-template <typename Pol, int SRC, int DST, int U, bool VEC, bool UNSHARD>
-__device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const typename ElemOf<SRC>::type* src,
-                                          typename ElemOf<DST>::type* dst) {
-  typedef typename ElemOf<DST>::type DstT;
-  constexpr int UNIT = UnitOf<SRC, DST>::n;
-  constexpr int TILE = kCopyBlock * U * UNIT;
-  const int base = t * TILE;
-  if (base >= (UNSHARD ? cv.valid : cv.len)) return;
-  if constexpr (VEC) {
-    if (base + TILE <= cv.valid) {
-      copy_units<Pol, SRC, DST, U, true, UNSHARD>(src + base, dst + base, TILE, TILE, TILE);
-      return;
-    }
-    const int whole = cv.valid / UNIT * UNIT;                  // slots covered by fully real units
-    const int zero_from = (cv.valid + UNIT - 1) / UNIT * UNIT; // first unit that is all padding
-    copy_units<Pol, SRC, DST, U, false, UNSHARD>(src + base, dst + base, whole - base, zero_from - base, cv.len - base);
-    // the unit that straddles the end of the variable: real elements, then (shard_format) zeros
-    if (whole != cv.valid && whole >= base && whole < base + TILE && (int)threadIdx.x < UNIT) {
-      const int e = whole + threadIdx.x;
-      if (e < cv.valid) dst[e] = (DstT)convert<SRC, DST>((uint32_t)src[e]);
-      else if (!UNSHARD) dst[e] = (DstT)0;
-    }
-  } else {
-    const int end = (UNSHARD ? cv.valid : cv.len) < base + TILE ? (UNSHARD ? cv.valid : cv.len) : base + TILE;
-    for (int e = base + threadIdx.x; e < end; e += kCopyBlock)
-      dst[e] = (DstT)((e < cv.valid) ? convert<SRC, DST>((uint32_t)src[e]) : 0u);
-  }
-}
-
-// UNSHARD = false: shard_format; `packed` is the output, shard r0 + replica goes to row `replica`.
-// UNSHARD = true : unshard_format; `packed` is the gathered buffer, r0 = 0.
-// blockIdx.x = (replica * n_chunks + chunk) * tiles_per_chunk + tile.
-template <typename Pol, int SRC, int DST, int U, bool VEC, bool UNSHARD>
-__device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
-                                              const void* const* __restrict__ ptrs, void* packed, int r0,
-                                              int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  typedef typename ElemOf<SRC>::type SrcT;
-  typedef typename ElemOf<DST>::type DstT;
-  const int item = blockIdx.x / tiles_per_chunk;
-  const int tile = blockIdx.x - item * tiles_per_chunk;
-  const int replica = item / n_chunks;
-  const ChunkView cv = chunk_view(vars, chunks, item - replica * n_chunks, r0 + replica);
-  // skip the pointer look-up for tiles with nothing to do (beyond a short chunk, or all padding)
-  constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
-  if (tile * TILE >= (UNSHARD ? cv.valid : cv.len)) return;
-  const void* ptr = ptrs[cv.var];
-  // 128-bit accesses need this chunk's place in the full tensor on a 16-byte boundary (VEC already
-  // says its place in the shard is); a tensor or a row-plan piece that is not takes the
-  // element-wise path, the others are unaffected
-  const uintptr_t full_addr = reinterpret_cast<uintptr_t>(ptr) + (uintptr_t)cv.flat0 * sizeof(typename ElemOf<UNSHARD ? DST : SRC>::type);
-  const bool vec = VEC && (full_addr & 15u) == 0;
-  if constexpr (UNSHARD) {
-    const SrcT* src = (const SrcT*)packed + (int64_t)replica * row_stride + cv.shard0;
-    DstT* dst = (DstT*)const_cast<void*>(ptr) + cv.flat0;
-    if (vec) copy_tile<Pol, SRC, DST, U, true, true>(cv, tile, src, dst);
-    else copy_tile<Pol, SRC, DST, U, false, true>(cv, tile, src, dst);
-  } else {
-    const SrcT* src = (const SrcT*)ptr + cv.flat0;      // not dereferenced where there is no real element
-    DstT* dst = (DstT*)packed + (int64_t)replica * row_stride + cv.shard0;
-    if (vec) copy_tile<Pol, SRC, DST, U, true, false>(cv, tile, src, dst);
-    else copy_tile<Pol, SRC, DST, U, false, false>(cv, tile, src, dst);
-  }
-}
-
-// ---- whole-model copies on a flat plan, variable by variable ---------------------------------------
-// unshard_format and shard_format_all move every variable between its full tensor and the N rows of
-// the gathered buffer.  On a flat plan the gathered buffer holds, for variable i, an [N][L_i] view of
-// the variable padded to N*L_i slots: padded slot p lives in row p / L_i at off_i + p % L_i, and
-// the full tensor is the first n_i padded slots.  Work items are chunks of padded slots (FullChunk),
-// cut into tiles like the items above: the full-tensor side of a tile is one contiguous span, the
-// gathered side consists of runs of L_i slots.  The number of workgroups follows the model size, so
-// thousands of replicas with pieces of a few slots cost no more launches' worth of work than eight.
-// Units (4 or 8 slots) never straddle two pieces because L_i is a multiple of 8 on the VEC path.
-
-// Slot `d` counted from the start of piece r0 (d < L + 16384): which piece and where in it.
-__device__ __forceinline__ void locate(int64_t d, int64_t L, int64_t r0, int64_t& r, int64_t& k) {
-  if (L >= (int64_t)1 << 30) {               // a tile can reach into the next piece at most
-    const bool next = d >= L;
-    r = r0 + (next ? 1 : 0);
-    k = next ? d - L : d;
-  } else {                                    // d < 2^30 + 2^14: 32-bit division
-    const uint32_t q = (uint32_t)d / (uint32_t)L;
-    r = r0 + q;
-    k = (int64_t)((uint32_t)d - q * (uint32_t)L);
-  }
-}
-
-// TO_FULL: gathered -> full tensors (unshard_format), padding dropped.
-// otherwise: full tensors -> gathered rows (shard_format_all), padding written as zeros.
-template <typename Pol, int SRC, int DST, int U, bool VEC, bool TO_FULL>
-__device__ __forceinline__ void reformat_flat_body(const VarDesc* __restrict__ vars,
-                                                   const FullChunk* __restrict__ fchunks,
-                                                   const void* const* __restrict__ ptrs, void* packed,
-                                                   int64_t row_stride, int tiles_per_chunk) {
-  typedef typename ElemOf<SRC>::type SrcT;
-  typedef typename ElemOf<DST>::type DstT;
-  typedef typename ElemOf<TO_FULL ? DST : SRC>::type FullT;
-  typedef typename ElemOf<TO_FULL ? SRC : DST>::type PackT;
-  constexpr int UNIT = UnitOf<SRC, DST>::n;
-  constexpr int TILE = kCopyBlock * U * UNIT;
-  const int item = blockIdx.x / tiles_per_chunk;
-  const int tile = blockIdx.x - item * tiles_per_chunk;
-  const FullChunk fc = fchunks[item];
-  const int base = tile * TILE;
-  if (base >= fc.len) return;
-  const VarDesc vd = vars[fc.var];
-  const int64_t p_tile = fc.p0 + base;                       // first padded slot of the tile = flat index
-  if (TO_FULL && p_tile >= vd.n) return;                     // a tile of padding: nothing to restore
-  const int here = fc.len - base < TILE ? fc.len - base : TILE;
-  const int64_t r0 = p_tile / vd.L;
-  const int64_t k0 = p_tile - r0 * vd.L;
-  const void* ptr = ptrs[fc.var];
-  FullT* full = (FullT*)const_cast<void*>(ptr) + p_tile;     // not dereferenced past the variable's end
-  PackT* rows = (PackT*)packed + vd.off;
-  const bool vec = VEC && (reinterpret_cast<uintptr_t>(full) & 15u) == 0;
-  const int64_t real = vd.n - p_tile;                        // slots of the tile that exist in the full tensor (may exceed it)
-  if (vec) {
-    uint32_t x[U][UNIT];
-    int64_t po[U];                                           // offset of the unit in the gathered buffer, -1: none
-    const bool single = k0 + here <= vd.L;                   // the whole tile lies in piece r0
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
-      po[i] = -1;
-      if (e < here) {
-        int64_t r = r0, k = k0 + e;
-        if (!single) locate(k0 + e, vd.L, r0, r, k);
-        po[i] = r * row_stride + k;
-        if (TO_FULL) {
-          if (e + UNIT <= real) load_unit<Pol, SRC, UNIT>((const SrcT*)rows + po[i], x[i]);
-        } else {
-          if (e + UNIT <= real) load_unit<Pol, SRC, UNIT>((const SrcT*)full + e, x[i]);
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int e = (i * kCopyBlock + (int)threadIdx.x) * UNIT;
-      if (po[i] < 0) continue;
-      if (e + UNIT <= real) {
-#pragma unroll
-        for (int j = 0; j < UNIT; ++j) x[i][j] = convert<SRC, DST>(x[i][j]);
-        if (TO_FULL) store_unit<Pol, DST, UNIT>((DstT*)full + e, x[i]);
-        else store_unit<Pol, DST, UNIT>((DstT*)rows + po[i], x[i]);
-      } else if (TO_FULL) {
-        // the unit that straddles the end of the variable: its real slots one by one
-        for (int j = 0; j < UNIT; ++j)
-          if (e + j < real) ((DstT*)full)[e + j] = (DstT)convert<SRC, DST>((uint32_t)((const SrcT*)rows)[po[i] + j]);
-      } else {
-        // past (or across) the end of the variable: real slots, then zeros
-#pragma unroll
-        for (int j = 0; j < UNIT; ++j)
-          x[i][j] = (e + j < real) ? convert<SRC, DST>((uint32_t)((const SrcT*)full)[e + j]) : 0u;
-        store_unit<Pol, DST, UNIT>((DstT*)rows + po[i], x[i]);
-      }
-    }
-  } else {
-    for (int e = threadIdx.x; e < here; e += kCopyBlock) {
-      const int64_t p = p_tile + e;
-      const int64_t r = p / vd.L, k = p - r * vd.L;
-      const int64_t o = r * row_stride + k;
-      if (TO_FULL) {
-        if (e < real) ((DstT*)full)[e] = (DstT)convert<SRC, DST>((uint32_t)((const SrcT*)rows)[o]);
-      } else {
-        ((DstT*)rows)[o] = (DstT)((e < real) ? convert<SRC, DST>((uint32_t)((const SrcT*)full)[e]) : 0u);
-      }
-    }
-  }
-}
-
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kCopyBlock) void unshard_flat_kernel(const VarDesc* __restrict__ vars,
-                                                              const FullChunk* __restrict__ fchunks,
-                                                              const void* const* __restrict__ ptrs, void* gathered,
-                                                              int64_t row_stride, int tiles_per_chunk) {
-  reformat_flat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, fchunks, ptrs, gathered, row_stride, tiles_per_chunk);
-}
-
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kCopyBlock) void format_all_flat_kernel(const VarDesc* __restrict__ vars,
-                                                                 const FullChunk* __restrict__ fchunks,
-                                                                 const void* const* __restrict__ ptrs, void* out,
-                                                                 int64_t row_stride, int tiles_per_chunk) {
-  reformat_flat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, fchunks, ptrs, out, row_stride, tiles_per_chunk);
-}
-
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __restrict__ vars,
-                                                        const ChunkDesc* __restrict__ chunks,
-                                                        const void* const* __restrict__ ptrs, void* out, int r0,
-                                                        int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormat, SRC, DST, SU_FORMAT_UNROLL, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
-}
-
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kCopyBlock) void format_all_kernel(const VarDesc* __restrict__ vars,
-                                                            const ChunkDesc* __restrict__ chunks,
-                                                            const void* const* __restrict__ ptrs, void* out,
-                                                            int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk);
-}
-
-template <int SRC, int DST, bool VEC>
-__global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const VarDesc* __restrict__ vars,
-                                                         const ChunkDesc* __restrict__ chunks,
-                                                         const void* const* __restrict__ ptrs, void* gathered,
-                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
 }
 
 // ---- element-wise optimizer arithmetic ------------------------------------------------------------
@@ -1201,129 +829,7 @@ inline unsigned flat_grid(int64_t n4, int unroll) {
 
 }  // namespace
 
-// ---- profiling scope -------------------------------------------------------------------------------
-
-ProfScope::ProfScope(shard_plan_t* plan, int kernel, hipStream_t s) : p(plan), stream(s), on(plan->prof) {
-  if (!on) return;
-  if (!p->prof_free.empty()) {
-    rec = p->prof_free.back();
-    p->prof_free.pop_back();
-  } else if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) {
-    on = false;
-    return;
-  }
-  rec.kernel = kernel;
-  (void)hipEventRecord(rec.start, stream);
-}
-
-ProfScope::~ProfScope() {
-  if (!on) return;
-  (void)hipEventRecord(rec.stop, stream);
-  p->prof_live.push_back(rec);
-}
-
 // ---- launchers -------------------------------------------------------------------------------------
-
-hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const void** dev_table, hipStream_t stream) {
-  ProfScope ps(p, SHARD_K_PTR_TABLE, stream);
-  for (int base = 0; base < p->V; base += kPtrBatch) {
-    PtrBatch b;
-    const int count = (p->V - base < kPtrBatch) ? (p->V - base) : kPtrBatch;
-    for (int i = 0; i < kPtrBatch; ++i) b.p[i] = (i < count) ? host_ptrs[base + i] : nullptr;
-    hipLaunchKernelGGL(ptr_table_kernel, dim3(1), dim3(kPtrBatch), 0, stream, b, dev_table + base, count);
-  }
-  return hipGetLastError();
-}
-
-namespace {
-
-// MODE: 0 = shard_format (one replica), 1 = unshard_format, 2 = shard_format_all
-template <int SRC, int DST, int MODE>
-void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
-                       bool vec, hipStream_t stream) {
-  const int n_chunks = (int)p->chunks.size();
-  constexpr int U = MODE == 0 ? SU_FORMAT_UNROLL : (MODE == 1 ? SU_UNSHARD_UNROLL : SU_FORMAT_ALL_UNROLL);
-  constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
-  const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
-  // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31, and a tile is at least 1024 slots
-  const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kCopyBlock);
-  const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
-  const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  if (MODE != 0 && p->flat_copies) {
-    // flat plan: variable by variable over the padded variables (same tiles, another item table)
-    const FullChunk* fchunks = ws_at<FullChunk>(p, p->ws.full_chunks);
-    const dim3 gf((unsigned)((int64_t)p->full_chunks.size() * tiles_per_chunk));
-    if constexpr (MODE == 2) {
-      if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-      else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-    } else if constexpr (MODE == 1) {
-      if (vec) hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-      else hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-    }
-    return;
-  }
-  if constexpr (MODE == 2) {
-    if (vec)
-      hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
-    else
-      hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
-  } else if constexpr (MODE == 1) {
-    if (vec)
-      hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride, n_chunks,
-                         tiles_per_chunk);
-    else
-      hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
-  } else {
-    if (vec)
-      hipLaunchKernelGGL((format_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
-                         n_chunks, tiles_per_chunk);
-    else
-      hipLaunchKernelGGL((format_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
-                         n_chunks, tiles_per_chunk);
-  }
-}
-
-template <int MODE>
-void reformat_any(shard_plan_t* p, int r0, int replicas, const void* const* tab, int src_dtype, void* packed,
-                  int64_t stride, int dst_dtype, bool vec, hipStream_t stream) {
-  if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
-  else if (src_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
-  else if (dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_BF16, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
-  else
-    reformat_dispatch<SHARD_BF16, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
-}
-}  // namespace
-
-hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src_dtype, void* out, int dst_dtype,
-                         bool vec, hipStream_t stream) {
-  if (p->chunks.empty()) return hipSuccess;
-  ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<0>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, stream);
-  return hipGetLastError();
-}
-
-hipError_t launch_format_all(shard_plan_t* p, const void* const* tab, int src_dtype, void* out, int64_t row_stride,
-                             int dst_dtype, bool vec, hipStream_t stream) {
-  if (p->chunks.empty()) return hipSuccess;
-  ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<2>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, stream);
-  return hipGetLastError();
-}
-
-hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* tab,
-                          int dst_dtype, bool vec, hipStream_t stream) {
-  if (p->chunks.empty()) return hipSuccess;
-  ProfScope ps(p, SHARD_K_UNSHARD, stream);
-  reformat_any<1>(p, 0, p->N, reinterpret_cast<const void* const*>(tab), src_dtype, const_cast<void*>(gathered),
-                     row_stride, dst_dtype, vec, stream);
-  return hipGetLastError();
-}
 
 hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, float* v, void* w16, const AdamK& k,
                        hipStream_t stream) {
