@@ -1,7 +1,8 @@
 /* A plain C client of libshardupdate.so: no PyTorch, no C++.  It shows that the boundary is usable
  * from C with nothing but the HIP runtime for device memory, and checks one pass of the path
  * (plan -> bind -> format -> momentum update with mu = 0 -> unshard) against the closed form
- * w' = w - lr (g + wd w), evaluated here in double.  Exit status 0 = pass.
+ * w' = w - lr (g + wd w), evaluated here in double, then repeats the update with the gradient read in place
+ * from the full tensors and compares the shards bit for bit.  Exit status 0 = pass.
  *
  * Built by __graft_entry__.build() with gcc; run by tests/test_gpu_f_c_client.py on a GPU machine. */
 #include <hip/hip_runtime_api.h>
@@ -90,6 +91,27 @@ int main(void) {
       }
     }
     free(got);
+  }
+  /* the same update with the gradient read in place from the full tensors: the same bits in the shard */
+  {
+    void *w2 = NULL, *m2 = NULL;
+    float *a = (float*)malloc(sizeof(float) * (size_t)S), *b = (float*)malloc(sizeof(float) * (size_t)S);
+    shard_momentum_hp hp;
+    hp.lr = lr; hp.mu = 0.0f; hp.weight_decay = wd;
+    CHECK_HIP(hipMalloc(&w2, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMalloc(&m2, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMemset(m2, 0, sizeof(float) * (size_t)S));
+    CHECK_SU(shard_format(plan, R, (const void* const*)full_w, SHARD_F32, w2, SHARD_F32, NULL));
+    CHECK_SU(shard_update_momentum_full_grads(plan, R, (float*)w2, (const void* const*)full_g, SHARD_F32, (float*)m2, NULL,
+                                              &hp, NULL));
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_HIP(hipMemcpy(a, w, sizeof(float) * (size_t)S, hipMemcpyDeviceToHost));
+    CHECK_HIP(hipMemcpy(b, w2, sizeof(float) * (size_t)S, hipMemcpyDeviceToHost));
+    if (memcmp(a, b, sizeof(float) * (size_t)S) != 0) {
+      fprintf(stderr, "shard_update_momentum_full_grads differs from shard_format + shard_update_momentum\n");
+      ++failures;
+    }
+    free(a); free(b); hipFree(w2); hipFree(m2);
   }
   /* an error path: replica id out of range */
   if (shard_format(plan, N, (const void* const*)full_w, SHARD_F32, w, SHARD_F32, NULL) != SHARD_EINVAL) ++failures;
