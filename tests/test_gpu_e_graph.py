@@ -29,23 +29,32 @@ class State:
         self.w16 = torch.zeros(S, dtype=torch.bfloat16, device=DEV)
         self.other = torch.full((plan.V, 2), 0.25, dtype=torch.float32, device=DEV)
         self.r = r
+        self.fused = False
 
     def step(self, plan):
         r = self.r
-        su.shard_format(plan, r, self.full_g, self.g)
-        su.shard_update_lamb(plan, r, self.gathered[r], self.g, self.m, self.v, LAMB, 5, other_replicas_sumsq=self.other,
-                             w_bf16_out=self.w16)
+        if self.fused:                          # the gradient read in place from the full tensors
+            su.shard_update_lamb_full_grads(plan, r, self.gathered[r], self.full_g, self.m, self.v, LAMB, 5,
+                                            other_replicas_sumsq=self.other, w_bf16_out=self.w16)
+        else:
+            su.shard_format(plan, r, self.full_g, self.g)
+            su.shard_update_lamb(plan, r, self.gathered[r], self.g, self.m, self.v, LAMB, 5,
+                                 other_replicas_sumsq=self.other, w_bf16_out=self.w16)
         su.unshard_format(plan, self.gathered, self.full_w)
 
     def snapshot(self):
         return [to_host(t) for t in (self.gathered, self.m, self.v, self.w16, torch.cat(self.full_w))]
 
 
-def test_step_captured_in_a_graph_replays_like_eager():
+@pytest.mark.parametrize("fused", [False, True])
+def test_step_captured_in_a_graph_replays_like_eager(fused):
+    """fused: the captured step reads the gradient from the full tensors; the eager one it is compared with
+    formats it first (the two routes give the same bits)."""
     cfg = [c for c in CONFIGS if c.name == "tiny"][0]
     N, r = 4, 1
     plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8))
     eager, graphed = State(plan, cfg, r, 91), State(plan, cfg, r, 91)
+    graphed.fused = fused
     side = torch.cuda.Stream()
     torch.cuda.synchronize()
     with torch.cuda.stream(side):
