@@ -226,6 +226,19 @@ def headline(args, torch, su, cfgs):
     ms16, _ = _time_region(torch, one_step_bf16, args.steps)
     bf16_gather = {"ms_per_step": round(ms16, 5), "params_per_s": wb.real / (ms16 * 1e-3),
                    "what": "float32 LAMB update that also writes bf16(w'), bfloat16 gathered buffer and full tensors"}
+
+    # both at once: gradient read in place from the full tensors, weights gathered in bfloat16
+    def one_step_fused_bf16():
+        state["t"] += 1
+        su.shard_update_lamb_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v, hp, state["t"],
+                                        other_replicas_sumsq=wb.other, w_bf16_out=g16[r])
+        su.unshard_format(plan, g16, full16)
+
+    for _ in range(3):
+        one_step_fused_bf16()
+    msfb, _ = _time_region(torch, one_step_fused_bf16, args.steps)
+    fused_bf16 = {"ms_per_step": round(msfb, 5), "params_per_s": wb.real / (msfb * 1e-3),
+                  "what": "shard_update_lamb_full_grads that also writes bf16(w') + bfloat16 unshard_format"}
     del g16, flat16, full16
 
     # The same float32 step with the formatting of the gradient fused into the update (Section 5.1): phase 1
@@ -261,6 +274,7 @@ def headline(args, torch, su, cfgs):
         "update_only": update_only,
         "bf16_gather": bf16_gather,
         "fused_format": fused_format,
+        "fused_format_bf16_gather": fused_bf16,
         "wall_ms_per_step": round(wall_ms, 5),
     }
     wb.free()
