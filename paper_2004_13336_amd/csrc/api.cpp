@@ -133,6 +133,143 @@ int fold_lars(const shard_lars_hp* hp, LarsK* k) {
   return SHARD_OK;
 }
 
+// The gradient argument of an update: a packed shard, or the list of full tensors the shard would have
+// been formatted from (the *_full_grads entry points).
+struct GradArg {
+  const float* shard;
+  const void* const* full;
+  int dtype;
+  bool from_full;
+};
+inline GradArg shard_grad(const float* g) { return GradArg{g, nullptr, SHARD_F32, false}; }
+inline GradArg full_grads(const void* const* ptrs, int dtype) { return GradArg{nullptr, ptrs, dtype, true}; }
+
+int check_grad(const shard_plan_t* p, const GradArg& g) {
+  if (!g.from_full) return p->S > 0 ? check_shard_ptr(g.shard) : SHARD_OK;
+  if (!dtype_ok(g.dtype)) return SHARD_EINVAL;
+  return check_full_ptrs(p, g.full);
+}
+
+// g_source of the launchers (0 shard, 1 full float32, 2 full bfloat16) and, for full tensors, the device
+// table of their pointers.
+int resolve_grad(shard_plan_t* p, const GradArg& g, hipStream_t s, int* source, const void*** table) {
+  *source = 0;
+  *table = nullptr;
+  if (!g.from_full) return SHARD_OK;
+  *source = g.dtype == SHARD_F32 ? 1 : 2;
+  return resident_ptr_table(p, g.full, s, table);
+}
+
+int lamb_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* m, float* v,
+                      const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
+    return rc;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
+  return hip_status(e);
+}
+
+int lamb_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, float* v, void* w_bf16_out,
+             const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq, float* local_sumsq_out,
+             shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (hp == nullptr) return SHARD_EINVAL;
+  AdamK k;
+  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
+int lars_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* local_sumsq_out,
+                      shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK)) return rc;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
+  return hip_status(e);
+}
+
+int lars_apply_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out,
+                   const shard_lars_hp* hp, const float* global_sumsq, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
+      (rc = check_grad(p, g)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK)
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  return hip_status(launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, global_sumsq, s));
+}
+
+int lars_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out, const shard_lars_hp* hp,
+             const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream) {
+  int rc = check_plan_r(p, r, true);
+  if (rc != SHARD_OK) return rc;
+  LarsK k;
+  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
+  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
+  if (p->V == 0) return SHARD_OK;
+  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
+    return SHARD_EALIGN;
+  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
+                   (rc = check_shard_ptr(m)) != SHARD_OK))
+    return rc;
+  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
+  hipStream_t s = as_stream(stream);
+  int source;
+  const void** table;
+  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
+  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
+  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  if (e == hipSuccess) e = launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, sums, s);
+  return hip_status(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -346,147 +483,6 @@ int shard_update_momentum(shard_plan_t* p, int r, float* w, const float* g, floa
   MomentumK k{hp->mu, hp->lr, hp->weight_decay};
   return hip_status(launch_momentum(p, w, g, m, w_bf16_out, k, as_stream(stream)));
 }
-
-namespace {
-
-// The gradient argument of an update: a packed shard, or the list of full tensors the shard would have
-// been formatted from (the *_full_grads entry points).
-struct GradArg {
-  const float* shard;
-  const void* const* full;
-  int dtype;
-  bool from_full;
-};
-inline GradArg shard_grad(const float* g) { return GradArg{g, nullptr, SHARD_F32, false}; }
-inline GradArg full_grads(const void* const* ptrs, int dtype) { return GradArg{nullptr, ptrs, dtype, true}; }
-
-int check_grad(const shard_plan_t* p, const GradArg& g) {
-  if (!g.from_full) return p->S > 0 ? check_shard_ptr(g.shard) : SHARD_OK;
-  if (!dtype_ok(g.dtype)) return SHARD_EINVAL;
-  return check_full_ptrs(p, g.full);
-}
-
-// g_source of the launchers (0 shard, 1 full float32, 2 full bfloat16) and, for full tensors, the device
-// table of their pointers.
-int resolve_grad(shard_plan_t* p, const GradArg& g, hipStream_t s, int* source, const void*** table) {
-  *source = 0;
-  *table = nullptr;
-  if (!g.from_full) return SHARD_OK;
-  *source = g.dtype == SHARD_F32 ? 1 : 2;
-  return resident_ptr_table(p, g.full, s, table);
-}
-
-int lamb_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* m, float* v,
-                      const shard_lamb_hp* hp, int64_t step, float* local_sumsq_out, shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  if (hp == nullptr) return SHARD_EINVAL;
-  AdamK k;
-  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
-  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
-                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
-    return rc;
-  hipStream_t s = as_stream(stream);
-  int source;
-  const void** table;
-  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
-  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
-  return hip_status(e);
-}
-
-int lamb_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, float* v, void* w_bf16_out,
-             const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq, float* local_sumsq_out,
-             shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  if (hp == nullptr) return SHARD_EINVAL;
-  AdamK k;
-  if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
-  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
-    return SHARD_EALIGN;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
-                   (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK))
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  hipStream_t s = as_stream(stream);
-  int source;
-  const void** table;
-  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
-  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
-  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
-  if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
-  return hip_status(e);
-}
-
-int lars_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, float* local_sumsq_out,
-                      shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((rc = check_shard_ptr(local_sumsq_out)) != SHARD_OK) return rc;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK)) return rc;
-  hipStream_t s = as_stream(stream);
-  int source;
-  const void** table;
-  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
-  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, nullptr, nullptr, local_sumsq_out, s);
-  return hip_status(e);
-}
-
-int lars_apply_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out,
-                   const shard_lars_hp* hp, const float* global_sumsq, shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  LarsK k;
-  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
-  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
-  if (p->S == 0) return SHARD_OK;
-  if ((rc = check_shard_ptr(global_sumsq)) != SHARD_OK || (rc = check_shard_ptr(w)) != SHARD_OK ||
-      (rc = check_grad(p, g)) != SHARD_OK || (rc = check_shard_ptr(m)) != SHARD_OK)
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  hipStream_t s = as_stream(stream);
-  int source;
-  const void** table;
-  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
-  return hip_status(launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, global_sumsq, s));
-}
-
-int lars_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, void* w_bf16_out, const shard_lars_hp* hp,
-             const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream) {
-  int rc = check_plan_r(p, r, true);
-  if (rc != SHARD_OK) return rc;
-  LarsK k;
-  if ((rc = fold_lars(hp, &k)) != SHARD_OK) return rc;
-  if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
-  if (p->V == 0) return SHARD_OK;
-  if ((other_replicas_sumsq && !aligned16(other_replicas_sumsq)) || (local_sumsq_out && !aligned16(local_sumsq_out)))
-    return SHARD_EALIGN;
-  if (p->S > 0 && ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_grad(p, g)) != SHARD_OK ||
-                   (rc = check_shard_ptr(m)) != SHARD_OK))
-    return rc;
-  if (w_bf16_out && !aligned16(w_bf16_out)) return SHARD_EALIGN;
-  hipStream_t s = as_stream(stream);
-  int source;
-  const void** table;
-  if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
-  float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
-  hipError_t e = launch_lars_p1(p, r, w, g.shard, source, table, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
-  if (e == hipSuccess) e = launch_lars_p2(p, r, w, g.shard, source, table, m, w_bf16_out, k, sums, s);
-  return hip_status(e);
-}
-
-}  // namespace
 
 int shard_update_adam_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype, float* m,
                                  float* v, void* w_bf16_out, const shard_adam_hp* hp, int64_t step,
