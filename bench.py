@@ -57,6 +57,8 @@ def parse_args():
                          "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
                          "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
+    ap.add_argument("--cold", action="store_true",
+                    help="with --stage: flush the memory-side cache (a 1 GiB copy) before every launch of the stage")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run one plain device copy of 1 GiB (2^28 float32), so that a rocprofv3 --pmc run "
                          "has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -497,10 +499,16 @@ def one_stage(args, torch, su, cfgs):
     if name not in stages:
         raise SystemExit("unknown --stage %s" % name)
     fn, kernels, nbytes = stages[name]
+    # --cold: a 1 GiB device copy between launches of the stage, so that nothing of the previous launch is
+    # left in the 256 MB memory-side cache (between two real steps a forward and a backward pass run); the
+    # event pairs time the library's kernels only
+    spill = torch.empty((2, 1 << 28), dtype=torch.float32, device="cuda") if args.cold else None
     for t in range(1, 1 + max(args.warmup, 1)):
         fn(t)
     su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
     for t in range(100, 100 + args.steps):
+        if spill is not None:
+            spill[1].copy_(spill[0])
         fn(t)
     torch.cuda.synchronize()
     per = {}
@@ -510,7 +518,7 @@ def one_stage(args, torch, su, cfgs):
     us = sum(per.values())
     print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
                       "total_us": round(us, 2), "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
-                      "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}))
+                      "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold)}))
     wb.free()
 
 
