@@ -55,7 +55,8 @@ def parse_args():
     ap.add_argument("--stage", default=None,
                     help="instead of the headline step, run ONE stage of --config at --replicas for --steps launches "
                          "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
-                         "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads) "
+                         "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads | "
+                         "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--cold", action="store_true",
                     help="with --stage: flush the memory-side cache (a 1 GiB copy) before every launch of the stage")
@@ -458,7 +459,8 @@ def one_stage(args, torch, su, cfgs):
         row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
         print(json.dumps(row))
         return
-    needs_full = name in ("shard_format", "unshard_format", "shard_format_all") or name.endswith("_full_grads")
+    needs_full = (name in ("shard_format", "unshard_format", "shard_format_all") or name.endswith("_full_grads")
+                  or name.endswith("_step"))
     wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full)
     plan, S = wb.plan, wb.S
     hp = wb.hp()
@@ -491,6 +493,19 @@ def one_stage(args, torch, su, cfgs):
         stages["lars_full_grads"] = (lambda t: su.shard_update_lars_full_grads(plan, r, wb.w, wb.full_g, wb.m, lars_hp,
                                                                                 other_replicas_sumsq=wb.other),
                                      ["lars_p1", "norm_reduce", "lars_p2"], 28 * S)
+        # whole steps (format g, update, unshard w) of each optimizer: what a cache policy costs or gains
+        # the kernel AFTER it only shows in such a sum
+        step_bytes = 8 * S + 4 * N * S + 4 * cfg.total
+
+        def _step(update):
+            def run(t):
+                su.shard_format(plan, r, wb.full_g, wb.g)
+                update(t)
+                su.unshard_format(plan, wb.gathered, wb.full_w)
+            return run
+        for opt in ("adam", "momentum", "lars", "lamb"):
+            fn0, ks, nb = stages[opt]
+            stages[opt + "_step"] = (_step(fn0), ["format"] + ks + ["unshard"], nb + step_bytes)
         stages["shard_format"] = (lambda t: su.shard_format(plan, r, wb.full_g, wb.g), ["format"], 8 * S)
         stages["unshard_format"] = (lambda t: su.unshard_format(plan, wb.gathered, wb.full_w), ["unshard"],
                                     4 * N * S + 4 * cfg.total)
