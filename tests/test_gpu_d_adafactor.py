@@ -21,6 +21,32 @@ CASES = [
 ]
 
 
+def _random_case(seed):
+    """Seeded random shape list that reaches every tile geometry of the row-plan kernels: pieces of a few
+    rows and of hundreds, narrow and very wide matrices, column counts off the 4-element grid, vectors,
+    empty variables."""
+    rng = np.random.default_rng(4200 + seed)
+    shapes = []
+    for _ in range(int(rng.integers(2, 7))):
+        kind = int(rng.integers(0, 6))
+        if kind == 0:
+            shapes.append((int(rng.integers(0, 3)), int(rng.integers(0, 5))))
+        elif kind == 1:
+            shapes.append((int(rng.integers(1, 3000)), 1))                              # vector
+        elif kind == 2:
+            shapes.append((int(rng.integers(1, 40)), int(rng.integers(1, 6000))))       # few rows, wide
+        elif kind == 3:
+            shapes.append((int(rng.integers(200, 1500)), int(rng.integers(1, 70))))     # many rows, narrow
+        elif kind == 4:
+            shapes.append((int(rng.integers(30, 300)), 4 * int(rng.integers(1, 300))))  # aligned columns
+        else:
+            shapes.append((int(rng.integers(1, 120)), int(rng.integers(250, 1100))))
+    return shapes, int(rng.choice([1, 2, 3, 5, 8])), int(rng.choice([1, 4, 8]))
+
+
+CASES += [_random_case(s) for s in range(6)]
+
+
 def _split(layout_off, lengths, flat):
     return [flat[o:o + n] for o, n in zip(layout_off, lengths)]
 
