@@ -56,7 +56,7 @@ def parse_args():
                     help="instead of the headline step, run ONE stage of --config at --replicas for --steps launches "
                          "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
                          "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads | "
-                         "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w) "
+                         "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w | unshard_format_bf16) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--cold", action="store_true",
                     help="with --stage: flush the memory-side cache (a 1 GiB copy) before every launch of the stage")
@@ -459,7 +459,8 @@ def one_stage(args, torch, su, cfgs):
         row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
         print(json.dumps(row))
         return
-    needs_full = (name in ("shard_format", "unshard_format", "shard_format_all") or name.endswith("_full_grads")
+    needs_full = (name in ("shard_format", "unshard_format", "shard_format_all", "unshard_format_bf16")
+                  or name.endswith("_full_grads")
                   or name.endswith("_step"))
     wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full)
     plan, S = wb.plan, wb.S
@@ -511,6 +512,14 @@ def one_stage(args, torch, su, cfgs):
                                     4 * N * S + 4 * cfg.total)
         stages["shard_format_all"] = (lambda t: su.shard_format_all(plan, wb.full_g, wb.gathered), ["format"],
                                       4 * N * S + 4 * cfg.total)
+        if name == "unshard_format_bf16":                       # the all-gather in bfloat16 (Section 4.2)
+            g16 = su.gathered_empty(plan, dtype=torch.bfloat16).normal_(0.0, cfg.weight_std)
+            flat16 = torch.empty(cfg.total, dtype=torch.bfloat16, device="cuda")
+            full16, pos = [], 0
+            for n in cfg.numel:
+                full16.append(flat16[pos:pos + n]); pos += n
+            full16 = su.FullTensors(plan, full16)
+            stages[name] = (lambda t: su.unshard_format(plan, g16, full16), ["unshard"], 2 * N * S + 2 * cfg.total)
     if name not in stages:
         raise SystemExit("unknown --stage %s" % name)
     fn, kernels, nbytes = stages[name]
