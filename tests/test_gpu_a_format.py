@@ -95,16 +95,32 @@ def test_format_and_unshard_match_oracle(numel, N, align, src, dst):
     plan.free()
 
 
-def test_unshard_converting_f32_shards_to_bf16_tensors():
-    numel, N = [1000, 37, 4099], 3
-    oplan = oracle.make_plan(numel, N, 8)
-    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
-    flats = [np.random.default_rng(i).standard_normal(n).astype(np.float32) for i, n in enumerate(numel)]
-    g32 = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
-    outs = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in numel]
-    su.unshard_format(plan, to_dev(g32), outs)
-    for o, w in zip(outs, oracle.unshard_format(oplan, g32, dst="bf16")):
+@pytest.mark.parametrize("numel,N,align", [([1000, 37, 4099], 3, 8), ([100, 33, 7], 4, 1),
+                                          ([1024, 300000, 30522, 2, 70001], 2048, 8),      # variable-by-variable walk
+                                          ([5000, 333, 40000], 1000, 1), ([9000, 16], 257, 16)])
+@pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("bf16", "f32")])
+def test_unshard_converting_between_element_types(numel, N, align, src, dst):
+    """float32 shards restored as bfloat16 tensors (rounded to nearest even) and bfloat16 shards as float32
+    tensors, on plans of either walk; bit patterns include NaN payloads, infinities and -0.0."""
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+    flats = _bit_tensors(29, numel, src)
+    gathered = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
+    sdt, ddt = (torch.float32, torch.bfloat16) if src == "f32" else (torch.bfloat16, torch.float32)
+    esz = 2 if dst == "bf16" else 4
+    outs, bufs = [], []
+    for n in numel:
+        b, p, bd = _guarded(n * esz)
+        bufs.append((b, bd, n * esz))
+        outs.append(p.view(ddt))
+    rows = torch.empty((N, max(oplan.S, 1)), dtype=sdt, device=DEV)[:, :oplan.S]
+    rows.copy_(to_dev(gathered))
+    su.unshard_format(plan, rows, outs)
+    torch.cuda.synchronize()
+    for (b, bd, nb), o, w in zip(bufs, outs, oracle.unshard_format(oplan, gathered, dst=dst)):
+        assert _bands_intact(b, bd, nb)
         assert same_bits(to_host(o), w)
+    plan.free()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -264,7 +280,7 @@ def test_formatting_stress_1p5b_128_replicas_bf16():
 @pytest.mark.parametrize("numel,N,align", [([1000, 37, 0, 8, 4099, 1], 3, 8), ([64, 64, 9000], 32, 8), ([100, 33, 7], 4, 1),
                                           ([2, 1024, 30522, 513], 8, 8), ([1024, 300000, 30522, 2, 70001], 2048, 8),
                                           ([5000, 333, 40000], 1000, 1)])
-@pytest.mark.parametrize("src,dst", [("f32", "f32"), ("f32", "bf16"), ("bf16", "bf16")])
+@pytest.mark.parametrize("src,dst", [("f32", "f32"), ("f32", "bf16"), ("bf16", "bf16"), ("bf16", "f32")])
 def test_format_all_replicas_in_one_pass(numel, N, align, src, dst):
     """Row r of the output is shard_r, for all r at once (the reduce-scatter input layout)."""
     oplan = oracle.make_plan(numel, N, align)
