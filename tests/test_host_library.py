@@ -275,6 +275,37 @@ def test_full_gradient_updates_check_arguments_without_touching_the_gpu():
     plan.free()
 
 
+def test_oracle_and_product_do_not_know_each_other():
+    """The oracle is test infrastructure: the package, its C++ sources and the input generators never name it,
+    it never names them or the GPU stack, and the bench reaches it only from its CPU-baseline legs."""
+    import ast
+    import glob
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imported(path):
+        names = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                names |= {a.name.split(".")[0] for a in node.names}
+            elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+                names.add(node.module.split(".")[0])
+        return names
+
+    for path in glob.glob(os.path.join(root, "paper_2004_13336_amd", "*.py")) + glob.glob(os.path.join(root, "workloads", "*.py")):
+        assert "oracle" not in imported(path), path
+    for path in glob.glob(os.path.join(root, "paper_2004_13336_amd", "csrc", "*")) + [HEADER]:
+        assert "oracle" not in open(path).read().lower(), path
+    for path in glob.glob(os.path.join(root, "oracle", "*.py")):
+        assert not (imported(path) & {"paper_2004_13336_amd", "torch", "ctypes", "workloads"}), path
+    # bench.py: `import oracle` only inside the functions of the CPU-baseline legs
+    tree = ast.parse(open(os.path.join(root, "bench.py")).read())
+    for node in tree.body:
+        if isinstance(node, (ast.Import, ast.ImportFrom)):
+            assert "oracle" not in ast.dump(node)
+        if isinstance(node, ast.FunctionDef) and "oracle" in {n.names[0].name for n in ast.walk(node) if isinstance(n, ast.Import)}:
+            assert node.name.startswith("cpu_baseline") or node.name.startswith("_cpu_"), node.name
+
+
 def test_header_is_valid_c99_and_the_c_client_builds():
     import subprocess
     proc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
