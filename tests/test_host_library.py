@@ -275,6 +275,24 @@ def test_full_gradient_updates_check_arguments_without_touching_the_gpu():
     plan.free()
 
 
+def test_without_the_library_every_call_fails_loudly():
+    """There is no fallback: with no loadable libshardupdate.so the first call raises (a fresh interpreter,
+    pointed at a file that does not exist)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import paper_2004_13336_amd as su\n"
+            "try:\n"
+            "    su.shard_plan([8, 8], 2)\n"
+            "except OSError as e:\n"
+            "    print('raised', type(e).__name__)\n"
+            "else:\n"
+            "    print('no error')\n")
+    env = dict(os.environ, SHARDUPDATE_LIB=os.path.join(root, "no_such_dir", "libshardupdate.so"), PYTHONPATH=root)
+    proc = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, cwd=root)
+    assert proc.stdout.strip() == "raised OSError", proc.stdout + proc.stderr
+
+
 def test_oracle_and_product_do_not_know_each_other():
     """The oracle is test infrastructure: the package, its C++ sources and the input generators never name it,
     it never names them or the GPU stack, and the bench reaches it only from its CPU-baseline legs."""
