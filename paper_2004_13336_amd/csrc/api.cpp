@@ -371,6 +371,14 @@ int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard
                                                 p->full_chunks.size() * sizeof(FullChunk), hipMemcpyHostToDevice,
                                                 s) != hipSuccess)
     return SHARD_EHIP;
+  if (!p->major_chunks.empty() && hipMemcpyAsync(ws.base + ws.major_chunks, p->major_chunks.data(),
+                                                 p->major_chunks.size() * sizeof(ChunkDesc), hipMemcpyHostToDevice,
+                                                 s) != hipSuccess)
+    return SHARD_EHIP;
+  if (!p->small_full_chunks.empty() && hipMemcpyAsync(ws.base + ws.small_full_chunks, p->small_full_chunks.data(),
+                                                      p->small_full_chunks.size() * sizeof(FullChunk),
+                                                      hipMemcpyHostToDevice, s) != hipSuccess)
+    return SHARD_EHIP;
   if (p->row_plan) {
     if (!p->rc_vars.empty() && hipMemcpyAsync(ws.base + ws.rc_vars, p->rc_vars.data(), p->rc_vars.size() * sizeof(RowColVar),
                                               hipMemcpyHostToDevice, s) != hipSuccess)

@@ -185,13 +185,17 @@ __device__ __forceinline__ void copy_tile(const ChunkView& cv, int t, const type
 template <typename Pol, int SRC, int DST, int U, bool VEC, bool UNSHARD>
 __device__ __forceinline__ void reformat_body(const VarDesc* __restrict__ vars, const ChunkDesc* __restrict__ chunks,
                                               const void* const* __restrict__ ptrs, void* packed, int r0,
-                                              int64_t row_stride, int n_chunks, int tiles_per_chunk) {
+                                              int64_t row_stride, int n_chunks, int tiles_per_chunk,
+                                              int wg_per_replica) {
   typedef typename ElemOf<SRC>::type SrcT;
   typedef typename ElemOf<DST>::type DstT;
-  const int item = blockIdx.x / tiles_per_chunk;
-  const int tile = blockIdx.x - item * tiles_per_chunk;
-  const int replica = item / n_chunks;
-  const ChunkView cv = chunk_view(vars, chunks, item - replica * n_chunks, r0 + replica);
+  // wg_per_replica = n_chunks * tiles_per_chunk, plus one idle workgroup where that is even (see odd_count)
+  const int replica = blockIdx.x / wg_per_replica;
+  const int j = blockIdx.x - replica * wg_per_replica;
+  const int item = j / tiles_per_chunk;
+  if (item >= n_chunks) return;
+  const int tile = j - item * tiles_per_chunk;
+  const ChunkView cv = chunk_view(vars, chunks, item, r0 + replica);
   // skip the pointer look-up for tiles with nothing to do (beyond a short chunk, or all padding)
   constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   if (tile * TILE >= (UNSHARD ? cv.valid : cv.len)) return;
@@ -340,24 +344,27 @@ template <int SRC, int DST, bool VEC>
 __global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __restrict__ vars,
                                                         const ChunkDesc* __restrict__ chunks,
                                                         const void* const* __restrict__ ptrs, void* out, int r0,
-                                                        int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormat, SRC, DST, SU_FORMAT_UNROLL, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk);
+                                                        int64_t row_stride, int n_chunks, int tiles_per_chunk,
+                                                        int wg_per_replica) {
+  reformat_body<PolFormat, SRC, DST, SU_FORMAT_UNROLL, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 template <int SRC, int DST, bool VEC>
 __global__ __launch_bounds__(kCopyBlock) void format_all_kernel(const VarDesc* __restrict__ vars,
                                                             const ChunkDesc* __restrict__ chunks,
                                                             const void* const* __restrict__ ptrs, void* out,
-                                                            int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk);
+                                                            int64_t row_stride, int n_chunks, int tiles_per_chunk,
+                                                            int wg_per_replica) {
+  reformat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 template <int SRC, int DST, bool VEC>
 __global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const void* const* __restrict__ ptrs, void* gathered,
-                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk) {
-  reformat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk);
+                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk,
+                                                         int wg_per_replica) {
+  reformat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 }  // namespace
@@ -377,6 +384,19 @@ hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const
 
 namespace {
 
+// Workgroups are dealt out to the 8 XCDs in turn, and the light ones (the last, partly filled tiles of a
+// variable, the empty second tile of a short chunk) sit at the same places of every replica's sequence.  With an
+// even number of workgroups per replica the same XCDs would get them replica after replica and run out of work
+// while the others are still busy (measured: 5 % on the 1.5 G-parameter list at 128 replicas); an odd count moves
+// the sequence on by one XCD per replica.  SU_WG_PAD (0: off) exists for measurements.
+#ifndef SU_WG_PAD
+#define SU_WG_PAD 1
+#endif
+inline int odd_count(int64_t wgs, int replicas) {
+  if (SU_WG_PAD && replicas > 1 && (wgs & 1) == 0 && (wgs + 1) * replicas <= 0x7FFFFFFF) return (int)wgs + 1;
+  return (int)wgs;
+}
+
 // MODE: 0 = shard_format (one replica), 1 = unshard_format, 2 = shard_format_all
 template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
@@ -386,7 +406,8 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
   // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31, and a tile is at least 1024 slots
-  const dim3 g((unsigned)((int64_t)n_chunks * replicas * tiles_per_chunk)), b(kCopyBlock);
+  const int per = odd_count((int64_t)n_chunks * tiles_per_chunk, replicas);
+  const dim3 g((unsigned)((int64_t)per * replicas)), b(kCopyBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   if (MODE != 0 && p->flat_copies) {
@@ -394,8 +415,22 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
     const FullChunk* fchunks = ws_at<FullChunk>(p, p->ws.full_chunks);
     const dim3 gf((unsigned)((int64_t)p->full_chunks.size() * tiles_per_chunk));
     if constexpr (MODE == 2) {
-      if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-      else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+      // Formatting writes the gathered rows: variables with whole-chunk pieces go replica by replica (contiguous
+      // writes), the small ones variable by variable (full tiles); two launches over two sub-tables.
+      const int n_major = (int)p->major_chunks.size();
+      const ChunkDesc* major = ws_at<ChunkDesc>(p, p->ws.major_chunks);
+      const int per_major = odd_count((int64_t)n_major * tiles_per_chunk, replicas);
+      const dim3 gm((unsigned)((int64_t)per_major * replicas));
+      if (n_major > 0) {
+        if (vec) hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
+        else hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
+      }
+      const FullChunk* small = ws_at<FullChunk>(p, p->ws.small_full_chunks);
+      const dim3 gs((unsigned)((int64_t)p->small_full_chunks.size() * tiles_per_chunk));
+      if (!p->small_full_chunks.empty()) {
+        if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
+        else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
+      }
     } else if constexpr (MODE == 1) {
       if (vec) hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
       else hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
@@ -405,24 +440,24 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   if constexpr (MODE == 2) {
     if (vec)
       hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
+                         n_chunks, tiles_per_chunk, per);
     else
       hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
+                         n_chunks, tiles_per_chunk, per);
   } else if constexpr (MODE == 1) {
     if (vec)
       hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride, n_chunks,
-                         tiles_per_chunk);
+                         tiles_per_chunk, per);
     else
       hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
-                         n_chunks, tiles_per_chunk);
+                         n_chunks, tiles_per_chunk, per);
   } else {
     if (vec)
       hipLaunchKernelGGL((format_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
-                         n_chunks, tiles_per_chunk);
+                         n_chunks, tiles_per_chunk, per);
     else
       hipLaunchKernelGGL((format_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
-                         n_chunks, tiles_per_chunk);
+                         n_chunks, tiles_per_chunk, per);
   }
 }
 

@@ -128,6 +128,7 @@ struct Workspace {
   // byte offsets inside base
   size_t vars = 0, chunks = 0, ptrs = 0, chunk_sums = 0, var_sums = 0;
   size_t full_chunks = 0;                                             // flat plans only
+  size_t major_chunks = 0, small_full_chunks = 0;                     // flat plans with flat_copies only
   size_t rc_vars = 0, rc_items = 0, rc_colpart = 0, rc_rowpart = 0;   // row plans only
   size_t rc_col_items = 0, rc_row_items = 0, rc_colitem_part = 0;
   // Adafactor (row plans only): per-item partial sums, per-variable scalars, the factors of 1/sqrt(Vhat),
@@ -152,6 +153,10 @@ struct shard_plan_s {
   std::vector<su::ChunkDesc> chunks;
   std::vector<su::FullChunk> full_chunks;  // flat plans only
   bool flat_copies = false;                // whole-model copies walk full_chunks instead of (replica, chunk)
+  // With flat_copies, shard_format_all splits the variables: those whose pieces hold at least one whole chunk go
+  // replica by replica (their chunks, copied here), the others variable by variable (their items of full_chunks).
+  std::vector<su::ChunkDesc> major_chunks;
+  std::vector<su::FullChunk> small_full_chunks;
   bool row_plan = false;
   std::vector<su::RowColVar> rc_vars;      // row plans only
   std::vector<su::RowColItem> rc_items;

@@ -50,6 +50,7 @@ CASES = [
     ([1024, 300000, 30522, 2, 70001], 2048, 8),   # thousands of replicas: pieces of 8 to 152 slots, most of them padding
     ([5000, 333, 40000], 1000, 1),                # the same without alignment (5-, 1- and 40-slot pieces)
     ([9000, 16], 257, 16),
+    ([3000000, 100, 64, 7, 50000, 1000000], 64, 8),   # variable-by-variable walk with pieces of many chunks among tiny ones
 ]
 
 
@@ -279,7 +280,9 @@ def test_formatting_stress_1p5b_128_replicas_bf16():
 
 @pytest.mark.parametrize("numel,N,align", [([1000, 37, 0, 8, 4099, 1], 3, 8), ([64, 64, 9000], 32, 8), ([100, 33, 7], 4, 1),
                                           ([2, 1024, 30522, 513], 8, 8), ([1024, 300000, 30522, 2, 70001], 2048, 8),
-                                          ([5000, 333, 40000], 1000, 1)])
+                                          ([5000, 333, 40000], 1000, 1),
+                                          ([3000000, 100, 64, 7, 50000, 1000000], 64, 8),
+                                          ([5000, 2000001, 3, 700000], 100, 4)])
 @pytest.mark.parametrize("src,dst", [("f32", "f32"), ("f32", "bf16"), ("bf16", "bf16"), ("bf16", "f32")])
 def test_format_all_replicas_in_one_pass(numel, N, align, src, dst):
     """Row r of the output is shard_r, for all r at once (the reduce-scatter input layout)."""
