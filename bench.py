@@ -206,6 +206,26 @@ def headline(args, torch, su, cfgs):
         "GBps": round(40 * S / (lamb_us * 1e-6) / 1e9, 1),
         "frac_of_hbm_peak": round(40 * S / (lamb_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
     }
+    # the practical ceiling, measured in this same run on this same GPU: a plain copy (no table, no padding)
+    # that moves as many bytes as unshard_format does
+    half = (4 * N * S + 4 * cfg.total) // 2 // 16 * 16
+    ca = torch.empty(half, dtype=torch.uint8, device="cuda"); cb = torch.empty(half, dtype=torch.uint8, device="cuda")
+    ca.zero_()
+    for _ in range(3):
+        su.shard_profile_plain_copy(plan, cb, ca)
+    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+    for _ in range(20):
+        su.shard_profile_plain_copy(plan, cb, ca)
+    torch.cuda.synchronize()
+    n_copy, ms_copy = su.shard_profile_read(plan, "plain_copy")
+    su.shard_profile_enable(plan, False)
+    copy_us = 1e3 * ms_copy / n_copy
+    plain_copy = {"bytes": 2 * half, "avg_us": round(copy_us, 2), "GBps": round(2 * half / (copy_us * 1e-6) / 1e9, 1),
+                  "frac_of_hbm_peak": round(2 * half / (copy_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                  "what": "plain device copy of the bytes unshard_format moves (one 128-bit access per thread, "
+                          "non-temporal): the practical ceiling on this GPU, same run"}
+    del ca, cb
+
     # The same step as the paper runs it (Section 4.2, all-gather in bfloat16): the float32 update also
     # emits bf16(w') into this replica's row of a bfloat16 gathered buffer, and unshard_format restores
     # bfloat16 tensors for the forward pass.  Reported beside the float32 headline, never as `value`.
@@ -275,6 +295,7 @@ def headline(args, torch, su, cfgs):
         "roofline": roof,
         "kernels": rooflines,
         "update_only": update_only,
+        "plain_copy": plain_copy,
         "bf16_gather": bf16_gather,
         "fused_format": fused_format,
         "fused_format_bf16_gather": fused_bf16,

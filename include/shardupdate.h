@@ -80,7 +80,8 @@ enum {
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
   SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9, SHARD_K_ROWCOL_P1 = 10, SHARD_K_ROWCOL_P2 = 11,
   SHARD_K_ADAFACTOR_STATE = 12, SHARD_K_ADAFACTOR_USQ = 13, SHARD_K_ADAFACTOR_APPLY = 14,
-  SHARD_K_COUNT = 15
+  SHARD_K_PLAIN_COPY = 15,
+  SHARD_K_COUNT = 16
 };
 
 const char* shard_strerror(int status);
@@ -407,6 +408,14 @@ int shard_plan_peak_bytes(const shard_plan_t* plan, int weight_bytes, int aux_by
 int shard_profile_enable(shard_plan_t* plan, int on);
 int shard_profile_read(shard_plan_t* plan, int kernel_id, int64_t* launches, double* total_ms);
 int shard_profile_reset(shard_plan_t* plan);
+
+/* A measurement aid, not part of the path: the plainest device copy there is (one 128-bit access per thread,
+ * non-temporal, no table, no padding), launched and timed through the same event mechanism under the kernel
+ * id SHARD_K_PLAIN_COPY.  What it reaches on a GPU is the practical ceiling the formatting kernels, which move
+ * the same bytes through a chunk table, can be compared with in the same run.
+ * dst, src: device pointers, 16-byte aligned, not overlapping; bytes: a positive multiple of 16.
+ * Errors: SHARD_EINVAL, SHARD_EALIGN, SHARD_EHIP. */
+int shard_profile_plain_copy(shard_plan_t* plan, void* dst, const void* src, size_t bytes, shard_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
               "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11,
-              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14}
+              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14, "plain_copy": 15}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -453,6 +453,16 @@ def shard_profile_read(plan: Plan, kernel: str) -> Tuple[int, float]:
 
 def shard_profile_reset(plan: Plan) -> None:
     _check(lib().shard_profile_reset(plan.handle), "shard_profile_reset")
+
+
+def shard_profile_plain_copy(plan: Plan, dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """The plainest device copy (measurement aid): dst and src contiguous CUDA tensors of the same byte size."""
+    nbytes = src.numel() * src.element_size()
+    if not (dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()) or \
+            dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must be contiguous CUDA tensors of equal size")
+    _check(lib().shard_profile_plain_copy(plan.handle, C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes,
+                                          _stream(stream)), "shard_profile_plain_copy")
 
 
 # ---- replica arrays (host only) ---------------------------------------------------------------------

@@ -92,7 +92,7 @@ const char* const kKernelNames[SHARD_K_COUNT] = {
     "format_kernel", "unshard_kernel", "adam_kernel", "momentum_kernel",
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
     "lars_p1_kernel", "lars_p2_kernel", "rowcol_p1_kernel", "rowcol_p2_kernel",
-    "adafactor_state_kernel", "adafactor_usq_kernel", "adafactor_apply_kernel",
+    "adafactor_state_kernel", "adafactor_usq_kernel", "adafactor_apply_kernel", "plain_copy_kernel",
 };
 
 // Step-dependent constants of Adafactor, taken in double and rounded once.
@@ -735,6 +735,13 @@ int shard_profile_reset(shard_plan_t* p) {
     p->prof_ms[i] = 0.0;
   }
   return SHARD_OK;
+}
+
+int shard_profile_plain_copy(shard_plan_t* p, void* dst, const void* src, size_t bytes, shard_stream_t stream) {
+  if (p == nullptr || dst == nullptr || src == nullptr || bytes == 0 || bytes % 16 != 0) return SHARD_EINVAL;
+  if (!aligned16(dst) || !aligned16(src)) return SHARD_EALIGN;
+  if (bytes / 16 > (size_t)0x7FFFFFFF * 256) return SHARD_EINVAL;          // more workgroups than a launch can hold
+  return hip_status(launch_plain_copy(p, dst, src, bytes / 16, as_stream(stream)));
 }
 
 }  // extern "C"

@@ -55,6 +55,13 @@ __global__ __launch_bounds__(kPtrBatch) void ptr_table_kernel(PtrBatch b, const 
   if (i < count) dst[i] = b.p[i];
 }
 
+// ---- the plain copy the formatting kernels are measured against -----------------------------------
+__global__ __launch_bounds__(kCopyBlock) void plain_copy_kernel(const u4* __restrict__ src, u4* __restrict__ dst,
+                                                             size_t units16) {
+  const size_t u = (size_t)blockIdx.x * kCopyBlock + threadIdx.x;
+  if (u < units16) st<true>(dst + u, ld<true>(src + u));
+}
+
 // ---- shard_format / unshard_format ----------------------------------------------------------------
 // A unit is what one lane moves per access: 4 elements whenever float32 is involved (one 128-bit
 // access on the float32 side, 64 bits on the bfloat16 side), 8 elements for bfloat16 -> bfloat16
@@ -474,6 +481,14 @@ void reformat_any(shard_plan_t* p, int r0, int replicas, const void* const* tab,
     reformat_dispatch<SHARD_BF16, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
 }
 }  // namespace
+
+hipError_t launch_plain_copy(shard_plan_t* p, void* dst, const void* src, size_t units16, hipStream_t stream) {
+  ProfScope ps(p, SHARD_K_PLAIN_COPY, stream);
+  const size_t blocks = (units16 + kCopyBlock - 1) / kCopyBlock;
+  hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)blocks), dim3(kCopyBlock), 0, stream, (const u4*)src, (u4*)dst,
+                     units16);
+  return hipGetLastError();
+}
 
 hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src_dtype, void* out, int dst_dtype,
                          bool vec, hipStream_t stream) {

@@ -218,6 +218,7 @@ hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_o
 hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w16, const AdamK& k,
                           const float* sums, hipStream_t stream);
 
+hipError_t launch_plain_copy(shard_plan_t* p, void* dst, const void* src, size_t units16, hipStream_t stream);
 hipError_t launch_format_all(shard_plan_t* p, const void* const* dev_ptr_table, int src_dtype, void* out,
                              int64_t row_stride, int dst_dtype, bool vec, hipStream_t stream);
 hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,

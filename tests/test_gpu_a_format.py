@@ -358,3 +358,24 @@ def test_random_plans_whole_model_copies():
         for i, (o, f) in enumerate(zip(back, flats)):
             assert same_bits(to_host(o), f), (case, i)
         plan.free()
+
+
+def test_plain_copy_measurement_aid():
+    plan = su.shard_plan([64], 2)                                   # any plan: it only carries the event records
+    src = torch.arange(0, 1 << 20, dtype=torch.int32, device=DEV)
+    buf, payload, band = _guarded(src.numel() * 4)
+    dst = payload.view(torch.int32)
+    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+    su.shard_profile_plain_copy(plan, dst, src)
+    su.shard_profile_plain_copy(plan, dst[:1000], src[4:1004])     # 4000 bytes, 16-byte aligned ends
+    torch.cuda.synchronize()
+    assert torch.equal(dst[1000:], src[1000:]) and torch.equal(dst[:1000], src[4:1004]) and _bands_intact(buf, band, src.numel() * 4)
+    n, ms = su.shard_profile_read(plan, "plain_copy")
+    assert n == 2 and ms > 0.0
+    with pytest.raises(su.ShardError) as e:
+        su.shard_profile_plain_copy(plan, dst[:1001], src[:1001])   # 4004 bytes
+    assert e.value.status == -1
+    with pytest.raises(su.ShardError) as e:
+        su.shard_profile_plain_copy(plan, dst[:1000], src[1:1001])  # source 4 bytes off a 16-byte boundary
+    assert e.value.status == -3
+    plan.free()
