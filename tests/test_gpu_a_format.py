@@ -233,6 +233,12 @@ def test_full_size_format_round_trip(name, N, replicas):
         su.shard_format(plan, r, dev_full, gathered[r])
     for r in replicas:
         assert same_bits(to_host(gathered[r]), oracle.shard_format(oplan, r, flats)), r
+    # all replicas in one pass (at 64 replicas of the 340 M model: large pieces replica by replica, small ones
+    # variable by variable): the same bits as replica after replica, in rows 128 bytes apart too
+    both = su.gathered_empty(plan).fill_(7.0)
+    su.shard_format_all(plan, dev_full, both)
+    assert torch.equal(both.view(torch.int32), gathered.view(torch.int32))
+    del both
     outs = [torch.empty(n, dtype=torch.float32, device=DEV) for n in numel]
     su.unshard_format(plan, gathered, outs)
     for i, (o, f) in enumerate(zip(outs, flats)):
