@@ -315,6 +315,32 @@ def test_format_all_replicas_in_one_pass(numel, N, align, src, dst):
     plan.free()
 
 
+@pytest.mark.parametrize("align,src,dst", [(8, "f32", "bf16"), (4, "bf16", "f32")])
+def test_format_all_split_walk_with_conversion(align, src, dst):
+    """Large enough (2^26 elements) for the plan to split the all-replica formatting: the two big variables
+    replica by replica, the small ones variable by variable; with a conversion, and once on the element-wise path."""
+    numel, N = [67000000] + [100, 64, 7, 1000] * 50 + [50000, 1200003], 64     # the small ones make the plan leave the replica walk
+    oplan = oracle.make_plan(numel, N, align)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+    flats = _bit_tensors(41, numel, src)
+    dev_full = [to_dev(f) for f in flats]
+    tdt = torch.float32 if dst == "f32" else torch.bfloat16
+    rows = torch.full((N, oplan.S + 8), 3.0, dtype=tdt, device=DEV)
+    su.shard_format_all(plan, dev_full, rows[:, :oplan.S])
+    assert bool((rows[:, oplan.S:] == 3.0).all())
+    for r in (0, 1, 31, 62, 63):
+        assert same_bits(to_host(rows[r, :oplan.S].contiguous()), oracle.shard_format(oplan, r, flats, dst=dst)), r
+    # and back, through the variable-by-variable unshard, into the source type
+    back = [torch.empty(n, dtype=torch.float32 if src == "f32" else torch.bfloat16, device=DEV) for n in numel]
+    su.unshard_format(plan, rows[:, :oplan.S], back)
+    if src == "bf16":                                   # bf16 -> f32 -> bf16 is the identity on every bit pattern but NaN payloads
+        for o, f in zip(back, flats):
+            a, b = to_host(o), f
+            nan = (b & 0x7F80 == 0x7F80) & (b & 0x007F != 0)
+            assert np.array_equal(a[~nan], b[~nan])
+    plan.free()
+
+
 def test_format_all_full_size_transformer():
     cfg = [c for c in CONFIGS if c.name == "transformer_big"][0]
     N = 16
