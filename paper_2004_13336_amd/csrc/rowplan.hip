@@ -204,6 +204,23 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
   }
 }
 
+// p[first * stride] + p[(first + step) * stride] + ... over the indices below n, added in exactly that order,
+// with eight loads in flight (the order is what makes results reproducible; the loads do not depend on each
+// other, only the additions do).
+__device__ __forceinline__ float ordered_sum(const float* __restrict__ p, int64_t stride, int first, int step, int n) {
+  float s = 0.0f;
+  int i = first;
+  for (; i + 7 * step < n; i += 8 * step) {
+    float a[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[j] = p[(int64_t)(i + j * step) * stride];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += a[j];
+  }
+  for (; i < n; i += step) s += p[(int64_t)i * stride];
+  return s;
+}
+
 // Adds the partial results of phase 1 in a fixed order.  The grid holds, in this order,
 //   one workgroup per column item: 64 columns whose row blocks the four wavefronts share (results
 //     combined in LDS), or 256 columns with a thread each where row blocks are few; other_col
@@ -238,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
       const bool ok = c < v.cols;
       float s = 0.0f;
       if (ok)
-        for (int rb = wave; rb < v.n_rb; rb += kWaves) s += colpart[v.cp_off + (int64_t)rb * v.cols + c];
+        s = ordered_sum(colpart + v.cp_off + c, v.cols, wave, kWaves, v.n_rb);
       lds[wave][lane] = s;
       __syncthreads();
       if (wave == 0) {
@@ -259,7 +276,7 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
       const int64_t c = (int64_t)it.tile * 256 + threadIdx.x;
       float tot = 0.0f;
       if (c < v.cols) {
-        for (int rb = 0; rb < v.n_rb; ++rb) tot += colpart[v.cp_off + (int64_t)rb * v.cols + c];
+        tot = ordered_sum(colpart + v.cp_off + c, v.cols, 0, 1, v.n_rb);
         if (other_col) tot += other_col[v.col_off + c];
         col_out[v.col_off + c] = tot;
       }
@@ -276,14 +293,14 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
     const RowColVar v = vars[it.var];
     if (it.wide) {
       float s = 0.0f;
-      for (int ct = threadIdx.x; ct < v.n_ct; ct += kBlock) s += rowpart[v.rp_off + (int64_t)ct * v.Lr + it.first_row];
+      s = ordered_sum(rowpart + v.rp_off + it.first_row, v.Lr, threadIdx.x, kBlock, v.n_ct);
       s = block_sum1(s);
       if (threadIdx.x == 0) row_out[v.row_off + it.first_row] = s;
     } else {
       const int64_t k = it.first_row + threadIdx.x;
       if (k < v.Lr) {
         float s = 0.0f;
-        for (int ct = 0; ct < v.n_ct; ++ct) s += rowpart[v.rp_off + (int64_t)ct * v.Lr + k];
+        s = ordered_sum(rowpart + v.rp_off + k, v.Lr, 0, 1, v.n_ct);
         row_out[v.row_off + k] = s;
       }
     }
