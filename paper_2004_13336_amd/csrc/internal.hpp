@@ -133,7 +133,7 @@ struct Workspace {
   size_t rc_col_items = 0, rc_row_items = 0, rc_colitem_part = 0;
   // Adafactor (row plans only): per-item partial sums, per-variable scalars, the factors of 1/sqrt(Vhat),
   // and the tables the fused call keeps between its phases
-  size_t af_wpart = 0, af_upart = 0, af_sumr = 0, af_inv_r = 0, af_inv_c = 0;
+  size_t af_wpart = 0, af_upart = 0, af_inv_r = 0, af_inv_c = 0;
   size_t af_rowsq = 0, af_colsq = 0, af_table = 0, af_usq = 0;
 };
 

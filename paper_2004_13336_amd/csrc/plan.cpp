@@ -226,7 +226,6 @@ size_t workspace_layout(const shard_plan_t* p, Workspace* ws) {
     const size_t items = p->rc_items.size(), rows = (size_t)p->rc_total_rows, cols = (size_t)p->rc_total_cols;
     ws->af_wpart = pos;    pos = align_up(pos + items * sizeof(float), 256);
     ws->af_upart = pos;    pos = align_up(pos + items * sizeof(float), 256);
-    ws->af_sumr = pos;     pos = align_up(pos + V * sizeof(float), 256);
     ws->af_inv_r = pos;    pos = align_up(pos + rows * sizeof(float), 256);
     ws->af_inv_c = pos;    pos = align_up(pos + cols * sizeof(float), 256);
     ws->af_rowsq = pos;    pos = align_up(pos + rows * sizeof(float), 256);

@@ -347,36 +347,33 @@ __global__ __launch_bounds__(kBlock) void adafactor_colsum_kernel(const RowColVa
   if (threadIdx.x == 0) colitem_part[blockIdx.x] = s;
 }
 
-// One workgroup per variable: sum(R) of the new row state.
-__global__ __launch_bounds__(kBlock) void adafactor_sumr_kernel(const RowColVar* __restrict__ vars,
-                                                                const float* __restrict__ colitem_part,
-                                                                const float* __restrict__ table_global,
-                                                                float* __restrict__ sum_r, AdafactorK k) {
-  const int i = blockIdx.x;
-  const RowColVar v = vars[i];
-  double s = 0.0;
-  for (int q = threadIdx.x; q < v.n_col_items; q += kBlock) s += (double)colitem_part[v.first_col_item + q];
-  s = block_sum_f64(s);
-  if (threadIdx.x == 0) {
-    const double n = (double)v.rows * (double)v.cols;
-    sum_r[i] = (float)((double)k.beta2 * (double)table_global[2 * i + 1] + (double)k.omb2 * (s + n * (double)k.eps1));
-  }
-}
-
 // Column items, then row items: new state, and the two factors of 1/sqrt(Vhat):
 // inv_r[k] = rsqrt(R_k) (0 for padded rows), inv_c[j] = rsqrt(C_j / sum(R)).
+// sum(R) over all replicas' rows = beta2 * (all-reduced sum of the old R) + (1-beta2) * (sum of the all-reduced
+// column sums + rows cols eps1); every column item adds its variable's few hundred item sums anew, in one fixed
+// order with float64 accumulators (cheaper than a launch of its own for one number per variable).
 __global__ __launch_bounds__(kBlock) void adafactor_state_kernel(const RowColVar* __restrict__ vars,
                                                                  const ColItem* __restrict__ col_items,
                                                                  const RowItem* __restrict__ row_items, int n_col_items,
                                                                  const float* __restrict__ row_sq,
                                                                  const float* __restrict__ col_sq_global,
-                                                                 const float* __restrict__ sum_r, float* R, float* C,
+                                                                 const float* __restrict__ colitem_part,
+                                                                 const float* __restrict__ table_global, float* R, float* C,
                                                                  float* __restrict__ inv_r, float* __restrict__ inv_c,
                                                                  int r, AdafactorK k) {
   int b = blockIdx.x;
   if (b < n_col_items) {
     const ColItem it = col_items[b];
     const RowColVar v = vars[it.var];
+    __shared__ float sum_r;
+    double s = 0.0;
+    for (int q = threadIdx.x; q < v.n_col_items; q += kBlock) s += (double)colitem_part[v.first_col_item + q];
+    s = block_sum_f64(s);
+    if (threadIdx.x == 0) {
+      const double n = (double)v.rows * (double)v.cols;
+      sum_r = (float)((double)k.beta2 * (double)table_global[2 * it.var + 1] + (double)k.omb2 * (s + n * (double)k.eps1));
+    }
+    __syncthreads();
     const int span = col_span(v.n_rb);
     const int64_t c = (int64_t)it.tile * span + threadIdx.x;
     if ((int)threadIdx.x >= span || c >= v.cols || v.rows == 0) return;    // no rows: the state stays as it is
@@ -387,7 +384,7 @@ __global__ __launch_bounds__(kBlock) void adafactor_state_kernel(const RowColVar
     const float col_eps = (float)v.rows * k.eps1;
     const float cn = fmaf(k.beta2, C[v.col_off + c], k.omb2 * (col_sq_global[v.col_off + c] + col_eps));
     C[v.col_off + c] = cn;
-    inv_c[v.col_off + c] = 1.0f / sqrtf(cn / sum_r[it.var]);
+    inv_c[v.col_off + c] = 1.0f / sqrtf(cn / sum_r);
     return;
   }
   const RowItem it = row_items[b - n_col_items];
@@ -600,7 +597,6 @@ hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, floa
   const RowItem* row_items = ws_at<RowItem>(p, p->ws.rc_row_items);
   const int n_col = (int)p->rc_col_items.size(), n_row = (int)p->rc_row_items.size();
   float* colitem_part = ws_at<float>(p, p->ws.rc_colitem_part);
-  float* sum_r = ws_at<float>(p, p->ws.af_sumr);
   float* inv_r = ws_at<float>(p, p->ws.af_inv_r);
   float* inv_c = ws_at<float>(p, p->ws.af_inv_c);
   float* upart = ws_at<float>(p, p->ws.af_upart);
@@ -609,11 +605,10 @@ hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, floa
     if (!have_column_item_sums && n_col > 0)
       hipLaunchKernelGGL(adafactor_colsum_kernel, dim3((unsigned)n_col), dim3(kBlock), 0, stream, vars, col_items,
                          col_sq_global, colitem_part);
-    hipLaunchKernelGGL(adafactor_sumr_kernel, dim3((unsigned)p->V), dim3(kBlock), 0, stream, vars,
-                       (const float*)colitem_part, table_global, sum_r, k);
     if (n_col + n_row > 0)
       hipLaunchKernelGGL(adafactor_state_kernel, dim3((unsigned)(n_col + n_row)), dim3(kBlock), 0, stream, vars,
-                         col_items, row_items, n_col, row_sq, col_sq_global, (const float*)sum_r, R, C, inv_r, inv_c, r,
+                         col_items, row_items, n_col, row_sq, col_sq_global, (const float*)colitem_part, table_global, R, C, inv_r,
+                         inv_c, r,
                          k);
   }
   hipError_t e = hipGetLastError();
