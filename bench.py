@@ -70,6 +70,18 @@ def _device_normal(n, std, gen, torch):
     return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, std, generator=gen)
 
 
+def _settle_copy(torch, su, plan, copy, full, fn):
+    """Lets the library finish timing its two orders of a whole-model copy (its first calls with a list of full
+    tensors) before anything is measured; returns the order it settled on and the two times in ms."""
+    for _ in range(16):
+        if su.shard_plan_copy_walk(plan, copy, full) != "auto":
+            break
+        fn()
+        torch.cuda.synchronize()
+    walk, (by_replica_ms, by_variable_ms) = su.shard_plan_copy_walk(plan, copy, full, with_times=True)
+    return {"walk": walk, "timed_ms_by_replica": round(by_replica_ms, 4), "timed_ms_by_variable": round(by_variable_ms, 4)}
+
+
 def _time_region(torch, fn, steps):
     """Milliseconds per call of fn over `steps` back-to-back calls, bracketed by synchronisation."""
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -127,6 +139,20 @@ class Workbench:
         import numpy as np
         return {k: float(np.float32(v)) for k, v in self.cfg.hyper.items()}
 
+    def settle_copies(self, format_all=False):
+        """The library times its two orders of a whole-model copy on the first calls with a list of tensors;
+        this makes those calls, so that what is measured afterwards is the order it settled on."""
+        su, plan = self.su, self.plan
+        if self.full_w is None:
+            return {}
+        out = {"unshard_format": _settle_copy(self.torch, su, plan, "unshard_format", self.full_w,
+                                              lambda: su.unshard_format(plan, self.gathered, self.full_w))}
+        if format_all:
+            out["shard_format_all"] = _settle_copy(self.torch, su, plan, "shard_format_all", self.full_g,
+                                                   lambda: su.shard_format_all(plan, self.full_g, self.gathered))
+            self.gathered.normal_(0.0, self.cfg.weight_std, generator=self.gen)    # weights again, not gradients
+        return out
+
     def free(self):
         self.plan.free()
 
@@ -155,6 +181,7 @@ def headline(args, torch, su, cfgs):
         su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, hp, state["t"], other_replicas_sumsq=wb.other)
         su.unshard_format(plan, wb.gathered, wb.full_w)
 
+    unshard_walk = wb.settle_copies()["unshard_format"]
     for _ in range(max(args.warmup, 2)):
         one_step()
     ms_step, wall_ms = _time_region(torch, one_step, args.steps)
@@ -244,6 +271,7 @@ def headline(args, torch, su, cfgs):
                              w_bf16_out=g16[r])
         su.unshard_format(plan, g16, full16)
 
+    _settle_copy(torch, su, plan, "unshard_format", full16, lambda: su.unshard_format(plan, g16, full16))
     for _ in range(3):
         one_step_bf16()
     ms16, _ = _time_region(torch, one_step_bf16, args.steps)
@@ -291,7 +319,7 @@ def headline(args, torch, su, cfgs):
         "config": {"workload": "%s fp32 LAMB N=%d r=%d: shard_format(g) + shard_update_lamb + unshard_format(w)"
                                % (cfg.name, N, r),
                    "variables": plan.V, "params": cfg.total, "shard_slots": S, "shard_params": wb.real,
-                   "chunk_elems": plan.chunk_elems},
+                   "chunk_elems": plan.chunk_elems, "unshard_order": unshard_walk},
         "roofline": roof,
         "kernels": rooflines,
         "update_only": update_only,
@@ -452,6 +480,7 @@ def table(args, torch, su, cfgs, path):
                     su.unshard_format(plan, wb.gathered, wb.full_w)
                 stages.append(("step: format + %s + unshard" % opt_name, whole_step, ["format"] + opt_kernels + ["unshard"],
                                8 * S + opt_bytes + 4 * N * S + 4 * cfg.total))
+            copy_orders = wb.settle_copies(format_all=True)
             for name, fn, kernels, nbytes in stages:
                 for t in range(1, 6):
                     fn(t)
@@ -471,6 +500,8 @@ def table(args, torch, su, cfgs, path):
                              "params_per_s": wb.real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                              "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                              "cache_resident": state_bytes < 256e6})
+                if name in copy_orders:
+                    rows[-1]["order"] = copy_orders[name]["walk"]
                 print("table:", rows[-1], file=sys.stderr, flush=True)
             wb.free()
             del wb
@@ -554,6 +585,9 @@ def one_stage(args, torch, su, cfgs):
     if name not in stages:
         raise SystemExit("unknown --stage %s" % name)
     fn, kernels, nbytes = stages[name]
+    copy_orders = wb.settle_copies(format_all=name == "shard_format_all") if needs_full else {}
+    if name == "unshard_format_bf16":
+        copy_orders = {"unshard_format": _settle_copy(torch, su, plan, "unshard_format", full16, lambda: fn(0))}
     # --cold: a 1 GiB device copy between launches of the stage, so that nothing of the previous launch is
     # left in the 256 MB memory-side cache (between two real steps a forward and a backward pass run); the
     # event pairs time the library's kernels only
@@ -573,7 +607,8 @@ def one_stage(args, torch, su, cfgs):
     us = sum(per.values())
     print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
                       "total_us": round(us, 2), "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
-                      "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold)}))
+                      "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold),
+                      "copy_orders": copy_orders}))
     wb.free()
 
 

@@ -37,7 +37,8 @@
  *  - A plan is not thread-safe, and calls that use one plan must be ordered on one
  *    stream (or otherwise synchronised by the caller): they share the plan's workspace.
  *  - HIP graphs: the formatting and update calls only launch kernels (no allocation, no
- *    synchronisation, no memset), so a step can be recorded with stream capture.  Scalars passed by
+ *    synchronisation, no memset; the two whole-model copies also record and query events on their first calls,
+ *    but never on a capturing stream), so a step can be recorded with stream capture.  Scalars passed by
  *    value (replica id, step, hyper-parameters) are frozen into the graph.  The device tables of
  *    full-tensor pointers are cached in the plan's workspace (the 4 most recently used lists); a
  *    recorded graph reads the tables that were resident at capture time, so between capture and the
@@ -73,6 +74,11 @@ enum {
   SHARD_VAR_NO_DECAY = 1u,   /* weight decay is not applied to this variable */
   SHARD_VAR_NO_ADAPT = 2u    /* the trust ratio of this variable is fixed at 1 */
 };
+
+/* Order of the work items of the whole-model copies (shard_plan_set_copy_walk) and which copy is meant
+ * (shard_plan_copy_walk). */
+enum { SHARD_WALK_AUTO = 0, SHARD_WALK_BY_REPLICA = 1, SHARD_WALK_BY_VARIABLE = 2 };
+enum { SHARD_COPY_UNSHARD = 0, SHARD_COPY_FORMAT_ALL = 1 };
 
 /* Kernel ids for shard_profile_read. */
 enum {
@@ -171,6 +177,29 @@ int shard_format_all(shard_plan_t* plan, const void* const* full_ptrs, int src_d
  * needs, Section 4.2). */
 int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride, int src_dtype,
                    void* const* full_ptrs, int dst_dtype, shard_stream_t stream);
+
+/* The order in which shard_format_all and unshard_format, which move the whole model, take their work
+ * items: replica by replica (each row of the gathered buffer from end to end) or variable by variable (each
+ * full tensor from end to end).  The bytes written are the same; the time is not.  Small pieces (many
+ * replicas) go by variable, which shard_plan decides.  With large pieces going by replica is the faster by
+ * about 5 %, unless the caller's full tensors lie where the pieces that are in flight together collide
+ * in memory: equal-sized tensors an exact power of two apart (a framework's allocator places a layer stack's
+ * 4 MiB matrices like that) cost that order a quarter of its rate on MI355X, by variable nothing.  Addresses
+ * alone do not tell, so the default measures:
+ *   SHARD_WALK_AUTO         (default) on a flat plan with large pieces and N > 1, the first 6 calls of each of the
+ *                           two copies with a given list of full tensors (and element types, row_stride) are
+ *                           timed, 3 in each order in turn, by an event pair on `stream` that a later call reads
+ *                           without waiting; from then on the faster order is used while that list stays among the
+ *                           plan's 4 cached ones.  Calls on a capturing stream, and calls made while the last timed
+ *                           one has not finished, go by replica untimed and do not count.  No call blocks.
+ *   SHARD_WALK_BY_REPLICA, SHARD_WALK_BY_VARIABLE   always that order (row plans and N = 1 know only the first).
+ * shard_plan_copy_walk reports, for `copy` (SHARD_COPY_*) and a host list of full-tensor pointers (may be NULL),
+ * the order the next such call takes: a fixed one, or SHARD_WALK_AUTO while the measurement is still under way
+ * or the list is not cached; best_ms_out (host, 2 floats, may be NULL) receives the fastest timed call by replica
+ * and by variable so far in milliseconds, 0 where there is none.  Errors: SHARD_EINVAL. */
+int shard_plan_set_copy_walk(shard_plan_t* plan, int walk);
+int shard_plan_copy_walk(const shard_plan_t* plan, int copy, const void* const* full_ptrs, int* walk_out,
+                         float* best_ms_out);
 
 /* ------------------------------------------------------------------------------------------
  * Fused optimizer updates on one packed shard (Section 2.2: read gradient, weight and

@@ -204,6 +204,32 @@ def unshard_format(plan: Plan, gathered: torch.Tensor, full_tensors: Sequence[to
     return full_tensors
 
 
+COPY_WALKS = {"auto": 0, "by_replica": 1, "by_variable": 2}
+COPIES = {"unshard_format": 0, "shard_format_all": 1}
+
+
+def shard_plan_set_copy_walk(plan: Plan, walk: str) -> None:
+    """Order of the work items of shard_format_all and unshard_format: "auto" (measured on the first calls),
+    "by_replica" or "by_variable"."""
+    if walk not in COPY_WALKS:
+        raise ValueError("walk must be one of %s" % sorted(COPY_WALKS))
+    _check(lib().shard_plan_set_copy_walk(plan.handle, COPY_WALKS[walk]), "shard_plan_set_copy_walk")
+
+
+def shard_plan_copy_walk(plan: Plan, copy: str, full_tensors=None, with_times: bool = False):
+    """The order the next `copy` ("unshard_format" or "shard_format_all") with these full tensors takes;
+    "auto" while it is still being measured.  with_times: also the fastest timed call in each order so far
+    (by replica, by variable) in ms."""
+    if copy not in COPIES:
+        raise ValueError("copy must be one of %s" % sorted(COPIES))
+    arr = None if full_tensors is None else _full_ptrs(plan, full_tensors, "full_tensors")[0]
+    out = C.c_int(-1)
+    best = (C.c_float * 2)()
+    _check(lib().shard_plan_copy_walk(plan.handle, COPIES[copy], arr, C.byref(out), best), "shard_plan_copy_walk")
+    walk = {v: k for k, v in COPY_WALKS.items()}[out.value]
+    return (walk, (best[0], best[1])) if with_times else walk
+
+
 def _hp(cls, hp: Dict[str, float]):
     return cls(**{name: float(hp.get(name, 0.0)) for name, _ in cls._fields_})
 

@@ -48,7 +48,8 @@ int check_plan_r(const shard_plan_t* p, int r, bool need_ws) {
 
 // Returns the device address of a pointer table holding `ptrs`, uploading it into the least
 // recently used slot unless an identical table is already resident.
-int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t stream, const void*** table) {
+int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t stream, const void*** table,
+                       int* slot_out = nullptr) {
   const size_t bytes = (size_t)p->V * sizeof(void*);
   int slot = -1;
   for (int s = 0; s < kPtrSlots; ++s)
@@ -71,11 +72,104 @@ int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t str
       std::memcpy(p->slot_ptrs[slot].data(), ptrs, bytes);
     }
     p->slot_valid[slot] = true;
+    for (WalkTrial& t : p->walk_trial[slot]) t.restart();    // other tensors: what was measured no longer holds
   }
   p->slot_age[slot] = ++p->clock;
   *table = base + (size_t)slot * p->V;
+  if (slot_out) *slot_out = slot;
   return SHARD_OK;
 }
+
+// ---- the order of a whole-model copy -----------------------------------------------------------
+// Both orders move the same bytes to the same places.  Which is faster depends on the piece size (small
+// pieces: by variable, decided when the plan is built) and, for large pieces, on how the caller's full tensors
+// lie in memory: equal-sized tensors a power of two apart make the pieces that are in flight together by
+// replica fall on the same memory channels and banks, and that order then loses a quarter of its rate
+// while the other keeps it.  The library cannot tell from the addresses, so under SHARD_WALK_AUTO the first
+// calls with a list of tensors are timed, in turn one order and the other, with an event pair on the caller's
+// stream that is read (never waited for) at a later call.
+
+// Static answer, or SHARD_WALK_AUTO where only a measurement decides.
+int static_walk(const shard_plan_t* p) {
+  if (p->row_plan || p->full_chunks.empty() || p->N == 1) return SHARD_WALK_BY_REPLICA;
+  if (p->copy_walk != SHARD_WALK_AUTO) return p->copy_walk;
+  if (p->flat_copies) return SHARD_WALK_BY_VARIABLE;
+  return SHARD_WALK_AUTO;
+}
+
+struct WalkChoice {
+  bool by_variable;
+  WalkTrial* timed;      // not null: bracket the launch with timed->ev
+};
+
+WalkChoice choose_walk(shard_plan_t* p, int slot, int op, int src_dtype, int dst_dtype, int64_t row_stride,
+                       hipStream_t stream) {
+  const int fixed = static_walk(p);
+  if (fixed != SHARD_WALK_AUTO) return WalkChoice{fixed == SHARD_WALK_BY_VARIABLE, nullptr};
+  WalkTrial& t = p->walk_trial[slot][op];
+  if (t.src_dtype != src_dtype || t.dst_dtype != dst_dtype || t.row_stride != row_stride) {
+    t.restart();
+    t.src_dtype = src_dtype;
+    t.dst_dtype = dst_dtype;
+    t.row_stride = row_stride;
+  }
+  if (t.chosen != SHARD_WALK_AUTO) return WalkChoice{t.chosen == SHARD_WALK_BY_VARIABLE, nullptr};
+  const WalkChoice untimed{false, nullptr};
+  // a stream that is being captured takes no event queries: such calls are not part of the trial
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) {
+    (void)hipGetLastError();
+    return untimed;
+  }
+  if (capturing != hipStreamCaptureStatusNone) return untimed;
+  if (t.pending) {
+    const hipError_t q = hipEventQuery(t.ev[1]);
+    if (q == hipErrorNotReady) {
+      (void)hipGetLastError();
+      return untimed;                                   // the timed call still runs: this one is not timed
+    }
+    float ms = 0.0f;
+    if (q != hipSuccess || hipEventElapsedTime(&ms, t.ev[0], t.ev[1]) != hipSuccess) {
+      (void)hipGetLastError();
+      t.chosen = SHARD_WALK_BY_REPLICA;                 // no timing to be had: the default for large pieces
+      return untimed;
+    }
+    t.pending = false;
+    const int which = t.calls & 1;
+    if (t.calls < 2 || ms < t.best_ms[which]) t.best_ms[which] = ms;
+    if (++t.calls == 2 * kWalkTrialRounds) {
+      // A call timed on its own still has part of its writes in the memory-side cache when it ends, which
+      // later kernels pay for; that flatters going by variable, which back to back is the slower by 4 to 5 %
+      // on well-placed tensors while both time alike here.  Colliding tensors cost going by replica 10 to 25 %:
+      // only a lead of that kind counts.
+      t.chosen = t.best_ms[1] < 0.95f * t.best_ms[0] ? SHARD_WALK_BY_VARIABLE : SHARD_WALK_BY_REPLICA;
+      return WalkChoice{t.chosen == SHARD_WALK_BY_VARIABLE, nullptr};
+    }
+  }
+  if (t.ev[0] == nullptr && (hipEventCreate(&t.ev[0]) != hipSuccess || hipEventCreate(&t.ev[1]) != hipSuccess)) {
+    (void)hipGetLastError();
+    t.chosen = SHARD_WALK_BY_REPLICA;
+    return untimed;
+  }
+  return WalkChoice{(t.calls & 1) != 0, &t};
+}
+
+// Brackets one launch with the trial's events when the call is a timed one.
+struct WalkTimer {
+  WalkTrial* t;
+  hipStream_t stream;
+  WalkTimer(const WalkChoice& c, hipStream_t s) : t(c.timed), stream(s) {
+    if (t && hipEventRecord(t->ev[0], stream) != hipSuccess) {
+      (void)hipGetLastError();
+      t = nullptr;
+    }
+  }
+  ~WalkTimer() {
+    if (!t) return;
+    if (hipEventRecord(t->ev[1], stream) == hipSuccess) t->pending = true;
+    else (void)hipGetLastError();
+  }
+};
 
 // 128-bit path: pieces start on 16-byte boundaries for both element sizes.  (Whether each full
 // tensor does too is checked per variable inside the kernels.)
@@ -411,6 +505,10 @@ void shard_plan_free(shard_plan_t* p) {
     (void)hipEventDestroy(rec.start);
     (void)hipEventDestroy(rec.stop);
   }
+  for (auto& slot : p->walk_trial)
+    for (WalkTrial& t : slot)
+      for (hipEvent_t e : t.ev)
+        if (e != nullptr) (void)hipEventDestroy(e);
   delete p;
 }
 
@@ -439,9 +537,13 @@ int shard_format_all(shard_plan_t* p, const void* const* full_ptrs, int src_dtyp
   if (p->S == 0) return SHARD_OK;
   if ((rc = check_shard_ptr(out)) != SHARD_OK) return rc;
   const void** table = nullptr;
-  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
+  int slot = 0;
+  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table, &slot)) != SHARD_OK) return rc;
   const bool vec = pieces_vectorisable(p) && row_stride % 8 == 0;
-  return hip_status(launch_format_all(p, table, src_dtype, out, row_stride, dst_dtype, vec, as_stream(stream)));
+  const WalkChoice walk = choose_walk(p, slot, SHARD_COPY_FORMAT_ALL, src_dtype, dst_dtype, row_stride, as_stream(stream));
+  WalkTimer timer(walk, as_stream(stream));
+  return hip_status(launch_format_all(p, table, src_dtype, out, row_stride, dst_dtype, vec, walk.by_variable,
+                                      as_stream(stream)));
 }
 
 int unshard_format(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* full_ptrs,
@@ -455,11 +557,41 @@ int unshard_format(shard_plan_t* p, const void* gathered, int64_t row_stride, in
   if (p->S == 0) return SHARD_OK;
   if ((rc = check_shard_ptr(gathered)) != SHARD_OK) return rc;
   const void** table = nullptr;
-  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table)) != SHARD_OK) return rc;
+  int slot = 0;
+  if ((rc = resident_ptr_table(p, full_ptrs, as_stream(stream), &table, &slot)) != SHARD_OK) return rc;
   const bool vec = pieces_vectorisable(p) && row_stride % 8 == 0;   // rows stay 16-byte aligned
+  const WalkChoice walk = choose_walk(p, slot, SHARD_COPY_UNSHARD, src_dtype, dst_dtype, row_stride, as_stream(stream));
+  WalkTimer timer(walk, as_stream(stream));
   return hip_status(launch_unshard(p, gathered, row_stride, src_dtype,
                                    reinterpret_cast<void* const*>(const_cast<void**>(table)), dst_dtype, vec,
-                                   as_stream(stream)));
+                                   walk.by_variable, as_stream(stream)));
+}
+
+int shard_plan_set_copy_walk(shard_plan_t* p, int walk) {
+  if (p == nullptr || (walk != SHARD_WALK_AUTO && walk != SHARD_WALK_BY_REPLICA && walk != SHARD_WALK_BY_VARIABLE))
+    return SHARD_EINVAL;
+  p->copy_walk = walk;
+  return SHARD_OK;
+}
+
+int shard_plan_copy_walk(const shard_plan_t* p, int copy, const void* const* full_ptrs, int* walk_out,
+                         float* best_ms_out) {
+  if (p == nullptr || walk_out == nullptr || (copy != SHARD_COPY_UNSHARD && copy != SHARD_COPY_FORMAT_ALL))
+    return SHARD_EINVAL;
+  if (best_ms_out) best_ms_out[0] = best_ms_out[1] = 0.0f;
+  *walk_out = static_walk(p);
+  if (*walk_out != SHARD_WALK_AUTO || full_ptrs == nullptr) return SHARD_OK;
+  const size_t bytes = (size_t)p->V * sizeof(void*);
+  for (int s = 0; s < kPtrSlots; ++s)
+    if (p->slot_valid[s] && std::memcmp(p->slot_ptrs[s].data(), full_ptrs, bytes) == 0) {
+      const WalkTrial& t = p->walk_trial[s][copy];
+      *walk_out = t.chosen;
+      if (best_ms_out) {
+        best_ms_out[0] = t.calls > 0 ? t.best_ms[0] : 0.0f;
+        best_ms_out[1] = t.calls > 1 ? t.best_ms[1] : 0.0f;
+      }
+    }
+  return SHARD_OK;
 }
 
 int shard_update_adam(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,

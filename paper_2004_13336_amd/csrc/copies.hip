@@ -407,7 +407,7 @@ inline int odd_count(int64_t wgs, int replicas) {
 // MODE: 0 = shard_format (one replica), 1 = unshard_format, 2 = shard_format_all
 template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
-                       bool vec, hipStream_t stream) {
+                       bool vec, bool by_variable, hipStream_t stream) {
   const int n_chunks = (int)p->chunks.size();
   constexpr int U = MODE == 0 ? SU_FORMAT_UNROLL : (MODE == 1 ? SU_UNSHARD_UNROLL : SU_FORMAT_ALL_UNROLL);
   constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
@@ -417,7 +417,7 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
   const dim3 g((unsigned)((int64_t)per * replicas)), b(kCopyBlock);
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  if (MODE != 0 && p->flat_copies) {
+  if (MODE != 0 && by_variable && !p->full_chunks.empty()) {
     // flat plan: variable by variable over the padded variables (same tiles, another item table)
     const FullChunk* fchunks = ws_at<FullChunk>(p, p->ws.full_chunks);
     const dim3 gf((unsigned)((int64_t)p->full_chunks.size() * tiles_per_chunk));
@@ -432,9 +432,12 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
         if (vec) hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
         else hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
       }
-      const FullChunk* small = ws_at<FullChunk>(p, p->ws.small_full_chunks);
-      const dim3 gs((unsigned)((int64_t)p->small_full_chunks.size() * tiles_per_chunk));
-      if (!p->small_full_chunks.empty()) {
+      // no split (large pieces throughout, this order picked by measurement): every item variable by variable
+      const bool split = p->flat_copies;
+      const FullChunk* small = split ? ws_at<FullChunk>(p, p->ws.small_full_chunks) : fchunks;
+      const size_t n_small = split ? p->small_full_chunks.size() : p->full_chunks.size();
+      const dim3 gs((unsigned)((int64_t)n_small * tiles_per_chunk));
+      if (n_small > 0) {
         if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
         else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
       }
@@ -470,15 +473,15 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
 
 template <int MODE>
 void reformat_any(shard_plan_t* p, int r0, int replicas, const void* const* tab, int src_dtype, void* packed,
-                  int64_t stride, int dst_dtype, bool vec, hipStream_t stream) {
+                  int64_t stride, int dst_dtype, bool vec, bool by_variable, hipStream_t stream) {
   if (src_dtype == SHARD_F32 && dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_F32, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, by_variable, stream);
   else if (src_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_F32, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_F32, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, by_variable, stream);
   else if (dst_dtype == SHARD_F32)
-    reformat_dispatch<SHARD_BF16, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_BF16, SHARD_F32, MODE>(p, r0, replicas, tab, packed, stride, vec, by_variable, stream);
   else
-    reformat_dispatch<SHARD_BF16, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, stream);
+    reformat_dispatch<SHARD_BF16, SHARD_BF16, MODE>(p, r0, replicas, tab, packed, stride, vec, by_variable, stream);
 }
 }  // namespace
 
@@ -494,24 +497,24 @@ hipError_t launch_format(shard_plan_t* p, int r, const void* const* tab, int src
                          bool vec, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<0>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, stream);
+  reformat_any<0>(p, r, 1, tab, src_dtype, out, p->S, dst_dtype, vec, false, stream);
   return hipGetLastError();
 }
 
 hipError_t launch_format_all(shard_plan_t* p, const void* const* tab, int src_dtype, void* out, int64_t row_stride,
-                             int dst_dtype, bool vec, hipStream_t stream) {
+                             int dst_dtype, bool vec, bool by_variable, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_FORMAT, stream);
-  reformat_any<2>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, stream);
+  reformat_any<2>(p, 0, p->N, tab, src_dtype, out, row_stride, dst_dtype, vec, by_variable, stream);
   return hipGetLastError();
 }
 
 hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype, void* const* tab,
-                          int dst_dtype, bool vec, hipStream_t stream) {
+                          int dst_dtype, bool vec, bool by_variable, hipStream_t stream) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_UNSHARD, stream);
   reformat_any<1>(p, 0, p->N, reinterpret_cast<const void* const*>(tab), src_dtype, const_cast<void*>(gathered),
-                     row_stride, dst_dtype, vec, stream);
+                     row_stride, dst_dtype, vec, by_variable, stream);
   return hipGetLastError();
 }
 

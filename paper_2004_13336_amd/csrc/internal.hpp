@@ -142,6 +142,27 @@ struct ProfRecord {
   int kernel;
 };
 
+// Which of the two orders a whole-model copy takes for one cached pointer table, found by timing both on the
+// first calls (SHARD_WALK_AUTO).  One per (pointer slot, operation); starts again when the slot gets other
+// pointers or the call other element types or another row stride.
+constexpr int kWalkTrialRounds = 3;  // timed calls per order
+struct WalkTrial {
+  int src_dtype = -1, dst_dtype = -1;
+  int64_t row_stride = -1;
+  int calls = 0;                      // timed calls read so far; even ones went by replica, odd ones by variable
+  float best_ms[2] = {0.0f, 0.0f};    // fastest call by replica, by variable
+  int chosen = SHARD_WALK_AUTO;       // SHARD_WALK_AUTO while the trial runs
+  bool pending = false;               // ev[] bracket a timed call whose time has not been read yet
+  hipEvent_t ev[2] = {nullptr, nullptr};   // created at the first timed call, destroyed with the plan
+  void restart() {
+    src_dtype = dst_dtype = -1;
+    row_stride = -1;
+    calls = 0;
+    chosen = SHARD_WALK_AUTO;
+    pending = false;
+  }
+};
+
 }  // namespace su
 
 struct shard_plan_s {
@@ -152,7 +173,9 @@ struct shard_plan_s {
   std::vector<su::VarDesc> vars;
   std::vector<su::ChunkDesc> chunks;
   std::vector<su::FullChunk> full_chunks;  // flat plans only
-  bool flat_copies = false;                // whole-model copies walk full_chunks instead of (replica, chunk)
+  bool flat_copies = false;                // pieces are small: whole-model copies go variable by variable
+  int copy_walk = SHARD_WALK_AUTO;         // shard_plan_set_copy_walk
+  su::WalkTrial walk_trial[su::kPtrSlots][2];   // [slot][SHARD_COPY_UNSHARD or SHARD_COPY_FORMAT_ALL]
   // With flat_copies, shard_format_all splits the variables: those whose pieces hold at least one whole chunk go
   // replica by replica (their chunks, copied here), the others variable by variable (their items of full_chunks).
   std::vector<su::ChunkDesc> major_chunks;
@@ -198,9 +221,10 @@ hipError_t launch_ptr_table(shard_plan_t* p, const void* const* host_ptrs, const
 
 hipError_t launch_format(shard_plan_t* p, int r, const void* const* dev_ptr_table, int src_dtype, void* out,
                          int dst_dtype, bool vec, hipStream_t stream);
+// by_variable: the work items are chunks of the padded variables (flat plans only), else (replica, chunk)
 hipError_t launch_unshard(shard_plan_t* p, const void* gathered, int64_t row_stride, int src_dtype,
-                          void* const* dev_ptr_table,
-                          int dst_dtype, bool vec, hipStream_t stream);
+                          void* const* dev_ptr_table, int dst_dtype, bool vec, bool by_variable,
+                          hipStream_t stream);
 
 hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, float* v, void* w16, const AdamK& k,
                        hipStream_t stream);
@@ -220,7 +244,7 @@ hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, cons
 
 hipError_t launch_plain_copy(shard_plan_t* p, void* dst, const void* src, size_t units16, hipStream_t stream);
 hipError_t launch_format_all(shard_plan_t* p, const void* const* dev_ptr_table, int src_dtype, void* out,
-                             int64_t row_stride, int dst_dtype, bool vec, hipStream_t stream);
+                             int64_t row_stride, int dst_dtype, bool vec, bool by_variable, hipStream_t stream);
 hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
                           const void* const* g_full, hipStream_t stream);
 hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, int g_source, const void* const* g_full,

@@ -9,6 +9,9 @@
 
 #include "internal.hpp"
 
+#ifndef SU_SPLIT_LOG2
+#define SU_SPLIT_LOG2 26
+#endif
 namespace su {
 
 namespace {
@@ -116,7 +119,6 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       // one a number that does not grow with N; where pieces are large the former is the faster (7 %
       // at 8 replicas), so the latter is taken once fragments make the former's item count 7 % larger.
       p->flat_copies = (int64_t)N * (int64_t)p->chunks.size() * 100 > (int64_t)p->full_chunks.size() * kFlatWalkPercent;
-      if (!p->flat_copies) std::vector<FullChunk>().swap(p->full_chunks);     // not needed: keep the workspace small
       // Writes that stay contiguous matter more than reads that do: unshard_format writes the full tensors, so
       // its variable-by-variable walk is the contiguous one; shard_format_all writes the gathered rows, so for
       // variables whose pieces hold whole chunks the replica-by-replica walk is (measured: 6 to 9 % faster from
@@ -127,7 +129,7 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       if (p->flat_copies) {
         // a model that fits the memory-side cache copies in tens of microseconds: a second launch costs more
         // than the split gains (ResNet-50-shaped, 32 replicas: 39 against 37 us)
-        const bool split = p->total >= ((int64_t)1 << 26);
+        const bool split = p->total >= ((int64_t)1 << SU_SPLIT_LOG2);
         size_t fc = 0;
         for (int i = 0; i < V; ++i) {
           const bool big = split && p->L[i] >= chunk;

@@ -411,3 +411,84 @@ def test_plain_copy_measurement_aid():
         su.shard_profile_plain_copy(plan, dst[:1000], src[1:1001])  # source 4 bytes off a 16-byte boundary
     assert e.value.status == -3
     plan.free()
+
+
+WALK_CASES = [([30000, 37, 0, 8, 4099, 1, 65536], 3, 8), ([9000, 64, 64], 32, 8), ([100, 33, 7], 4, 1),
+              ([20011, 4096, 5], 1, 8)]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("numel,N,align", WALK_CASES)
+@pytest.mark.parametrize("src,dst", [("f32", "f32"), ("f32", "bf16"), ("bf16", "f32")])
+def test_both_orders_of_the_whole_model_copies_write_the_same_bytes(numel, N, align, src, dst):
+    """shard_format_all and unshard_format with the order forced either way against the oracle, on plans
+    whose default would be the one and the other."""
+    oplan = oracle.make_plan(numel, N, align)
+    flats = _bit_tensors(41, numel, src)
+    sdt = torch.float32 if src == "f32" else torch.bfloat16
+    ddt = torch.float32 if dst == "f32" else torch.bfloat16
+    want_rows = np.stack([oracle.shard_format(oplan, r, flats, dst=dst) for r in range(N)])
+    src_ref = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
+    want_full = oracle.unshard_format(oplan, src_ref, dst=dst)
+    for walk in ("by_replica", "by_variable"):
+        plan = su.shard_plan_bind(su.shard_plan(numel, N, align))
+        su.shard_plan_set_copy_walk(plan, walk)
+        full = [to_dev(f) for f in flats]
+        expect = walk if (N > 1) else "by_replica"
+        assert su.shard_plan_copy_walk(plan, "shard_format_all", full) == expect
+        rows = torch.full((N, max(oplan.S, 1)), 7.0, dtype=ddt, device=DEV)[:, :oplan.S]
+        su.shard_format_all(plan, full, rows)
+        assert same_bits(to_host(rows), want_rows), walk
+        src_rows = torch.empty((N, max(oplan.S, 1)), dtype=sdt, device=DEV)[:, :oplan.S]
+        src_rows.copy_(to_dev(src_ref))
+        outs = [torch.full((n,), 7.0, dtype=ddt, device=DEV) for n in numel]
+        su.unshard_format(plan, src_rows, outs)
+        for o, w in zip(outs, want_full):
+            assert same_bits(to_host(o), w), walk
+        plan.free()
+
+
+@pytest.mark.gpu
+def test_measured_order_settles_and_every_call_on_the_way_is_right():
+    """With large pieces the order is found by timing the first calls: each of them, whichever order it takes,
+    restores the same bytes; after at most 6 timed calls the order is fixed, and another list of tensors starts
+    a measurement of its own."""
+    numel, N = [262144, 100, 131072, 70000, 262144], 4
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = _bit_tensors(43, numel, "f32")
+    ref = np.stack([oracle.shard_format(oplan, r, flats) for r in range(N)])
+    gathered = su.gathered_empty(plan)
+    gathered.copy_(to_dev(ref))
+    outs = [torch.zeros(n, device=DEV) for n in numel]
+    assert su.shard_plan_copy_walk(plan, "unshard_format", outs) == "auto"
+    seen = []
+    for _ in range(8):
+        for o in outs:
+            o.fill_(3.0)
+        su.unshard_format(plan, gathered, outs)
+        torch.cuda.synchronize()
+        for o, f in zip(outs, flats):
+            assert same_bits(to_host(o), f)
+        seen.append(su.shard_plan_copy_walk(plan, "unshard_format", outs, with_times=True))
+    assert seen[5][0] == "auto" and seen[6][0] in ("by_replica", "by_variable"), seen
+    assert seen[6][1][0] > 0.0 and seen[6][1][1] > 0.0
+    assert seen[7] == seen[6]
+    # the other copy and another list of tensors have not been measured yet
+    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs) == "auto"
+    others = [torch.zeros(n, device=DEV) for n in numel]
+    assert su.shard_plan_copy_walk(plan, "unshard_format", others) == "auto"
+    rows = torch.zeros_like(gathered)
+    for _ in range(8):
+        rows.fill_(5.0)
+        su.shard_format_all(plan, outs, rows)
+        torch.cuda.synchronize()
+        assert same_bits(to_host(rows), ref)
+    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs) != "auto"
+    # calls that do not wait for one another settle as well, only later; all of them are right
+    for _ in range(40):
+        su.unshard_format(plan, gathered, others)
+    torch.cuda.synchronize()
+    for o, f in zip(others, flats):
+        assert same_bits(to_host(o), f)
+    plan.free()

@@ -332,3 +332,35 @@ def test_header_is_valid_c99_and_the_c_client_builds():
     import __graft_entry__
     lib()                                               # the library the client links against exists
     assert os.path.exists(__graft_entry__.build_c_client())
+
+
+def test_copy_order_api_on_the_host():
+    """Setting and reading the order of the whole-model copies needs no GPU: what a plan fixes by itself (small
+    pieces by variable; one replica and row plans by replica), what is left to measurement, and bad arguments."""
+    import ctypes as C
+    lib = su.lib()
+    large = su.shard_plan([1 << 20, 100, 1 << 18], 4, 8)
+    assert su.shard_plan_copy_walk(large, "unshard_format") == "auto"
+    assert su.shard_plan_copy_walk(large, "shard_format_all") == "auto"
+    for walk in ("by_replica", "by_variable", "auto"):
+        su.shard_plan_set_copy_walk(large, walk)
+        assert su.shard_plan_copy_walk(large, "unshard_format") == walk
+    small = su.shard_plan([100] * 300, 64, 8)
+    assert su.shard_plan_copy_walk(small, "unshard_format") == "by_variable"
+    su.shard_plan_set_copy_walk(small, "by_replica")
+    assert su.shard_plan_copy_walk(small, "shard_format_all") == "by_replica"
+    one = su.shard_plan([1 << 20], 1, 8)
+    su.shard_plan_set_copy_walk(one, "by_variable")
+    assert su.shard_plan_copy_walk(one, "unshard_format") == "by_replica"
+    rows = su.shard_plan_rows([64, 3], [128, 5], 4, 8)
+    su.shard_plan_set_copy_walk(rows, "by_variable")
+    assert su.shard_plan_copy_walk(rows, "unshard_format") == "by_replica"
+    out = C.c_int(0)
+    assert lib.shard_plan_set_copy_walk(large.handle, 3) == -1
+    assert lib.shard_plan_set_copy_walk(None, 0) == -1
+    assert lib.shard_plan_copy_walk(large.handle, 2, None, C.byref(out), None) == -1
+    assert lib.shard_plan_copy_walk(large.handle, 0, None, None, None) == -1
+    with pytest.raises(ValueError):
+        su.shard_plan_set_copy_walk(large, "sideways")
+    for p in (large, small, one, rows):
+        p.free()
