@@ -58,6 +58,12 @@ def parse_args():
                          "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads | "
                          "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w | unshard_format_bf16) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
+    ap.add_argument("--separate-tensors", action="store_true",
+                    help="with --stage: every full tensor is an allocation of its own from torch's caching allocator "
+                         "(how a framework holds its parameters; equal-sized tensors then sit a power of two apart) "
+                         "instead of a slice of one flat buffer")
+    ap.add_argument("--copy-order", default="auto", choices=["auto", "by_replica", "by_variable"],
+                    help="with --stage: shard_plan_set_copy_walk before anything runs")
     ap.add_argument("--cold", action="store_true",
                     help="with --stage: flush the memory-side cache (a 1 GiB copy) before every launch of the stage")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -99,9 +105,10 @@ def _time_region(torch, fn, steps):
 class Workbench:
     """Device state of one replica of one configuration."""
 
-    def __init__(self, cfg, N, r, chunk, torch, su, want_full=True):
+    def __init__(self, cfg, N, r, chunk, torch, su, want_full=True, separate=False, copy_order="auto"):
         self.cfg, self.N, self.r, self.torch, self.su = cfg, N, r, torch, su
         self.plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8, None, chunk))
+        su.shard_plan_set_copy_walk(self.plan, copy_order)
         S = self.plan.S
         self.S = S
         self.real = sum(self.plan.real_count(r))
@@ -123,8 +130,12 @@ class Workbench:
             flat_w = torch.empty(cfg.total, dtype=torch.float32, device="cuda")
             self.full_g, self.full_w, pos = [], [], 0
             for n in cfg.numel:
-                self.full_g.append(flat_g[pos:pos + n])
-                self.full_w.append(flat_w[pos:pos + n])
+                if separate:
+                    self.full_g.append(flat_g[pos:pos + n].clone())
+                    self.full_w.append(torch.empty(n, dtype=torch.float32, device="cuda"))
+                else:
+                    self.full_g.append(flat_g[pos:pos + n])
+                    self.full_w.append(flat_w[pos:pos + n])
                 pos += n
             self.full_g = su.FullTensors(self.plan, self.full_g)      # marshalled once, reused every step
             self.full_w = su.FullTensors(self.plan, self.full_w)
@@ -524,7 +535,8 @@ def one_stage(args, torch, su, cfgs):
     needs_full = (name in ("shard_format", "unshard_format", "shard_format_all", "unshard_format_bf16")
                   or name.endswith("_full_grads")
                   or name.endswith("_step"))
-    wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full)
+    wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full, separate=args.separate_tensors,
+                   copy_order=args.copy_order)
     plan, S = wb.plan, wb.S
     hp = wb.hp()
     adam_hp = hp if cfg.optimizer == "adam" else {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8, "weight_decay": 0.0}
@@ -608,7 +620,7 @@ def one_stage(args, torch, su, cfgs):
     print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
                       "total_us": round(us, 2), "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                       "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold),
-                      "copy_orders": copy_orders}))
+                      "separate_tensors": bool(args.separate_tensors), "copy_orders": copy_orders}))
     wb.free()
 
 
