@@ -113,6 +113,31 @@ int main(void) {
     }
     free(a); free(b); hipFree(w2); hipFree(m2);
   }
+  /* the whole-model copy once more in each order: the same bytes in the full tensors */
+  {
+    int order, walk = -1;
+    for (order = SHARD_WALK_BY_REPLICA; order <= SHARD_WALK_BY_VARIABLE; ++order) {
+      CHECK_SU(shard_plan_set_copy_walk(plan, order));
+      CHECK_SU(shard_plan_copy_walk(plan, SHARD_COPY_UNSHARD, (const void* const*)full_out, &walk, NULL));
+      if (walk != order) { fprintf(stderr, "copy order %d reported as %d\n", order, walk); ++failures; }
+      for (i = 0; i < V; ++i) {
+        float* before = (float*)malloc(sizeof(float) * (size_t)numel[i]);
+        float* after = (float*)malloc(sizeof(float) * (size_t)numel[i]);
+        CHECK_HIP(hipMemcpy(before, full_out[i], sizeof(float) * (size_t)numel[i], hipMemcpyDeviceToHost));
+        CHECK_HIP(hipMemset(full_out[i], 0xFF, sizeof(float) * (size_t)numel[i]));
+        CHECK_SU(unshard_format(plan, gathered, 0, SHARD_F32, full_out, SHARD_F32, NULL));
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(after, full_out[i], sizeof(float) * (size_t)numel[i], hipMemcpyDeviceToHost));
+        if (memcmp(before, after, sizeof(float) * (size_t)numel[i]) != 0) {
+          fprintf(stderr, "unshard_format in order %d differs in variable %d\n", order, i);
+          ++failures;
+        }
+        free(before); free(after);
+      }
+    }
+    CHECK_SU(shard_plan_set_copy_walk(plan, SHARD_WALK_AUTO));
+    if (shard_plan_set_copy_walk(plan, 7) != SHARD_EINVAL) ++failures;
+  }
   /* an error path: replica id out of range */
   if (shard_format(plan, N, (const void* const*)full_w, SHARD_F32, w, SHARD_F32, NULL) != SHARD_EINVAL) ++failures;
 
