@@ -379,16 +379,19 @@ def test_random_plans_whole_model_copies():
             rows = su.gathered_empty(plan, tdt)
         else:
             rows = torch.empty((N, max(oplan.S, 1)), dtype=tdt, device=DEV)[:, :oplan.S]
-        rows.fill_(3.0)
-        su.shard_format_all(plan, dev_full, rows)
-        got = to_host(rows.contiguous())
         check = range(N) if N <= 100 else sorted({0, 1, N // 3, N // 2, N - 2, N - 1} | {rnd.randrange(N) for _ in range(10)})
-        for r in check:
-            assert same_bits(got[r], oracle.shard_format(oplan, r, flats)), (case, r)
-        back = [torch.full((n,), 5.0, dtype=tdt, device=DEV) for n in numel]
-        su.unshard_format(plan, rows, back)
-        for i, (o, f) in enumerate(zip(back, flats)):
-            assert same_bits(to_host(o), f), (case, i)
+        want = {r: oracle.shard_format(oplan, r, flats) for r in check}
+        for walk in ("auto", "by_replica", "by_variable"):           # the plan's own choice, then each order forced
+            su.shard_plan_set_copy_walk(plan, walk)
+            rows.fill_(3.0)
+            su.shard_format_all(plan, dev_full, rows)
+            got = to_host(rows.contiguous())
+            for r in check:
+                assert same_bits(got[r], want[r]), (case, walk, r)
+            back = [torch.full((n,), 5.0, dtype=tdt, device=DEV) for n in numel]
+            su.unshard_format(plan, rows, back)
+            for i, (o, f) in enumerate(zip(back, flats)):
+                assert same_bits(to_host(o), f), (case, walk, i)
         plan.free()
 
 
