@@ -139,10 +139,10 @@ WalkChoice choose_walk(shard_plan_t* p, int slot, int op, int src_dtype, int dst
     if (t.calls < 2 || ms < t.best_ms[which]) t.best_ms[which] = ms;
     if (++t.calls == 2 * kWalkTrialRounds) {
       // A call timed on its own still has part of its writes in the memory-side cache when it ends, which
-      // later kernels pay for; that flatters going by variable, which back to back is the slower by 4 to 5 %
-      // on well-placed tensors while both time alike here.  Colliding tensors cost going by replica 10 to 25 %:
-      // only a lead of that kind counts.
-      t.chosen = t.best_ms[1] < 0.95f * t.best_ms[0] ? SHARD_WALK_BY_VARIABLE : SHARD_WALK_BY_REPLICA;
+      // later kernels pay for; that flatters going by variable, which on well-placed tensors leads by 2 % timed
+      // like this and trails by 2 to 5 % back to back.  Colliding tensors cost going by replica 8 to 25 %: only a
+      // lead of that kind counts.
+      t.chosen = t.best_ms[1] < 0.96f * t.best_ms[0] ? SHARD_WALK_BY_VARIABLE : SHARD_WALK_BY_REPLICA;
       return WalkChoice{t.chosen == SHARD_WALK_BY_VARIABLE, nullptr};
     }
   }

@@ -277,6 +277,12 @@ __device__ __forceinline__ void reformat_flat_body(const VarDesc* __restrict__ v
   PackT* rows = (PackT*)packed + vd.off;
   const bool vec = VEC && (reinterpret_cast<uintptr_t>(full) & 15u) == 0;
   const int64_t real = vd.n - p_tile;                        // slots of the tile that exist in the full tensor (may exceed it)
+  if (vec && here == TILE && k0 + TILE <= vd.L && real >= TILE) {
+    // a full tile of real elements inside one piece: two contiguous spans, moved without a branch
+    if (TO_FULL) copy_units<Pol, SRC, DST, U, true, true>((const SrcT*)rows + r0 * row_stride + k0, (DstT*)full, TILE, TILE, TILE);
+    else copy_units<Pol, SRC, DST, U, true, false>((const SrcT*)full, (DstT*)rows + r0 * row_stride + k0, TILE, TILE, TILE);
+    return;
+  }
   if (vec) {
     uint32_t x[U][UNIT];
     int64_t po[U];                                           // offset of the unit in the gathered buffer, -1: none
