@@ -9,13 +9,13 @@
 
 #include "internal.hpp"
 
-#ifndef SU_SPLIT_LOG2
-#define SU_SPLIT_LOG2 26
-#endif
 namespace su {
 
 namespace {
 constexpr int kDefaultChunk = 2048;   // measured best on MI355X for the formatting kernels
+#ifndef SU_SPLIT_LOG2
+#define SU_SPLIT_LOG2 26             // models from 2^26 elements on split shard_format_all by piece size (for measurements)
+#endif
 #ifndef SU_FLAT_WALK_PERCENT
 #define SU_FLAT_WALK_PERCENT 107     // measured cross-over on MI355X (BERT-shaped: between 32 and 64 replicas)
 #endif
