@@ -235,14 +235,20 @@ def test_full_size_format_round_trip(name, N, replicas):
         assert same_bits(to_host(gathered[r]), oracle.shard_format(oplan, r, flats)), r
     # all replicas in one pass (at 64 replicas of the 340 M model: large pieces replica by replica, small ones
     # variable by variable): the same bits as replica after replica, in rows 128 bytes apart too
-    both = su.gathered_empty(plan).fill_(7.0)
-    su.shard_format_all(plan, dev_full, both)
-    assert torch.equal(both.view(torch.int32), gathered.view(torch.int32))
-    del both
+    # ... and in either order of the work items, whichever the plan or its measurement would pick
+    both = su.gathered_empty(plan)
     outs = [torch.empty(n, dtype=torch.float32, device=DEV) for n in numel]
-    su.unshard_format(plan, gathered, outs)
-    for i, (o, f) in enumerate(zip(outs, flats)):
-        assert same_bits(to_host(o), f), i
+    for walk in ("auto", "by_replica", "by_variable"):
+        su.shard_plan_set_copy_walk(plan, walk)
+        both.fill_(7.0)
+        su.shard_format_all(plan, dev_full, both)
+        assert torch.equal(both.view(torch.int32), gathered.view(torch.int32)), walk
+        for o in outs:
+            o.fill_(7.0)
+        su.unshard_format(plan, gathered, outs)
+        for i, (o, f) in enumerate(zip(outs, flats)):
+            assert same_bits(to_host(o), f), (walk, i)
+    del both
     plan.free()
 
 
