@@ -364,3 +364,14 @@ def test_copy_order_api_on_the_host():
         su.shard_plan_set_copy_walk(large, "sideways")
     for p in (large, small, one, rows):
         p.free()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one replica's shard on one GPU; asked for more it says so and exits."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                          timeout=120)
+    assert proc.returncode != 0
+    assert "ONE GPU" in (proc.stdout + proc.stderr)
