@@ -182,15 +182,16 @@ int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride,
  * items: replica by replica (each row of the gathered buffer from end to end) or variable by variable (each
  * full tensor from end to end).  The bytes written are the same; the time is not.  Small pieces (many
  * replicas) go by variable, which shard_plan decides.  With large pieces going by replica is the faster by
- * about 5 %, unless the caller's full tensors lie where the pieces that are in flight together collide
+ * 2 to 6 %, unless the caller's full tensors lie where the pieces that are in flight together collide
  * in memory: equal-sized tensors an exact power of two apart (a framework's allocator places a layer stack's
  * 4 MiB matrices like that) cost that order a quarter of its rate on MI355X, by variable nothing.  Addresses
  * alone do not tell, so the default measures:
  *   SHARD_WALK_AUTO         (default) on a flat plan with large pieces and N > 1, the first 6 calls of each of the
  *                           two copies with a given list of full tensors (and element types, row_stride) are
  *                           timed, 3 in each order in turn, by an event pair on `stream` that a later call reads
- *                           without waiting; from then on the faster order is used while that list stays among the
- *                           plan's 4 cached ones.  Calls on a capturing stream, and calls made while the last timed
+ *                           without waiting; from then on the copy goes by variable if the fastest call in that order
+ *                           beat the fastest by replica by 4 % or more (a call timed alone flatters it by about
+ *                           that much), else by replica, while that list stays among the plan's 4 cached ones.  Calls on a capturing stream, and calls made while the last timed
  *                           one has not finished, go by replica untimed and do not count.  No call blocks.
  *   SHARD_WALK_BY_REPLICA, SHARD_WALK_BY_VARIABLE   always that order (row plans and N = 1 know only the first).
  * shard_plan_copy_walk reports, for `copy` (SHARD_COPY_*) and a host list of full-tensor pointers (may be NULL),
