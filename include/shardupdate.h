@@ -40,9 +40,12 @@
  *    synchronisation, no memset; the two whole-model copies also record and query events on their first calls,
  *    but never on a capturing stream), so a step can be recorded with stream capture.  Scalars passed by
  *    value (replica id, step, hyper-parameters) are frozen into the graph.  The device tables of
- *    full-tensor pointers are cached in the plan's workspace (the 4 most recently used lists); a
- *    recorded graph reads the tables that were resident at capture time, so between capture and the
- *    last replay do not pass more than 3 OTHER lists of full tensors to the same plan.
+ *    full-tensor pointers are cached in the plan's workspace (the 4 most recently used lists), and a
+ *    recorded graph reads, at every replay, the tables its calls used while they were captured.  Those
+ *    tables are therefore pinned: they keep their pointers, other lists share the remaining slots, and a
+ *    call that brings a new list when all 4 are pinned returns SHARD_ESTATE instead of overwriting one.
+ *    shard_plan_release_captured_tables unpins them once the graphs that used the plan are gone;
+ *    shard_plan_bind to another workspace does too (graphs recorded on the old one are void).
  */
 #ifndef SHARDUPDATE_H
 #define SHARDUPDATE_H
@@ -63,8 +66,9 @@ enum {
   SHARD_ENOMEM = -2,   /* host allocation failed, or workspace too small */
   SHARD_EALIGN = -3,   /* a packed-shard device pointer is not 16-byte aligned */
   SHARD_EHIP = -4,     /* the HIP runtime reported an error (no device, launch failure) */
-  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one, or the workspace holds the
-                          intermediate results of another call (shard_update_adafactor_apply) */
+  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one, the workspace holds the
+                          intermediate results of another call (shard_update_adafactor_apply), or every
+                          pointer-table slot is reserved for recorded graphs and the call brings a new list */
 };
 
 enum { SHARD_F32 = 0, SHARD_BF16 = 1 };   /* element types of formatted buffers */
@@ -146,6 +150,11 @@ int shard_plan_real_count(const shard_plan_t* plan, int r, int64_t* real);
 int shard_plan_bind(shard_plan_t* plan, void* device_workspace, size_t bytes, shard_stream_t stream);
 
 void shard_plan_free(shard_plan_t* plan);
+
+/* Pointer tables that calls on a capturing stream have used stay reserved for the recorded graphs (see "HIP
+ * graphs" above).  Call this when those graphs have been destroyed, to let other lists of tensors use the slots
+ * again.  Replaying a graph recorded before this call is then undefined.  Errors: SHARD_EINVAL. */
+int shard_plan_release_captured_tables(shard_plan_t* plan);
 
 /* ------------------------------------------------------------------------------------------
  * shard_format: replica r's zero-padded piece of every variable, packed (Section 4.1: the pad

@@ -204,6 +204,11 @@ def unshard_format(plan: Plan, gathered: torch.Tensor, full_tensors: Sequence[to
     return full_tensors
 
 
+def shard_plan_release_captured_tables(plan: Plan) -> None:
+    """Lets other lists of tensors reuse the pointer tables that captured calls reserved (once their graphs are gone)."""
+    _check(lib().shard_plan_release_captured_tables(plan.handle), "shard_plan_release_captured_tables")
+
+
 COPY_WALKS = {"auto": 0, "by_replica": 1, "by_variable": 2}
 COPIES = {"unshard_format": 0, "shard_format_all": 1}
 

@@ -46,8 +46,20 @@ int check_plan_r(const shard_plan_t* p, int r, bool need_ws) {
   return SHARD_OK;
 }
 
+// Whether work enqueued on `stream` is being recorded into a graph rather than run.
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &status) != hipSuccess) {
+    (void)hipGetLastError();      // e.g. the legacy default stream while another stream captures: nothing is recorded here
+    return false;
+  }
+  return status != hipStreamCaptureStatusNone;
+}
+
 // Returns the device address of a pointer table holding `ptrs`, uploading it into the least
-// recently used slot unless an identical table is already resident.
+// recently used slot unless an identical table is already resident.  A table that a capturing stream uses is
+// pinned: the recorded graph will read that slot at every replay, so no other list may take it (SHARD_ESTATE
+// once every slot is pinned and yet another list arrives).
 int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t stream, const void*** table,
                        int* slot_out = nullptr) {
   const size_t bytes = (size_t)p->V * sizeof(void*);
@@ -55,13 +67,14 @@ int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t str
   for (int s = 0; s < kPtrSlots; ++s)
     if (p->slot_valid[s] && (bytes == 0 || std::memcmp(p->slot_ptrs[s].data(), ptrs, bytes) == 0)) slot = s;
   const void** base = reinterpret_cast<const void**>(p->ws.base + p->ws.ptrs);
+  const bool capturing = stream_is_capturing(stream);
   if (slot < 0) {
     for (int s = 0; s < kPtrSlots && slot < 0; ++s)
       if (!p->slot_valid[s]) slot = s;                       // a free slot first
     if (slot < 0) {
-      slot = 0;                                              // else the least recently used
-      for (int s = 1; s < kPtrSlots; ++s)
-        if (p->slot_age[s] < p->slot_age[slot]) slot = s;
+      for (int s = 0; s < kPtrSlots; ++s)                    // else the least recently used that no graph reads
+        if (!p->slot_pinned[s] && (slot < 0 || p->slot_age[s] < p->slot_age[slot])) slot = s;
+      if (slot < 0) return SHARD_ESTATE;
     }
     const void** dev = base + (size_t)slot * p->V;
     if (p->V > 0) {
@@ -74,6 +87,7 @@ int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t str
     p->slot_valid[slot] = true;
     for (WalkTrial& t : p->walk_trial[slot]) t.restart();    // other tensors: what was measured no longer holds
   }
+  if (capturing) p->slot_pinned[slot] = true;
   p->slot_age[slot] = ++p->clock;
   *table = base + (size_t)slot * p->V;
   if (slot_out) *slot_out = slot;
@@ -116,12 +130,7 @@ WalkChoice choose_walk(shard_plan_t* p, int slot, int op, int src_dtype, int dst
   if (t.chosen != SHARD_WALK_AUTO) return WalkChoice{t.chosen == SHARD_WALK_BY_VARIABLE, nullptr};
   const WalkChoice untimed{false, nullptr};
   // a stream that is being captured takes no event queries: such calls are not part of the trial
-  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) {
-    (void)hipGetLastError();
-    return untimed;
-  }
-  if (capturing != hipStreamCaptureStatusNone) return untimed;
+  if (stream_is_capturing(stream)) return untimed;
   if (t.pending) {
     const hipError_t q = hipEventQuery(t.ev[1]);
     if (q == hipErrorNotReady) {
@@ -491,7 +500,7 @@ int shard_plan_bind(shard_plan_t* p, void* device_workspace, size_t bytes, shard
       return SHARD_EHIP;
   }
   p->ws = ws;
-  for (int i = 0; i < kPtrSlots; ++i) p->slot_valid[i] = false;
+  for (int i = 0; i < kPtrSlots; ++i) p->slot_valid[i] = p->slot_pinned[i] = false;   // graphs recorded on the old workspace are void
   return SHARD_OK;
 }
 
@@ -565,6 +574,12 @@ int unshard_format(shard_plan_t* p, const void* gathered, int64_t row_stride, in
   return hip_status(launch_unshard(p, gathered, row_stride, src_dtype,
                                    reinterpret_cast<void* const*>(const_cast<void**>(table)), dst_dtype, vec,
                                    walk.by_variable, as_stream(stream)));
+}
+
+int shard_plan_release_captured_tables(shard_plan_t* p) {
+  if (p == nullptr) return SHARD_EINVAL;
+  for (bool& pinned : p->slot_pinned) pinned = false;
+  return SHARD_OK;
 }
 
 int shard_plan_set_copy_walk(shard_plan_t* p, int walk) {

@@ -194,6 +194,9 @@ struct shard_plan_s {
   std::vector<const void*> slot_ptrs[su::kPtrSlots];
   uint64_t slot_age[su::kPtrSlots] = {0, 0, 0, 0};
   bool slot_valid[su::kPtrSlots] = {false, false, false, false};
+  // a slot whose table a stream capture has read: a recorded graph reads it at every replay, so it keeps its
+  // pointers until shard_plan_release_captured_tables (or the plan's end)
+  bool slot_pinned[su::kPtrSlots] = {false, false, false, false};
   uint64_t clock = 0;
 
   // Adafactor: which (replica, step) the factors in the workspace belong to; -1 = none yet

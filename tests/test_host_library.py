@@ -356,6 +356,8 @@ def test_copy_order_api_on_the_host():
     su.shard_plan_set_copy_walk(rows, "by_variable")
     assert su.shard_plan_copy_walk(rows, "unshard_format") == "by_replica"
     out = C.c_int(0)
+    assert lib.shard_plan_release_captured_tables(None) == -1
+    su.shard_plan_release_captured_tables(large)             # nothing reserved: a no-op
     assert lib.shard_plan_set_copy_walk(large.handle, 3) == -1
     assert lib.shard_plan_set_copy_walk(None, 0) == -1
     assert lib.shard_plan_copy_walk(large.handle, 2, None, C.byref(out), None) == -1
