@@ -70,7 +70,7 @@ int resident_ptr_table(shard_plan_t* p, const void* const* ptrs, hipStream_t str
   const bool capturing = stream_is_capturing(stream);
   if (slot < 0) {
     for (int s = 0; s < kPtrSlots && slot < 0; ++s)
-      if (!p->slot_valid[s]) slot = s;                       // a free slot first
+      if (!p->slot_valid[s] && !p->slot_pinned[s]) slot = s;  // a free slot first
     if (slot < 0) {
       for (int s = 0; s < kPtrSlots; ++s)                    // else the least recently used that no graph reads
         if (!p->slot_pinned[s] && (slot < 0 || p->slot_age[s] < p->slot_age[slot])) slot = s;
