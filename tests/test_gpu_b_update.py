@@ -618,3 +618,59 @@ def test_shard_longer_than_2_31_slots():
         assert_first_moment_close(to_host(M[a:a + ln]), m1, 1e-3)
     assert not bool(W[n:].view(torch.int32).any()) and not bool(M[n:].view(torch.int32).any())
     plan.free()
+
+
+def _same_where_finite(got, ref, what):
+    """NaN where the oracle has NaN, the same infinities, and the usual bound on everything finite."""
+    assert np.array_equal(np.isnan(got), np.isnan(ref)), what + ": NaN positions"
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf]), what + ": infinities"
+    ok = np.isfinite(ref)
+    assert_weights_close(got[ok], ref[ok], what)
+
+
+def test_non_finite_gradients_stay_inside_their_variable():
+    """A NaN in one variable's gradient and infinities in another's: LAMB, LARS and Adam put NaN exactly where the
+    oracle does (the sums of squares of those variables are NaN, so their trust ratios fall back to 1 on both
+    sides), and the variables next to them in the packed shard are updated as if nothing had happened."""
+    numel, N, seed = [5000, 3000, 4099, 64, 2500], 3, 77
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    ws, gs = gen_weights_grads(seed, numel, 0.02, 1e-3)
+    gs = [g.copy() for g in gs]
+    gs[1][17] = np.nan
+    gs[1][2999] = np.nan
+    gs[2][5] = np.inf
+    gs[2][4098] = -np.inf
+    zeros = [np.zeros_like(w) for w in ws]
+    # LAMB
+    with np.errstate(invalid="ignore"):
+        uw, um, uv, _ = oracle.lamb_unsharded_step(ws, gs, zeros, zeros, LAMB, 1)
+    W = dev_rows(shards_of(oplan, ws)); G = dev_rows(shards_of(oplan, gs)); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    _lamb_all_replicas(plan, oplan, W, G, M, V, LAMB, 1)
+    for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, host_rows(W)))):
+        _same_where_finite(b, a, "lamb w var %d" % i)
+        if i in (0, 3, 4):
+            assert np.all(np.isfinite(b))
+    for r in range(N):
+        assert pads_are_zero(oplan, r, host_rows(W)[r])
+    # LARS
+    with np.errstate(invalid="ignore"):
+        uw, um = oracle.lars_unsharded_step(ws, gs, zeros, LARS)[:2]
+    W = dev_rows(shards_of(oplan, ws)); M = zeros_like_rows(W)
+    _lars_all_replicas(plan, oplan, W, G, M, LARS)
+    for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, host_rows(W)))):
+        _same_where_finite(b, a, "lars w var %d" % i)
+        if i in (0, 3, 4):
+            assert np.all(np.isfinite(b))
+    # Adam: element-wise, so a non-finite gradient touches its own slot only
+    W = dev_rows(shards_of(oplan, ws)); M = zeros_like_rows(W); V = zeros_like_rows(W)
+    for r in range(N):
+        su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], ADAM, 1)
+    got = oracle.unshard_format(oplan, host_rows(W))
+    for i, (w, g) in enumerate(zip(ws, gs)):
+        with np.errstate(invalid="ignore"):
+            ref = oracle.adam_step(w, g, np.zeros_like(w), np.zeros_like(w), ADAM, 1)[0]
+        _same_where_finite(got[i], ref, "adam w var %d" % i)
+        assert int(np.sum(~np.isfinite(got[i]))) == int(np.sum(~np.isfinite(g)))
+    plan.free()
