@@ -674,3 +674,39 @@ def test_non_finite_gradients_stay_inside_their_variable():
         _same_where_finite(got[i], ref, "adam w var %d" % i)
         assert int(np.sum(~np.isfinite(got[i]))) == int(np.sum(~np.isfinite(g)))
     plan.free()
+
+
+@pytest.mark.parametrize("hp,t", [({"beta1": 0.0, "beta2": 0.0}, 1), ({"beta1": 0.0, "beta2": 0.0}, 7),
+                                  ({"beta1": 0.999, "beta2": 0.9}, 2), ({}, 100000), ({"lr": 0.0}, 3),
+                                  ({"eps": 1.0}, 1), ({"weight_decay": 0.5}, 4)])
+def test_adam_and_lamb_at_the_corners_of_the_hyper_parameter_ranges(hp, t):
+    """Both betas zero (no memory), the first moment slower than the second, a step count whose bias corrections
+    have reached 1, a zero learning rate (weights unchanged, moments not), a huge epsilon and a heavy decay: one
+    step from warmed-up moments on every replica against the oracle."""
+    numel, N, seed = [4099, 64, 7000], 2, 55
+    adam = f32_hp(dict(ADAM, **hp))
+    lamb = f32_hp(dict(LAMB, **hp))
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    ws, gs = gen_weights_grads(seed, numel, 0.02, 1e-3)
+    ms = [normal_f32(seed, i, "m", n, 1e-4) for i, n in enumerate(numel)]
+    vs = [np.square(normal_f32(seed, i, "v", n, 1e-3)).astype(np.float32) for i, n in enumerate(numel)]
+    # Adam
+    W, G = dev_rows(shards_of(oplan, ws)), dev_rows(shards_of(oplan, gs))
+    M, V = dev_rows(shards_of(oplan, ms)), dev_rows(shards_of(oplan, vs))
+    for r in range(N):
+        su.shard_update_adam(plan, r, W[r], G[r], M[r], V[r], adam, t)
+    got_w, got_m = oracle.unshard_format(oplan, host_rows(W)), oracle.unshard_format(oplan, host_rows(M))
+    for i in range(len(numel)):
+        rw, rm, rv = oracle.adam_step(ws[i], gs[i], ms[i], vs[i], adam, t)
+        assert_weights_close(got_w[i], rw, "adam w var %d" % i)
+        assert_first_moment_close(got_m[i], rm, 1e-3, 1)
+        if adam["lr"] == 0.0:
+            assert same_bits(got_w[i], ws[i])
+    # LAMB
+    W, M, V = dev_rows(shards_of(oplan, ws)), dev_rows(shards_of(oplan, ms)), dev_rows(shards_of(oplan, vs))
+    _lamb_all_replicas(plan, oplan, W, G, M, V, lamb, t)
+    uw = oracle.lamb_unsharded_step(ws, gs, ms, vs, lamb, t)[0]
+    for i, (a, b) in enumerate(zip(uw, oracle.unshard_format(oplan, host_rows(W)))):
+        assert_weights_close(b, a, "lamb w var %d" % i)
+    plan.free()
