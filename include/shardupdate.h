@@ -236,8 +236,8 @@ int shard_update_momentum(shard_plan_t* plan, int r, float* w, const float* g, f
 /* LAMB, a non-elementwise optimizer on a shard (Section 4.1, "Non-elementwise operators":
  * mask the padding by position, reduce locally, all-reduce the scalars, then apply).
  *   m, v as Adam (no decay folded in);  u = m_hat/(sqrt(v_hat)+eps) + wd_i*w
- *   per variable i, over ALL replicas:  ratio_i = ||w_i|| / ||u_i||  (1 if either norm is 0
- *   or the variable has SHARD_VAR_NO_ADAPT);  w -= lr * ratio_i * u
+ *   per variable i, over ALL replicas:  ratio_i = ||w_i|| / ||u_i||  (1 unless both norms are positive
+ *   numbers, i.e. also when one is 0 or NaN, and 1 if the variable has SHARD_VAR_NO_ADAPT);  w -= lr * ratio_i * u
  * Sums of squares are exchanged as float32 tables [V][2] = {sum w^2, sum u^2} in device memory.
  *
  * shard_update_lamb_partials: phase 1.  Updates m and v, leaves w untouched, and writes this
@@ -267,7 +267,8 @@ int shard_update_lamb(shard_plan_t* plan, int r, float* w, const float* g, float
  * reduce inside the weight update (Section 4.1); same two-phase shape as LAMB.
  *   per variable i over ALL replicas:
  *     local_lr_i = trust_coeff * ||w_i|| / (||g_i|| + wd_i*||w_i|| + eps)
- *     (1 if either norm is 0 or the variable has SHARD_VAR_NO_ADAPT; wd_i = 0 with SHARD_VAR_NO_DECAY)
+ *     (1 unless both norms are positive numbers, or if the variable has SHARD_VAR_NO_ADAPT; wd_i = 0 with
+ *     SHARD_VAR_NO_DECAY)
  *   m = mu*m + lr*local_lr_i*(g + wd_i*w);   w -= m
  * Tables are float32 [V][2] = {sum w^2, sum g^2} in device memory.
  * shard_update_lars_partials reads w and g only; shard_update_lars_apply updates w and m in place
