@@ -14,7 +14,6 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline hipStream_t as_stream(shard_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SHARD_OK : SHARD_EHIP; }
 inline bool dtype_ok(int d) { return d == SHARD_F32 || d == SHARD_BF16; }
-inline size_t dtype_size(int d) { return d == SHARD_F32 ? 4 : 2; }
 
 // Folds the hyper-parameters of an Adam-shaped step into float constants.  Powers and
 // reciprocals are taken in double and rounded once.

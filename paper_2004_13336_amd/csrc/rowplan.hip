@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
       if (lane == 0) row_lds[wave][j] = s;
     }
     __syncthreads();
-    if (threadIdx.x < t.rows_here)
+    if ((int)threadIdx.x < t.rows_here)                 // rows_here is clamped to [0, 8]
       rp[threadIdx.x] = (row_lds[0][threadIdx.x] + row_lds[1][threadIdx.x]) + (row_lds[2][threadIdx.x] + row_lds[3][threadIdx.x]);
   } else {
     // the wavefronts hold different rows of the same columns: row sums are final, column sums are
