@@ -66,9 +66,10 @@ enum {
   SHARD_ENOMEM = -2,   /* host allocation failed, or workspace too small */
   SHARD_EALIGN = -3,   /* a packed-shard device pointer is not 16-byte aligned */
   SHARD_EHIP = -4,     /* the HIP runtime reported an error (no device, launch failure) */
-  SHARD_ESTATE = -5    /* the plan has no bound workspace but the call needs one, the workspace holds the
+  SHARD_ESTATE = -5,   /* the plan has no bound workspace but the call needs one, the workspace holds the
                           intermediate results of another call (shard_update_adafactor_apply), or every
                           pointer-table slot is reserved for recorded graphs and the call brings a new list */
+  SHARD_ELIMIT = -6    /* shard_update_lamb_noalloc: the plan exceeds SHARD_NOALLOC_MAX_CHUNKS or _MAX_VARS */
 };
 
 enum { SHARD_F32 = 0, SHARD_BF16 = 1 };   /* element types of formatted buffers */
@@ -262,6 +263,26 @@ int shard_update_lamb_apply(shard_plan_t* plan, int r, float* w, const float* m,
 int shard_update_lamb(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
                       void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
                       const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream);
+
+/* shard_update_lamb_noalloc: shard_update_lamb for callers that may not allocate device memory and have none to
+ * spare for intermediate sums: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels, same results bit for bit; the only difference is where the
+ * intermediate sums live: the per-chunk sums of phase 1 and the per-variable sums that phase 2 reads are kept in
+ * a fixed array inside the library's code object (2.25 MiB per GPU, held from the library's load to the
+ * process's end) instead of the plan's workspace.  The call allocates nothing and frees nothing; the array's
+ * address is looked up once per device, at the first call with that device current (make that call outside a
+ * stream capture).
+ *   Limits: the plan's n_chunks (shard_plan_info) <= SHARD_NOALLOC_MAX_CHUNKS and V <= SHARD_NOALLOC_MAX_VARS,
+ *   else SHARD_ELIMIT and nothing is launched.  The plan must still be bound (its tables are read).
+ *   Every call on one GPU uses that GPU's one array, whatever the plan or stream: calls that overlap in
+ *   time on one GPU race on it and must be ordered by the caller (one stream, or events).  Nothing in the
+ *   array has to be cleared between calls: each call writes every entry it later reads.
+ * Other errors as shard_update_lamb. */
+#define SHARD_NOALLOC_MAX_CHUNKS 262144
+#define SHARD_NOALLOC_MAX_VARS 32768
+int shard_update_lamb_noalloc(shard_plan_t* plan, int r, float* w, const float* g, float* m, float* v,
+                              void* w_bf16_out, const shard_lamb_hp* hp, int64_t step,
+                              const float* other_replicas_sumsq, float* local_sumsq_out, shard_stream_t stream);
 
 /* LARS, the optimizer of the paper's ResNet-50 runs (Section 6, Table 1) and its example of a
  * reduce inside the weight update (Section 4.1); same two-phase shape as LAMB.

@@ -67,6 +67,7 @@ SIGNATURES = {
     "shard_update_lamb_partials": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
     "shard_update_lamb_apply": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P]),
     "shard_update_lamb": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P, _P]),
+    "shard_update_lamb_noalloc": (C.c_int, [_P, C.c_int, _P, _P, _P, _P, _P, C.POINTER(LambHP), C.c_int64, _P, _P, _P]),
     "shard_update_adam_full_grads": (C.c_int, [_P, C.c_int, _P, C.POINTER(_P), C.c_int, _P, _P, _P, C.POINTER(AdamHP),
                                                C.c_int64, _P]),
     "shard_update_momentum_full_grads": (C.c_int, [_P, C.c_int, _P, C.POINTER(_P), C.c_int, _P, _P,

@@ -286,6 +286,19 @@ def shard_update_lamb(plan: Plan, r: int, w, g, m, v, hp, step: int, other_repli
                                    _stream(stream)), "shard_update_lamb")
 
 
+def shard_update_lamb_noalloc(plan: Plan, r: int, w, g, m, v, hp, step: int, other_replicas_sumsq=None,
+                              local_sumsq_out=None, w_bf16_out=None, stream=None):
+    """shard_update_lamb with the intermediate sums in the library's own static device array (no allocation)."""
+    f = torch.float32
+    _check(lib().shard_update_lamb_noalloc(plan.handle, int(r), _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                           _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"),
+                                           _dev(w_bf16_out, plan.S, torch.bfloat16, "w_bf16_out"),
+                                           C.byref(_hp(LambHP, hp)), int(step),
+                                           _dev(other_replicas_sumsq, 2 * plan.V, f, "other_replicas_sumsq"),
+                                           _dev(local_sumsq_out, 2 * plan.V, f, "local_sumsq_out"),
+                                           _stream(stream)), "shard_update_lamb_noalloc")
+
+
 def shard_update_lamb_partials_full_grads(plan: Plan, r: int, w, full_grads, m, v, hp, step: int, local_sumsq_out,
                                           stream=None):
     """Phase 1 with the gradient read in place from the full tensors (list or FullTensors)."""

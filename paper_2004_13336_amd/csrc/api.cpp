@@ -286,10 +286,12 @@ int lamb_partials_any(shard_plan_t* p, int r, const float* w, const GradArg& g, 
 
 int lamb_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, float* v, void* w_bf16_out,
              const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq, float* local_sumsq_out,
-             shard_stream_t stream) {
+             shard_stream_t stream, bool static_scratch = false) {
   int rc = check_plan_r(p, r, true);
   if (rc != SHARD_OK) return rc;
   if (hp == nullptr) return SHARD_EINVAL;
+  if (static_scratch && (p->chunks.size() > (size_t)SHARD_NOALLOC_MAX_CHUNKS || p->V > SHARD_NOALLOC_MAX_VARS))
+    return SHARD_ELIMIT;
   AdamK k;
   if ((rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k)) != SHARD_OK) return rc;
   if (g.from_full && (rc = check_grad(p, g)) != SHARD_OK) return rc;
@@ -305,8 +307,12 @@ int lamb_any(shard_plan_t* p, int r, float* w, const GradArg& g, float* m, float
   const void** table;
   if ((rc = resolve_grad(p, g, s, &source, &table)) != SHARD_OK) return rc;
   float* sums = reinterpret_cast<float*>(p->ws.base + p->ws.var_sums);
-  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s);
-  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s);
+  float* chunk_sums = nullptr;                                 // the workspace's
+  // Every chunk's pair and every variable's pair is written before it is read, so the static array
+  // needs no clearing between calls.
+  if (static_scratch && static_lamb_scratch(&chunk_sums, &sums) != hipSuccess) return SHARD_EHIP;
+  hipError_t e = launch_lamb_p1(p, r, w, g.shard, source, table, m, v, k, s, chunk_sums);
+  if (e == hipSuccess) e = launch_norm_reduce(p, other_replicas_sumsq, sums, local_sumsq_out, s, chunk_sums);
   if (e == hipSuccess) e = launch_lamb_p2(p, r, w, m, v, w_bf16_out, k, sums, s);
   return hip_status(e);
 }
@@ -384,6 +390,7 @@ const char* shard_strerror(int status) {
     case SHARD_EALIGN: return "packed-shard pointer not 16-byte aligned";
     case SHARD_EHIP: return "HIP runtime error";
     case SHARD_ESTATE: return "plan has no bound workspace, or its workspace holds another call's intermediate results";
+    case SHARD_ELIMIT: return "the plan has more chunks or variables than the library's static scratch array holds";
     default: return "unknown status";
   }
 }
@@ -709,6 +716,13 @@ int shard_update_lamb(shard_plan_t* p, int r, float* w, const float* g, float* m
                       const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq,
                       float* local_sumsq_out, shard_stream_t stream) {
   return lamb_any(p, r, w, shard_grad(g), m, v, w_bf16_out, hp, step, other_replicas_sumsq, local_sumsq_out, stream);
+}
+
+int shard_update_lamb_noalloc(shard_plan_t* p, int r, float* w, const float* g, float* m, float* v, void* w_bf16_out,
+                              const shard_lamb_hp* hp, int64_t step, const float* other_replicas_sumsq,
+                              float* local_sumsq_out, shard_stream_t stream) {
+  return lamb_any(p, r, w, shard_grad(g), m, v, w_bf16_out, hp, step, other_replicas_sumsq, local_sumsq_out, stream,
+                  true);
 }
 
 int shard_update_lamb_full_grads(shard_plan_t* p, int r, float* w, const void* const* full_g, int g_dtype, float* m,

@@ -236,12 +236,17 @@ hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, 
 
 // g_source 0: g is the packed shard gradient; 1 / 2: g_full is the device table of full float32 /
 // bfloat16 gradient tensors and g is unused.
+// chunk_sums (both launchers): where the per-chunk sums go and come from; nullptr = the plan's workspace.
 hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
-                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream);
+                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream,
+                          float* chunk_sums = nullptr);
 // Sums each variable's chunk partials in a fixed order, adds `other` (nullable), writes the totals to
 // `sums_out` (nullable) and `local_out` (nullable, without `other`).
 hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_out, float* local_out,
-                              hipStream_t stream);
+                              hipStream_t stream, const float* chunk_sums = nullptr);
+// The current device's copy of the library's static scratch array (updates.hip): room for the chunk sums of
+// SHARD_NOALLOC_MAX_CHUNKS chunks and the sums of SHARD_NOALLOC_MAX_VARS variables.  Resolved once per device.
+hipError_t static_lamb_scratch(float** chunk_sums, float** var_sums);
 hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, const float* v, void* w16, const AdamK& k,
                           const float* sums, hipStream_t stream);
 

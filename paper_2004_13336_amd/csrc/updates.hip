@@ -14,6 +14,8 @@
 // The file is compiled with -ffp-contract=off: fused multiply-adds appear only where fmaf() is
 // written, so every kernel (vector path, scalar path, sharded or not) performs bit-identical
 // arithmetic per element.
+#include <mutex>
+
 #include "chunk_view.hpp"
 
 #ifndef SU_UNROLL
@@ -876,13 +878,14 @@ hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, 
 }
 
 hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g, int g_source,
-                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream) {
+                          const void* const* g_full, float* m, float* v, const AdamK& k, hipStream_t stream,
+                          float* chunk_sums) {
   if (p->chunks.empty()) return hipSuccess;
   ProfScope ps(p, SHARD_K_LAMB_P1, stream);
   const dim3 grid((unsigned)p->chunks.size());
   const VarDesc* vars = ws_at<VarDesc>(p, p->ws.vars);
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
-  float* cs = ws_at<float>(p, p->ws.chunk_sums);
+  float* cs = chunk_sums ? chunk_sums : ws_at<float>(p, p->ws.chunk_sums);
   const bool vec = p->align % 4 == 0;
 #define SU_LAUNCH_P1(VEC, GS) \
   hipLaunchKernelGGL((lamb_p1_kernel<VEC, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, m, v, cs, r, k)
@@ -898,12 +901,12 @@ hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g
 }
 
 hipError_t launch_norm_reduce(shard_plan_t* p, const float* other, float* sums_out, float* local_out,
-                              hipStream_t stream) {
+                              hipStream_t stream, const float* chunk_sums) {
   if (p->V == 0) return hipSuccess;
   ProfScope ps(p, SHARD_K_NORM_REDUCE, stream);
   const dim3 grid((unsigned)p->V);
   hipLaunchKernelGGL(norm_reduce_kernel, grid, dim3(kBlock), 0, stream, ws_at<VarDesc>(p, p->ws.vars),
-                     ws_at<float>(p, p->ws.chunk_sums), p->V, other, sums_out, local_out);
+                     chunk_sums ? chunk_sums : ws_at<float>(p, p->ws.chunk_sums), p->V, other, sums_out, local_out);
   return hipGetLastError();
 }
 
@@ -1003,6 +1006,35 @@ hipError_t launch_momentum_full_grads(shard_plan_t* p, int r, float* w, int g_so
 #undef SU_LAUNCH
 #undef SU_LAUNCH_GS
   return hipGetLastError();
+}
+
+// ---- the sums of a LAMB step in memory the library owns (shard_update_lamb_noalloc) ------------------
+// One array per GPU, part of the loaded code object, for callers that cannot bring a buffer for the chunk sums
+// and the per-variable sums.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// address the kernels get is resolved once per device and kept.
+namespace {
+static __device__ __align__(256) float scratch[2 * (SHARD_NOALLOC_MAX_CHUNKS + SHARD_NOALLOC_MAX_VARS)];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+float* scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t static_lamb_scratch(float** chunk_sums, float** var_sums) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));       // this device's copy of the array
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  *chunk_sums = scratch_ptr[dev];
+  *var_sums = scratch_ptr[dev] + 2 * (size_t)SHARD_NOALLOC_MAX_CHUNKS;
+  return hipSuccess;
 }
 
 }  // namespace su
