@@ -76,15 +76,11 @@ def _device_normal(n, std, gen, torch):
     return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, std, generator=gen)
 
 
-def _settle_copy(torch, su, plan, copy, full, fn):
-    """Lets the library finish timing its two orders of a whole-model copy (its first calls with a list of full
-    tensors) before anything is measured; returns the order it settled on and the two times in ms."""
-    for _ in range(16):
-        if su.shard_plan_copy_walk(plan, copy, full) != "auto":
-            break
-        fn()
-        torch.cuda.synchronize()
-    walk, (by_replica_ms, by_variable_ms) = su.shard_plan_copy_walk(plan, copy, full, with_times=True)
+def _settle_copy(torch, su, plan, copy, gathered, full):
+    """Has the library measure its two orders of a whole-model copy on these tensors (a set-up call that runs the
+    copy and waits) before anything is timed; returns the order it fixed and the two times in ms per launch."""
+    walk, (by_replica_ms, by_variable_ms) = su.shard_plan_tune_copy_walk(plan, copy, gathered, full)
+    torch.cuda.synchronize()
     return {"walk": walk, "timed_ms_by_replica": round(by_replica_ms, 4), "timed_ms_by_variable": round(by_variable_ms, 4)}
 
 
@@ -151,16 +147,13 @@ class Workbench:
         return {k: float(np.float32(v)) for k, v in self.cfg.hyper.items()}
 
     def settle_copies(self, format_all=False):
-        """The library times its two orders of a whole-model copy on the first calls with a list of tensors;
-        this makes those calls, so that what is measured afterwards is the order it settled on."""
+        """shard_plan_tune_copy_walk for the copies that are about to be timed, on the real buffers."""
         su, plan = self.su, self.plan
         if self.full_w is None:
             return {}
-        out = {"unshard_format": _settle_copy(self.torch, su, plan, "unshard_format", self.full_w,
-                                              lambda: su.unshard_format(plan, self.gathered, self.full_w))}
+        out = {"unshard_format": _settle_copy(self.torch, su, plan, "unshard_format", self.gathered, self.full_w)}
         if format_all:
-            out["shard_format_all"] = _settle_copy(self.torch, su, plan, "shard_format_all", self.full_g,
-                                                   lambda: su.shard_format_all(plan, self.full_g, self.gathered))
+            out["shard_format_all"] = _settle_copy(self.torch, su, plan, "shard_format_all", self.gathered, self.full_g)
             self.gathered.normal_(0.0, self.cfg.weight_std, generator=self.gen)    # weights again, not gradients
         return out
 
@@ -603,7 +596,7 @@ def one_stage(args, torch, su, cfgs):
     fn, kernels, nbytes = stages[name]
     copy_orders = wb.settle_copies(format_all=name == "shard_format_all") if needs_full else {}
     if name == "unshard_format_bf16":
-        copy_orders = {"unshard_format": _settle_copy(torch, su, plan, "unshard_format", full16, lambda: fn(0))}
+        copy_orders = {"unshard_format": _settle_copy(torch, su, plan, "unshard_format", g16, full16)}
     # --cold: a 1 GiB device copy between launches of the stage, so that nothing of the previous launch is
     # left in the 256 MB memory-side cache (between two real steps a forward and a backward pass run); the
     # event pairs time the library's kernels only

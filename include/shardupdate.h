@@ -37,8 +37,7 @@
  *  - A plan is not thread-safe, and calls that use one plan must be ordered on one
  *    stream (or otherwise synchronised by the caller): they share the plan's workspace.
  *  - HIP graphs: the formatting and update calls only launch kernels (no allocation, no
- *    synchronisation, no memset; the two whole-model copies also record and query events on their first calls,
- *    but never on a capturing stream), so a step can be recorded with stream capture.  Scalars passed by
+ *    synchronisation, no memset, no events), so a step can be recorded with stream capture.  Scalars passed by
  *    value (replica id, step, hyper-parameters) are frozen into the graph.  The device tables of
  *    full-tensor pointers are cached in the plan's workspace (the 4 most recently used lists), and a
  *    recorded graph reads, at every replay, the tables its calls used while they were captured.  Those
@@ -46,6 +45,11 @@
  *    call that brings a new list when all 4 are pinned returns SHARD_ESTATE instead of overwriting one.
  *    shard_plan_release_captured_tables unpins them once the graphs that used the plan are gone;
  *    shard_plan_bind to another workspace does too (graphs recorded on the old one are void).
+ *    A list that a captured call brings for the first time is uploaded by a kernel recorded into that graph
+ *    (no eager warm-up call is needed); until an eager call has brought the same list, eager calls do not
+ *    use that table but upload one of their own into another slot.  shard_profile_* timing skips launches on
+ *    a capturing stream; do not enable it while another stream of the same thread is being captured in
+ *    the global capture mode (event calls are not allowed then).
  */
 #ifndef SHARDUPDATE_H
 #define SHARDUPDATE_H
@@ -195,22 +199,31 @@ int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride,
  * 2 to 6 %, unless the caller's full tensors lie where the pieces that are in flight together collide
  * in memory: equal-sized tensors an exact power of two apart (a framework's allocator places a layer stack's
  * 4 MiB matrices like that) cost that order a quarter of its rate on MI355X, by variable nothing.  Addresses
- * alone do not tell, so the default measures:
- *   SHARD_WALK_AUTO         (default) on a flat plan with large pieces and N > 1, the first 6 calls of each of the
- *                           two copies with a given list of full tensors (and element types, row_stride) are
- *                           timed, 3 in each order in turn, by an event pair on `stream` that a later call reads
- *                           without waiting; from then on the copy goes by variable if the fastest call in that order
- *                           beat the fastest by replica by 4 % or more (a call timed alone flatters it by about
- *                           that much), else by replica, while that list stays among the plan's 4 cached ones.  Calls on a capturing stream, and calls made while the last timed
- *                           one has not finished, go by replica untimed and do not count.  No call blocks.
+ * alone do not tell, and the library measures nothing behind the caller's back: which kernel a call launches
+ * never depends on timing, and the two copies record and query no events.
+ *   SHARD_WALK_AUTO         (default) small pieces go by variable; large pieces (a flat plan, N > 1) go by replica
+ *                           unless shard_plan_tune_copy_walk has measured this list of tensors and found by
+ *                           variable faster.
  *   SHARD_WALK_BY_REPLICA, SHARD_WALK_BY_VARIABLE   always that order (row plans and N = 1 know only the first).
+ * shard_plan_tune_copy_walk: measures both orders of `copy` (SHARD_COPY_UNSHARD: reads `gathered`, writes the full
+ *   tensors; SHARD_COPY_FORMAT_ALL: reads the full tensors, writes `gathered`) on the caller's real buffers, and
+ *   fixes the order for later calls with the same list of full tensors, element types and row_stride, while that
+ *   list stays among the plan's 4 cached ones.  It RUNS the copy 8 times (the destination is overwritten with what
+ *   the copy writes), one untimed and three timed launches back to back in each order, and WAITS for them
+ *   (hipEventSynchronize): a set-up call, not for the training loop, and refused on a capturing stream
+ *   (SHARD_ESTATE).  By variable is taken if it is at least 2 % faster per launch, else by replica.  Where the
+ *   order is already fixed (small pieces, a row plan, N = 1, shard_plan_set_copy_walk) nothing is launched.
+ *   walk_out (may be NULL) receives the order, best_ms_out (host, 2 floats, may be NULL) the milliseconds per
+ *   launch by replica and by variable.  Arguments and errors otherwise as the copy itself.
  * shard_plan_copy_walk reports, for `copy` (SHARD_COPY_*) and a host list of full-tensor pointers (may be NULL),
- * the order the next such call takes: a fixed one, or SHARD_WALK_AUTO while the measurement is still under way
- * or the list is not cached; best_ms_out (host, 2 floats, may be NULL) receives the fastest timed call by replica
- * and by variable so far in milliseconds, 0 where there is none.  Errors: SHARD_EINVAL. */
+ *   the order the next such call takes (never SHARD_WALK_AUTO); best_ms_out (host, 2 floats, may be NULL) receives
+ *   what shard_plan_tune_copy_walk measured for that list, 0 if it has not been called.  Errors: SHARD_EINVAL. */
 int shard_plan_set_copy_walk(shard_plan_t* plan, int walk);
 int shard_plan_copy_walk(const shard_plan_t* plan, int copy, const void* const* full_ptrs, int* walk_out,
                          float* best_ms_out);
+int shard_plan_tune_copy_walk(shard_plan_t* plan, int copy, void* gathered, int64_t row_stride, int gathered_dtype,
+                              void* const* full_ptrs, int full_dtype, shard_stream_t stream, int* walk_out,
+                              float* best_ms_out);
 
 /* ------------------------------------------------------------------------------------------
  * Fused optimizer updates on one packed shard (Section 2.2: read gradient, weight and

@@ -103,6 +103,8 @@ SIGNATURES = {
     "shard_plan_release_captured_tables": (C.c_int, [_P]),
     "shard_plan_set_copy_walk": (C.c_int, [_P, C.c_int]),
     "shard_plan_copy_walk": (C.c_int, [_P, C.c_int, _P, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
+    "shard_plan_tune_copy_walk": (C.c_int, [_P, C.c_int, _P, C.c_int64, C.c_int, C.POINTER(_P), C.c_int, _P,
+                                            C.POINTER(C.c_int), C.POINTER(C.c_float)]),
 }
 
 

@@ -214,17 +214,17 @@ COPIES = {"unshard_format": 0, "shard_format_all": 1}
 
 
 def shard_plan_set_copy_walk(plan: Plan, walk: str) -> None:
-    """Order of the work items of shard_format_all and unshard_format: "auto" (measured on the first calls),
-    "by_replica" or "by_variable"."""
+    """Order of the work items of shard_format_all and unshard_format: "auto" (small pieces by variable, large ones by
+    replica unless shard_plan_tune_copy_walk found otherwise), "by_replica" or "by_variable"."""
     if walk not in COPY_WALKS:
         raise ValueError("walk must be one of %s" % sorted(COPY_WALKS))
     _check(lib().shard_plan_set_copy_walk(plan.handle, COPY_WALKS[walk]), "shard_plan_set_copy_walk")
 
 
 def shard_plan_copy_walk(plan: Plan, copy: str, full_tensors=None, with_times: bool = False):
-    """The order the next `copy` ("unshard_format" or "shard_format_all") with these full tensors takes;
-    "auto" while it is still being measured.  with_times: also the fastest timed call in each order so far
-    (by replica, by variable) in ms."""
+    """The order the next `copy` ("unshard_format" or "shard_format_all") with these full tensors takes.
+    with_times: also what shard_plan_tune_copy_walk measured for them (ms per launch by replica, by variable;
+    zeros if it has not been called)."""
     if copy not in COPIES:
         raise ValueError("copy must be one of %s" % sorted(COPIES))
     arr = None if full_tensors is None else _full_ptrs(plan, full_tensors, "full_tensors")[0]
@@ -233,6 +233,21 @@ def shard_plan_copy_walk(plan: Plan, copy: str, full_tensors=None, with_times: b
     _check(lib().shard_plan_copy_walk(plan.handle, COPIES[copy], arr, C.byref(out), best), "shard_plan_copy_walk")
     walk = {v: k for k, v in COPY_WALKS.items()}[out.value]
     return (walk, (best[0], best[1])) if with_times else walk
+
+
+def shard_plan_tune_copy_walk(plan: Plan, copy: str, gathered: torch.Tensor, full_tensors, stream=None):
+    """Measures both orders of `copy` on these buffers (the copy really runs, 8 times, and is waited for) and fixes
+    the order for later calls with the same tensors.  Returns (order, (ms by replica, ms by variable))."""
+    if copy not in COPIES:
+        raise ValueError("copy must be one of %s" % sorted(COPIES))
+    arr, full_dtype = _full_ptrs(plan, full_tensors, "full_tensors")
+    ptr, stride = _rows(plan, gathered, "gathered")
+    out = C.c_int(-1)
+    best = (C.c_float * 2)()
+    _check(lib().shard_plan_tune_copy_walk(plan.handle, COPIES[copy], ptr, int(stride), _DTYPES[gathered.dtype], arr,
+                                           _DTYPES[full_dtype], _stream(stream), C.byref(out), best),
+           "shard_plan_tune_copy_walk")
+    return {v: k for k, v in COPY_WALKS.items()}[out.value], (best[0], best[1])
 
 
 def _hp(cls, hp: Dict[str, float]):

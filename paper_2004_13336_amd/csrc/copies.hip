@@ -10,42 +10,22 @@
 
 #include "chunk_view.hpp"
 
-// Cache policy per kernel, as a 3-bit mask: 4 = non-temporal loads, 1 = non-temporal stores (2 is unused
-// here: nothing is updated in place).  The defaults are the measured best on MI355X, scored on the whole
-// step (format, update, unshard), since a kernel's policy decides what the next kernel finds in the caches.
-#ifndef SU_NT_FORMAT
-#define SU_NT_FORMAT 4
-#endif
-#ifndef SU_NT_FORMAT_ALL
-#define SU_NT_FORMAT_ALL 5    // all-replica formatting: the output goes to a collective, not to the next kernel
-#endif
-#ifndef SU_NT_UNSHARD
-#define SU_NT_UNSHARD 5
-#endif
-#ifndef SU_COPY_BLOCK
-#define SU_COPY_BLOCK 256     // threads per workgroup of the formatting kernels
-#endif
-// Units per thread of the formatting kernels, all loaded before the first store.  One replica's
-// formatting (a few hundred MB, partly served by the memory-side cache) measures fastest with 2;
-// the whole-model copies (unshard, all-replica formatting) with 1.
-#ifndef SU_FORMAT_UNROLL
-#define SU_FORMAT_UNROLL 2
-#endif
-#ifndef SU_UNSHARD_UNROLL
-#define SU_UNSHARD_UNROLL 1
-#endif
-#ifndef SU_FORMAT_ALL_UNROLL
-#define SU_FORMAT_ALL_UNROLL 1
-#endif
-
 namespace su {
 namespace {
 
-constexpr int kCopyBlock = SU_COPY_BLOCK;
+constexpr int kCopyBlock = 256;    // threads per workgroup of the formatting kernels (128 or 64: -1 to -7 %; 512 and 1024: -3 to -30 %)
 
-typedef Policy<SU_NT_FORMAT> PolFormat;
-typedef Policy<SU_NT_UNSHARD> PolUnshard;
-typedef Policy<SU_NT_FORMAT_ALL> PolFormatAll;
+// Cache policy per kernel, as a 3-bit mask: 4 = non-temporal loads, 1 = non-temporal stores (2 is unused
+// here: nothing is updated in place).  Measured best on MI355X, scored on the whole step (format, update,
+// unshard), since a kernel's policy decides what the next kernel finds in the caches.
+typedef Policy<4> PolFormat;
+typedef Policy<5> PolUnshard;
+typedef Policy<5> PolFormatAll;    // all-replica formatting: the output goes to a collective, not to the next kernel
+
+// Units per thread of the formatting kernels, all loaded before the first store.  One replica's
+// formatting (a few hundred MB, partly served by the memory-side cache) measures fastest with 2;
+// the whole-model copies (unshard, all-replica formatting) with 1.
+constexpr int kFormatUnroll = 2, kUnshardUnroll = 1, kFormatAllUnroll = 1;
 
 // ---- pointer table --------------------------------------------------------------------------------
 // Device pointer tables are written by a kernel that carries the pointers as launch arguments:
@@ -342,7 +322,7 @@ __global__ __launch_bounds__(kCopyBlock) void unshard_flat_kernel(const VarDesc*
                                                               const FullChunk* __restrict__ fchunks,
                                                               const void* const* __restrict__ ptrs, void* gathered,
                                                               int64_t row_stride, int tiles_per_chunk) {
-  reformat_flat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, fchunks, ptrs, gathered, row_stride, tiles_per_chunk);
+  reformat_flat_body<PolUnshard, SRC, DST, kUnshardUnroll, VEC, true>(vars, fchunks, ptrs, gathered, row_stride, tiles_per_chunk);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -350,7 +330,7 @@ __global__ __launch_bounds__(kCopyBlock) void format_all_flat_kernel(const VarDe
                                                                  const FullChunk* __restrict__ fchunks,
                                                                  const void* const* __restrict__ ptrs, void* out,
                                                                  int64_t row_stride, int tiles_per_chunk) {
-  reformat_flat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, fchunks, ptrs, out, row_stride, tiles_per_chunk);
+  reformat_flat_body<PolFormatAll, SRC, DST, kFormatAllUnroll, VEC, false>(vars, fchunks, ptrs, out, row_stride, tiles_per_chunk);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -359,7 +339,7 @@ __global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __res
                                                         const void* const* __restrict__ ptrs, void* out, int r0,
                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk,
                                                         int wg_per_replica) {
-  reformat_body<PolFormat, SRC, DST, SU_FORMAT_UNROLL, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
+  reformat_body<PolFormat, SRC, DST, kFormatUnroll, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -368,7 +348,7 @@ __global__ __launch_bounds__(kCopyBlock) void format_all_kernel(const VarDesc* _
                                                             const void* const* __restrict__ ptrs, void* out,
                                                             int64_t row_stride, int n_chunks, int tiles_per_chunk,
                                                             int wg_per_replica) {
-  reformat_body<PolFormatAll, SRC, DST, SU_FORMAT_ALL_UNROLL, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
+  reformat_body<PolFormatAll, SRC, DST, kFormatAllUnroll, VEC, false>(vars, chunks, ptrs, out, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -377,7 +357,7 @@ __global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const VarDesc* __re
                                                          const void* const* __restrict__ ptrs, void* gathered,
                                                          int64_t row_stride, int n_chunks, int tiles_per_chunk,
                                                          int wg_per_replica) {
-  reformat_body<PolUnshard, SRC, DST, SU_UNSHARD_UNROLL, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
+  reformat_body<PolUnshard, SRC, DST, kUnshardUnroll, VEC, true>(vars, chunks, ptrs, gathered, 0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 }  // namespace
@@ -401,21 +381,21 @@ namespace {
 // variable, the empty second tile of a short chunk) sit at the same places of every replica's sequence.  With an
 // even number of workgroups per replica the same XCDs would get them replica after replica and run out of work
 // while the others are still busy (measured: 5 % on the 1.5 G-parameter list at 128 replicas); an odd count moves
-// the sequence on by one XCD per replica.  SU_WG_PAD (0: off) exists for measurements.
-#ifndef SU_WG_PAD
-#define SU_WG_PAD 1
-#endif
+// the sequence on by one XCD per replica.
 inline int odd_count(int64_t wgs, int replicas) {
-  if (SU_WG_PAD && replicas > 1 && (wgs & 1) == 0 && (wgs + 1) * replicas <= 0x7FFFFFFF) return (int)wgs + 1;
+  if (replicas > 1 && (wgs & 1) == 0 && (wgs + 1) * replicas <= 0x7FFFFFFF) return (int)wgs + 1;
   return (int)wgs;
 }
+
+// LDS reserved per workgroup (never touched) to cap the workgroups resident per CU: 0 = no cap.
+constexpr unsigned kLdsFormat = 0, kLdsUnshard = 0, kLdsFormatAll = 0, kLdsUnshardFlat = 0, kLdsFormatAllFlat = 0;
 
 // MODE: 0 = shard_format (one replica), 1 = unshard_format, 2 = shard_format_all
 template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
                        bool vec, bool by_variable, hipStream_t stream) {
   const int n_chunks = (int)p->chunks.size();
-  constexpr int U = MODE == 0 ? SU_FORMAT_UNROLL : (MODE == 1 ? SU_UNSHARD_UNROLL : SU_FORMAT_ALL_UNROLL);
+  constexpr int U = MODE == 0 ? kFormatUnroll : (MODE == 1 ? kUnshardUnroll : kFormatAllUnroll);
   constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
   // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31, and a tile is at least 1024 slots
@@ -435,8 +415,8 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
       const int per_major = odd_count((int64_t)n_major * tiles_per_chunk, replicas);
       const dim3 gm((unsigned)((int64_t)per_major * replicas));
       if (n_major > 0) {
-        if (vec) hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
-        else hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), gm, b, 0, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
+        if (vec) hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), gm, b, kLdsFormatAll, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
+        else hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), gm, b, kLdsFormatAll, stream, vars, major, tab, packed, stride, n_major, tiles_per_chunk, per_major);
       }
       // no split (large pieces throughout, this order picked by measurement): every item variable by variable
       const bool split = p->flat_copies;
@@ -444,35 +424,35 @@ void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const*
       const size_t n_small = split ? p->small_full_chunks.size() : p->full_chunks.size();
       const dim3 gs((unsigned)((int64_t)n_small * tiles_per_chunk));
       if (n_small > 0) {
-        if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
-        else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gs, b, 0, stream, vars, small, tab, packed, stride, tiles_per_chunk);
+        if (vec) hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, true>), gs, b, kLdsFormatAllFlat, stream, vars, small, tab, packed, stride, tiles_per_chunk);
+        else hipLaunchKernelGGL((format_all_flat_kernel<SRC, DST, false>), gs, b, kLdsFormatAllFlat, stream, vars, small, tab, packed, stride, tiles_per_chunk);
       }
     } else if constexpr (MODE == 1) {
-      if (vec) hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, true>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
-      else hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, false>), gf, b, 0, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+      if (vec) hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, true>), gf, b, kLdsUnshardFlat, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
+      else hipLaunchKernelGGL((unshard_flat_kernel<SRC, DST, false>), gf, b, kLdsUnshardFlat, stream, vars, fchunks, tab, packed, stride, tiles_per_chunk);
     }
     return;
   }
   if constexpr (MODE == 2) {
     if (vec)
-      hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+      hipLaunchKernelGGL((format_all_kernel<SRC, DST, true>), g, b, kLdsFormatAll, stream, vars, chunks, tab, packed, stride,
                          n_chunks, tiles_per_chunk, per);
     else
-      hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+      hipLaunchKernelGGL((format_all_kernel<SRC, DST, false>), g, b, kLdsFormatAll, stream, vars, chunks, tab, packed, stride,
                          n_chunks, tiles_per_chunk, per);
   } else if constexpr (MODE == 1) {
     if (vec)
-      hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, stride, n_chunks,
+      hipLaunchKernelGGL((unshard_kernel<SRC, DST, true>), g, b, kLdsUnshard, stream, vars, chunks, tab, packed, stride, n_chunks,
                          tiles_per_chunk, per);
     else
-      hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, stride,
+      hipLaunchKernelGGL((unshard_kernel<SRC, DST, false>), g, b, kLdsUnshard, stream, vars, chunks, tab, packed, stride,
                          n_chunks, tiles_per_chunk, per);
   } else {
     if (vec)
-      hipLaunchKernelGGL((format_kernel<SRC, DST, true>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
+      hipLaunchKernelGGL((format_kernel<SRC, DST, true>), g, b, kLdsFormat, stream, vars, chunks, tab, packed, r0, stride,
                          n_chunks, tiles_per_chunk, per);
     else
-      hipLaunchKernelGGL((format_kernel<SRC, DST, false>), g, b, 0, stream, vars, chunks, tab, packed, r0, stride,
+      hipLaunchKernelGGL((format_kernel<SRC, DST, false>), g, b, kLdsFormat, stream, vars, chunks, tab, packed, r0, stride,
                          n_chunks, tiles_per_chunk, per);
   }
 }

@@ -142,24 +142,20 @@ struct ProfRecord {
   int kernel;
 };
 
-// Which of the two orders a whole-model copy takes for one cached pointer table, found by timing both on the
-// first calls (SHARD_WALK_AUTO).  One per (pointer slot, operation); starts again when the slot gets other
-// pointers or the call other element types or another row stride.
-constexpr int kWalkTrialRounds = 3;  // timed calls per order
+// Which of the two orders a whole-model copy takes for one cached pointer table, once shard_plan_tune_copy_walk
+// has measured both.  One per (pointer slot, operation); void when the slot gets other pointers, and only valid
+// for the element types and row stride it was measured with.
+constexpr int kWalkTuneLaunches = 3;  // timed launches per order
 struct WalkTrial {
   int src_dtype = -1, dst_dtype = -1;
   int64_t row_stride = -1;
-  int calls = 0;                      // timed calls read so far; even ones went by replica, odd ones by variable
-  float best_ms[2] = {0.0f, 0.0f};    // fastest call by replica, by variable
-  int chosen = SHARD_WALK_AUTO;       // SHARD_WALK_AUTO while the trial runs
-  bool pending = false;               // ev[] bracket a timed call whose time has not been read yet
-  hipEvent_t ev[2] = {nullptr, nullptr};   // created at the first timed call, destroyed with the plan
+  float best_ms[2] = {0.0f, 0.0f};    // per launch: by replica, by variable
+  int chosen = SHARD_WALK_AUTO;       // SHARD_WALK_AUTO: not measured
   void restart() {
     src_dtype = dst_dtype = -1;
     row_stride = -1;
-    calls = 0;
+    best_ms[0] = best_ms[1] = 0.0f;
     chosen = SHARD_WALK_AUTO;
-    pending = false;
   }
 };
 
@@ -197,6 +193,8 @@ struct shard_plan_s {
   // a slot whose table a stream capture has read: a recorded graph reads it at every replay, so it keeps its
   // pointers until shard_plan_release_captured_tables (or the plan's end)
   bool slot_pinned[su::kPtrSlots] = {false, false, false, false};
+  // false: the slot's only upload was recorded by a stream capture, so the device may not hold the table yet
+  bool slot_on_device[su::kPtrSlots] = {false, false, false, false};
   uint64_t clock = 0;
 
   // Adafactor: which (replica, step) the factors in the workspace belong to; -1 = none yet
@@ -283,7 +281,10 @@ hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, floa
 hipError_t launch_adafactor_apply(shard_plan_t* p, int r, float* w, const float* g, const float* table_global,
                                   const float* usq_global, void* w16, const AdafactorK& k, hipStream_t stream);
 
-// RAII helper: records an event pair around a launch when profiling is on.
+// Whether work enqueued on `stream` is being recorded into a graph rather than run (profile.cpp).
+bool stream_is_capturing(hipStream_t stream);
+
+// RAII helper: records an event pair around a launch when profiling is on and the stream is not capturing.
 struct ProfScope {
   shard_plan_t* p;
   hipStream_t stream;

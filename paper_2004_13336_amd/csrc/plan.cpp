@@ -13,13 +13,8 @@ namespace su {
 
 namespace {
 constexpr int kDefaultChunk = 2048;   // measured best on MI355X for the formatting kernels
-#ifndef SU_SPLIT_LOG2
-#define SU_SPLIT_LOG2 26             // models from 2^26 elements on split shard_format_all by piece size (for measurements)
-#endif
-#ifndef SU_FLAT_WALK_PERCENT
-#define SU_FLAT_WALK_PERCENT 107     // measured cross-over on MI355X (BERT-shaped: between 32 and 64 replicas)
-#endif
-constexpr int kFlatWalkPercent = SU_FLAT_WALK_PERCENT;
+constexpr int kSplitLog2 = 26;        // models from 2^26 elements on split shard_format_all by piece size
+constexpr int kFlatWalkPercent = 107; // measured cross-over on MI355X (BERT-shaped: between 32 and 64 replicas)
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 }  // namespace
@@ -129,7 +124,7 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       if (p->flat_copies) {
         // a model that fits the memory-side cache copies in tens of microseconds: a second launch costs more
         // than the split gains (ResNet-50-shaped, 32 replicas: 39 against 37 us)
-        const bool split = p->total >= ((int64_t)1 << SU_SPLIT_LOG2);
+        const bool split = p->total >= ((int64_t)1 << kSplitLog2);
         size_t fc = 0;
         for (int i = 0; i < V; ++i) {
           const bool big = split && p->L[i] >= chunk;

@@ -21,19 +21,14 @@
 // non-temporally; Adafactor's gradient is read by three kernels in a row and stays cacheable (one
 // replica's piece fits the 256 MB memory-side cache), its weights are loaded non-temporally and stored
 // non-temporally by the last kernel.
-#ifndef SU_NT_ROWCOL
-#define SU_NT_ROWCOL 1     // 1: non-temporal loads in shard_reduce_sq_rows_cols
-#endif
-#ifndef SU_NT_ADAFACTOR
-#define SU_NT_ADAFACTOR 3  // mask of the Adafactor kernels (4: g loads, 2: w loads, 1: stores)
-#endif
 
 namespace su {
 namespace {
 
 constexpr int kWaves = kBlock / 64;
 constexpr int kRowsPerWave = kRowBlock / kWaves;     // 8 rows per wavefront: one batch of independent loads
-typedef Policy<SU_NT_ADAFACTOR> PolAf;
+constexpr bool kRowColNt = true;   // non-temporal loads in shard_reduce_sq_rows_cols
+typedef Policy<3> PolAf;           // mask of the Adafactor kernels (4: g loads, 2: w loads, 1: stores)
 
 // This thread's part of a tile item.  Tall tile: wavefront w takes rows 8w .. 8w+7, lane l the columns
 // 4l .. 4l+3 (or the single column l).  Flat tile: all wavefronts take the same 8 rows, wavefront w the
@@ -143,10 +138,10 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
     if (j < t.live_here && t.col_ok) {
       const int64_t o = (int64_t)j * t.v.cols;
       if (t.vec) {
-        val[j] = ld4<(SU_NT_ROWCOL != 0) && !WITH_W>(base + o);
+        val[j] = ld4<kRowColNt && !WITH_W>(base + o);
         if constexpr (WITH_W) wv[j] = ld4<false>(ybase + o);
       } else {
-        val[j].x = ld<(SU_NT_ROWCOL != 0) && !WITH_W>(base + o);
+        val[j].x = ld<kRowColNt && !WITH_W>(base + o);
         if constexpr (WITH_W) wv[j].x = ybase[o];
       }
     }

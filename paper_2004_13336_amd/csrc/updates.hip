@@ -18,66 +18,33 @@
 
 #include "chunk_view.hpp"
 
-#ifndef SU_UNROLL
-#define SU_UNROLL 2        // chunk-table kernels: 128-bit accesses per thread per stream in flight; 2 makes a tile the
-                           // default 2048-slot chunk, so that whole chunks run the branch-free path (4: phase 1 +5 %)
-#endif
-#ifndef SU_ADAM_UNROLL
-#define SU_ADAM_UNROLL 1       // flat Adam kernel: the same (1: -2 to -5 % against 4 on shards of 12 M to 1.5 G slots)
-#endif
-#ifndef SU_MOMENTUM_UNROLL
-#define SU_MOMENTUM_UNROLL 2   // flat momentum kernel
-#endif
-// Cache policy per kernel family, as a 3-bit mask: 4 = non-temporal loads of streams that are only
-// read, 2 = non-temporal loads of streams the same thread writes back in place, 1 = non-temporal
-// stores.  The defaults are the measured best on MI355X for each access pattern.
-#ifndef SU_NT_ADAM
-#define SU_NT_ADAM 3
-#endif
-#ifndef SU_NT_MOMENTUM
-#define SU_NT_MOMENTUM 3
-#endif
-#ifndef SU_NT_LAMB
-#define SU_NT_LAMB 6
-#endif
-#ifndef SU_NT_LAMB_P2
-#define SU_NT_LAMB_P2 5    // phase 2 of LAMB: w is loaded through the caches and stored past them (measured on the
-                           // whole step: the unshard that follows gains as much as phase 2 itself)
-#endif
-#ifndef SU_NT_LARS
-#define SU_NT_LARS 6
-#endif
-#ifndef SU_NT_LARS_P2
-#define SU_NT_LARS_P2 5    // phase 2 of LARS: as LAMB's (w and m loaded through the caches): 122 -> 116 us on 25.6 M slots
-#endif
-#ifndef SU_P1_REVERSE
-#define SU_P1_REVERSE 0        // 1: LAMB phase 1 walks the chunk table from the end
-#endif
-#ifndef SU_P2_REVERSE
-#define SU_P2_REVERSE 1        // 1: LAMB phase 2 walks it in the opposite direction to phase 1's default
-#endif
-#ifndef SU_GRID_CAP
-#define SU_GRID_CAP 0      // >0: flat kernels launch at most this many workgroups and loop
-#endif
-
 namespace su {
 namespace {
 
-constexpr int kUnroll = SU_UNROLL;
-constexpr int kAdamUnroll = SU_ADAM_UNROLL;
-constexpr int kMomentumUnroll = SU_MOMENTUM_UNROLL;
+// Launch shapes and cache policies below are the measured best on MI355X; each note says what the alternative cost.
+constexpr int kUpdBlock = 256;            // threads per workgroup of the table-driven update kernels (128 with one
+                                          // or two accesses per thread and stream measured within 2 % at every size)
+constexpr int kUnroll = 2;         // table-driven kernels: 128-bit accesses per thread per stream in flight; 2 makes a tile
+                                   // the default 2048-slot chunk, so that whole chunks run the branch-free path (4: phase 1 +5 %)
+constexpr int kAdamUnroll = 1;     // flat Adam kernel: the same (1: -2 to -5 % against 4 on shards of 12 M to 1.5 G slots)
+constexpr int kMomentumUnroll = 2; // flat momentum kernel
 
-typedef Policy<SU_NT_ADAM> PolAdam;
-typedef Policy<SU_NT_MOMENTUM> PolMomentum;
-typedef Policy<SU_NT_LAMB> PolLamb;
-typedef Policy<SU_NT_LAMB_P2> PolLambP2;
-typedef Policy<SU_NT_LARS> PolLars;
-typedef Policy<SU_NT_LARS_P2> PolLarsP2;
+// Cache policy per kernel family, as a 3-bit mask: 4 = non-temporal loads of streams that are only
+// read, 2 = non-temporal loads of streams the same thread writes back in place, 1 = non-temporal stores.
+typedef Policy<3> PolAdam;
+typedef Policy<3> PolMomentum;
+typedef Policy<6> PolLamb;
+typedef Policy<7> PolLambLarge;    // phase 1 on large shards: every access non-temporal
+typedef Policy<5> PolLambP2;       // phase 2 of LAMB: w is loaded through the caches and stored past them (measured on the
+                                   // whole step: the unshard that follows gains as much as phase 2 itself)
+typedef Policy<6> PolLars;
+typedef Policy<5> PolLarsP2;       // phase 2 of LARS: as LAMB's (w and m loaded through the caches): 122 -> 116 us on 25.6 M slots
+
 
 // Sum over the workgroup of two per-thread values, in a fixed order; the result is valid in
 // thread 0.  Wavefront step: xor shuffles; cross-wavefront step: LDS.
 __device__ __forceinline__ void block_sum2(float& a, float& b) {
-  __shared__ float part[2 * (kBlock / 64)];
+  __shared__ float part[2 * (kUpdBlock / 64)];
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) {
     a += __shfl_xor(a, s, 64);
@@ -92,7 +59,7 @@ __device__ __forceinline__ void block_sum2(float& a, float& b) {
   if (threadIdx.x == 0) {
     float x = part[0], y = part[1];
 #pragma unroll
-    for (int w = 1; w < kBlock / 64; ++w) {
+    for (int w = 1; w < kUpdBlock / 64; ++w) {
       x += part[2 * w];
       y += part[2 * w + 1];
     }
@@ -208,11 +175,10 @@ __device__ __forceinline__ float lamb_dir(float w, float m, float v, float wd, c
 
 // One tile = kBlock * unroll 128-bit accesses per stream.  FULL tiles (all but possibly the last)
 // run without a single branch: every load of the tile is issued before the first use.
-constexpr int kAdamTileElems = kBlock * kAdamUnroll * 4;   // float32 elements per tile and stream
-constexpr int kMomentumTileElems = kBlock * kMomentumUnroll * 4;
-constexpr int kTileElems = kBlock * kUnroll * 4;           // the same for the LAMB kernels
+// The two flat kernels come in two launch shapes (BLOCK threads per workgroup; see flat_shape below).
+constexpr int kTileElems = kUpdBlock * kUnroll * 4;        // slots per tile of the table-driven kernels
 
-template <bool FULL, bool BF16>
+template <int BLOCK, bool FULL, bool BF16>
 __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g, float* m, float* v,
                                           uint16_t* __restrict__ w16, int lim4, const AdamK& k) {
   // w, g, m, v, w16 point at the tile; lim4 = 128-bit units of the tile that exist (FULL: all)
@@ -220,8 +186,8 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
   F4 rw[kAdamUnroll], rg[kAdamUnroll], rm[kAdamUnroll], rv[kAdamUnroll];
 #pragma unroll
   for (int i = 0; i < kAdamUnroll; ++i) {
-    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
-      const int o = i * kBlock * 4 + t4;
+    if (FULL || (int)threadIdx.x + i * BLOCK < lim4) {
+      const int o = i * BLOCK * 4 + t4;
       rg[i] = ld4<PolAdam::RO>(g + o);
       rw[i] = ld4<PolAdam::RW>(w + o);
       rm[i] = ld4<PolAdam::RW>(m + o);
@@ -230,8 +196,8 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
   }
 #pragma unroll
   for (int i = 0; i < kAdamUnroll; ++i) {
-    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
-      const int o = i * kBlock * 4 + t4;
+    if (FULL || (int)threadIdx.x + i * BLOCK < lim4) {
+      const int o = i * BLOCK * 4 + t4;
       adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
       adam_elem(rw[i].y, rg[i].y, rm[i].y, rv[i].y, k);
       adam_elem(rw[i].z, rg[i].z, rm[i].z, rv[i].z, k);
@@ -244,18 +210,18 @@ __device__ __forceinline__ void adam_tile(float* w, const float* __restrict__ g,
   }
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void adam_kernel(float* w, const float* __restrict__ g, float* m, float* v,
+template <int BLOCK, bool BF16>
+__global__ __launch_bounds__(BLOCK) void adam_kernel(float* w, const float* __restrict__ g, float* m, float* v,
                                                       uint16_t* __restrict__ w16, int64_t n4, int tail, AdamK k) {
-  const int64_t tile4 = (int64_t)kBlock * kAdamUnroll;
+  const int64_t tile4 = (int64_t)BLOCK * kAdamUnroll;
   const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t e0 = t * kAdamTileElems;
+    const int64_t e0 = t * (tile4 * 4);
     const int64_t left4 = n4 - t * tile4;
     if (left4 >= tile4)
-      adam_tile<true, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)tile4, k);
+      adam_tile<BLOCK, true, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)tile4, k);
     else
-      adam_tile<false, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)left4, k);
+      adam_tile<BLOCK, false, BF16>(w + e0, g + e0, m + e0, v + e0, w16 + e0, (int)left4, k);
   }
   if (blockIdx.x == 0 && (int)threadIdx.x < tail) {        // S % 4 leftover elements (align < 4 only)
     const int64_t e = 4 * n4 + threadIdx.x;
@@ -266,15 +232,15 @@ __global__ __launch_bounds__(kBlock) void adam_kernel(float* w, const float* __r
   }
 }
 
-template <bool FULL, bool BF16>
+template <int BLOCK, bool FULL, bool BF16>
 __device__ __forceinline__ void momentum_tile(float* w, const float* __restrict__ g, float* m,
                                               uint16_t* __restrict__ w16, int lim4, const MomentumK& k) {
   const int t4 = threadIdx.x * 4;
   F4 rw[kMomentumUnroll], rg[kMomentumUnroll], rm[kMomentumUnroll];
 #pragma unroll
   for (int i = 0; i < kMomentumUnroll; ++i) {
-    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
-      const int o = i * kBlock * 4 + t4;
+    if (FULL || (int)threadIdx.x + i * BLOCK < lim4) {
+      const int o = i * BLOCK * 4 + t4;
       rg[i] = ld4<PolMomentum::RO>(g + o);
       rw[i] = ld4<PolMomentum::RW>(w + o);
       rm[i] = ld4<PolMomentum::RW>(m + o);
@@ -282,8 +248,8 @@ __device__ __forceinline__ void momentum_tile(float* w, const float* __restrict_
   }
 #pragma unroll
   for (int i = 0; i < kMomentumUnroll; ++i) {
-    if (FULL || (int)threadIdx.x + i * kBlock < lim4) {
-      const int o = i * kBlock * 4 + t4;
+    if (FULL || (int)threadIdx.x + i * BLOCK < lim4) {
+      const int o = i * BLOCK * 4 + t4;
       momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
       momentum_elem(rw[i].y, rg[i].y, rm[i].y, k);
       momentum_elem(rw[i].z, rg[i].z, rm[i].z, k);
@@ -295,19 +261,19 @@ __device__ __forceinline__ void momentum_tile(float* w, const float* __restrict_
   }
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float* __restrict__ g, float* m,
+template <int BLOCK, bool BF16>
+__global__ __launch_bounds__(BLOCK) void momentum_kernel(float* w, const float* __restrict__ g, float* m,
                                                           uint16_t* __restrict__ w16, int64_t n4, int tail,
                                                           MomentumK k) {
-  const int64_t tile4 = (int64_t)kBlock * kMomentumUnroll;
+  const int64_t tile4 = (int64_t)BLOCK * kMomentumUnroll;
   const int64_t tiles = (n4 + tile4 - 1) / tile4;
   for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-    const int64_t e0 = t * kMomentumTileElems;
+    const int64_t e0 = t * (tile4 * 4);
     const int64_t left4 = n4 - t * tile4;
     if (left4 >= tile4)
-      momentum_tile<true, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)tile4, k);
+      momentum_tile<BLOCK, true, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)tile4, k);
     else
-      momentum_tile<false, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)left4, k);
+      momentum_tile<BLOCK, false, BF16>(w + e0, g + e0, m + e0, w16 + e0, (int)left4, k);
   }
   if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
     const int64_t e = 4 * n4 + threadIdx.x;
@@ -326,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void momentum_kernel(float* w, const float*
 // One tile of phase 1: `lim` = slots of the tile that exist, `valid` = leading slots that hold real
 // elements (may be negative or exceed the tile).  FULL tiles run without branches; the mask on the
 // sums is a select.
-template <bool FULL, int GS, bool GFAST>
+template <typename Pol, bool FULL, int GS, bool GFAST>
 __device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const void* __restrict__ g, float* m,
                                              float* v, int lim, int valid, float wd, const AdamK& k, float& sw,
                                              float& su) {
@@ -334,17 +300,17 @@ __device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const 
   F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
-      rg[i] = load_g4<GS, GFAST, PolLamb::RO>(g, o, valid);
-      rw[i] = ld4<PolLamb::RO>(w + o);
-      rm[i] = ld4<PolLamb::RW>(m + o);
-      rv[i] = ld4<PolLamb::RW>(v + o);
+      rg[i] = load_g4<GS, GFAST, Pol::RO>(g, o, valid);
+      rw[i] = ld4<Pol::RO>(w + o);
+      rm[i] = ld4<Pol::RW>(m + o);
+      rv[i] = ld4<Pol::RW>(v + o);
     }
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       float d, wm;
 #define SU_LAMB_P1_LANE(c, j)                       \
@@ -359,19 +325,19 @@ __device__ __forceinline__ void lamb_p1_tile(const float* __restrict__ w, const 
       SU_LAMB_P1_LANE(z, 2)
       SU_LAMB_P1_LANE(w, 3)
 #undef SU_LAMB_P1_LANE
-      st4<PolLamb::ST>(m + o, rm[i]);
-      st4<PolLamb::ST>(v + o, rv[i]);
+      st4<Pol::ST>(m + o, rm[i]);
+      st4<Pol::ST>(v + o, rv[i]);
     }
   }
 }
 
-template <bool VEC, int GS>
-__global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restrict__ vars,
+template <typename Pol, bool VEC, int GS>
+__global__ __launch_bounds__(kUpdBlock) void lamb_p1_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const float* __restrict__ w, const float* __restrict__ g,
                                                          const void* const* __restrict__ g_full, float* m, float* v,
                                                          float* __restrict__ chunk_sums, int r, AdamK k) {
-  const int c = SU_P1_REVERSE ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const int c = (int)blockIdx.x;
   const ChunkView cv = chunk_view(vars, chunks, c, r);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
   const GradChunk<GS> gc = grad_chunk<GS>(g, g_full, cv);
@@ -382,18 +348,18 @@ __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restri
       const int lim = cv.len - base, valid = cv.valid - base;
       if (lim >= kTileElems) {
         if (gc.fast(kTileElems, valid))
-          lamb_p1_tile<true, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
+          lamb_p1_tile<Pol, true, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
         else
-          lamb_p1_tile<true, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
+          lamb_p1_tile<Pol, true, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, kTileElems, valid, wd, k, sw, su);
       } else {
         if (gc.fast(lim, valid))
-          lamb_p1_tile<false, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
+          lamb_p1_tile<Pol, false, GS, true>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
         else
-          lamb_p1_tile<false, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
+          lamb_p1_tile<Pol, false, GS, false>(w + s0, gc.tile(base), m + s0, v + s0, lim, valid, wd, k, sw, su);
       }
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const int64_t s = cv.shard0 + e;
       float mm = m[s], vv = v[s];
       const float ww = w[s];
@@ -415,7 +381,7 @@ __global__ __launch_bounds__(kBlock) void lamb_p1_kernel(const VarDesc* __restri
 }
 
 // One workgroup per variable: adds the variable's chunk sums in an order that depends only on the
-// chunk table (thread t takes chunks t, t + kBlock, ...; float64 accumulators; wavefront shuffles,
+// chunk table (thread t takes chunks t, t + kUpdBlock, ...; float64 accumulators; wavefront shuffles,
 // then the four wavefronts in order), optionally adds the other replicas' table (the all-reduce
 // stand-in).
 // (Folding this into phase 1, with the workgroup that finishes a variable's last chunk doing the
@@ -489,7 +455,7 @@ __device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__
   F4 rw[kUnroll], rm[kUnroll], rv[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rw[i] = ld4<PolLambP2::RW>(w + o);
       rm[i] = ld4<PolLambP2::RO>(m + o);
@@ -498,7 +464,7 @@ __device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rw[i].x = fmaf(-step, lamb_dir(rw[i].x, rm[i].x, rv[i].x, wd, k), rw[i].x);
       rw[i].y = fmaf(-step, lamb_dir(rw[i].y, rm[i].y, rv[i].y, wd, k), rw[i].y);
@@ -511,12 +477,12 @@ __device__ __forceinline__ void lamb_p2_tile(float* w, const float* __restrict__
 }
 
 template <bool VEC, bool BF16>
-__global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kUpdBlock) void lamb_p2_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks, float* w,
                                                          const float* __restrict__ m, const float* __restrict__ v,
                                                          uint16_t* __restrict__ w16, const float* __restrict__ sums,
                                                          AdamK k) {
-  const int c = SU_P2_REVERSE ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const int c = (int)(gridDim.x - 1 - blockIdx.x);          // opposite direction to phase 1: starts on what it touched last
   const ChunkView cv = chunk_view(vars, chunks, c, 0);
   const float wd = (cv.flags & SHARD_VAR_NO_DECAY) ? 0.0f : k.wd;
   float ratio = 1.0f;
@@ -534,7 +500,7 @@ __global__ __launch_bounds__(kBlock) void lamb_p2_kernel(const VarDesc* __restri
         lamb_p2_tile<false, BF16>(w + s0, m + s0, v + s0, w16 + s0, cv.len - base, wd, step, k);
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const int64_t s = cv.shard0 + e;
       const float ww = w[s];
       const float nw = fmaf(-step, lamb_dir(ww, m[s], v[s], wd, k), ww);
@@ -555,7 +521,7 @@ __device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const 
   F4 rw[kUnroll], rg[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rg[i] = load_g4<GS, GFAST, PolLars::RO>(g, o, valid);
       rw[i] = ld4<PolLars::RO>(w + o);
@@ -563,7 +529,7 @@ __device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const 
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       float a, b;
 #define SU_LARS_P1_LANE(c, j)                 \
@@ -581,7 +547,7 @@ __device__ __forceinline__ void lars_p1_tile(const float* __restrict__ w, const 
 }
 
 template <bool VEC, int GS>
-__global__ __launch_bounds__(kBlock) void lars_p1_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kUpdBlock) void lars_p1_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks,
                                                          const float* __restrict__ w, const float* __restrict__ g,
                                                          const void* const* __restrict__ g_full,
@@ -603,7 +569,7 @@ __global__ __launch_bounds__(kBlock) void lars_p1_kernel(const VarDesc* __restri
       }
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const float a = (e < cv.valid) ? w[cv.shard0 + e] : 0.0f;
       const float b = (e < cv.valid) ? load_g1<GS>(gc, e, cv.valid) : 0.0f;
       sw = fmaf(a, a, sw);
@@ -631,7 +597,7 @@ __device__ __forceinline__ void lars_p2_tile(float* w, const void* __restrict__ 
   F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rg[i] = load_g4<GS, GFAST, PolLarsP2::RO>(g, o, valid);
       rw[i] = ld4<PolLarsP2::RW>(w + o);
@@ -640,7 +606,7 @@ __device__ __forceinline__ void lars_p2_tile(float* w, const void* __restrict__ 
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       lars_elem(rw[i].x, rg[i].x, rm[i].x, wd, scale, mu);
       lars_elem(rw[i].y, rg[i].y, rm[i].y, wd, scale, mu);
@@ -654,7 +620,7 @@ __device__ __forceinline__ void lars_p2_tile(float* w, const void* __restrict__ 
 }
 
 template <bool VEC, bool BF16, int GS>
-__global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kUpdBlock) void lars_p2_kernel(const VarDesc* __restrict__ vars,
                                                          const ChunkDesc* __restrict__ chunks, float* w,
                                                          const float* __restrict__ g,
                                                          const void* const* __restrict__ g_full, float* m,
@@ -687,7 +653,7 @@ __global__ __launch_bounds__(kBlock) void lars_p2_kernel(const VarDesc* __restri
       }
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const int64_t s = cv.shard0 + e;
       float ww = w[s], mm = m[s];
       lars_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, wd, scale, k.mu);
@@ -710,7 +676,7 @@ __device__ __forceinline__ void adam_chunk_tile(float* w, const void* __restrict
   F4 rw[kUnroll], rg[kUnroll], rm[kUnroll], rv[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rg[i] = load_g4<GS, GFAST, true>(g, o, valid);
       rw[i] = ld4<PolAdam::RW>(w + o);
@@ -720,7 +686,7 @@ __device__ __forceinline__ void adam_chunk_tile(float* w, const void* __restrict
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       adam_elem(rw[i].x, rg[i].x, rm[i].x, rv[i].x, k);
       adam_elem(rw[i].y, rg[i].y, rm[i].y, rv[i].y, k);
@@ -735,7 +701,7 @@ __device__ __forceinline__ void adam_chunk_tile(float* w, const void* __restrict
 }
 
 template <bool VEC, bool BF16, int GS>
-__global__ __launch_bounds__(kBlock) void adam_chunk_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kUpdBlock) void adam_chunk_kernel(const VarDesc* __restrict__ vars,
                                                             const ChunkDesc* __restrict__ chunks, float* w,
                                                             const void* const* __restrict__ g_full, float* m, float* v,
                                                             uint16_t* __restrict__ w16, int r, AdamK k) {
@@ -758,7 +724,7 @@ __global__ __launch_bounds__(kBlock) void adam_chunk_kernel(const VarDesc* __res
       }
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const int64_t s = cv.shard0 + e;
       float ww = w[s], mm = m[s], vv = v[s];
       adam_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, vv, k);
@@ -776,7 +742,7 @@ __device__ __forceinline__ void momentum_chunk_tile(float* w, const void* __rest
   F4 rw[kUnroll], rg[kUnroll], rm[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       rg[i] = load_g4<GS, GFAST, true>(g, o, valid);
       rw[i] = ld4<PolMomentum::RW>(w + o);
@@ -785,7 +751,7 @@ __device__ __forceinline__ void momentum_chunk_tile(float* w, const void* __rest
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int o = i * kBlock * 4 + t4;
+    const int o = i * kUpdBlock * 4 + t4;
     if (FULL || o < lim) {
       momentum_elem(rw[i].x, rg[i].x, rm[i].x, k);
       momentum_elem(rw[i].y, rg[i].y, rm[i].y, k);
@@ -799,7 +765,7 @@ __device__ __forceinline__ void momentum_chunk_tile(float* w, const void* __rest
 }
 
 template <bool VEC, bool BF16, int GS>
-__global__ __launch_bounds__(kBlock) void momentum_chunk_kernel(const VarDesc* __restrict__ vars,
+__global__ __launch_bounds__(kUpdBlock) void momentum_chunk_kernel(const VarDesc* __restrict__ vars,
                                                                 const ChunkDesc* __restrict__ chunks, float* w,
                                                                 const void* const* __restrict__ g_full, float* m,
                                                                 uint16_t* __restrict__ w16, int r, MomentumK k) {
@@ -822,7 +788,7 @@ __global__ __launch_bounds__(kBlock) void momentum_chunk_kernel(const VarDesc* _
       }
     }
   } else {
-    for (int e = threadIdx.x; e < cv.len; e += kBlock) {
+    for (int e = threadIdx.x; e < cv.len; e += kUpdBlock) {
       const int64_t s = cv.shard0 + e;
       float ww = w[s], mm = m[s];
       momentum_elem(ww, load_g1<GS>(gc, e, cv.valid), mm, k);
@@ -832,14 +798,49 @@ __global__ __launch_bounds__(kBlock) void momentum_chunk_kernel(const VarDesc* _
   }
 }
 
-inline unsigned flat_grid(int64_t n4, int unroll) {
-  const int64_t tile = (int64_t)kBlock * unroll;
+// ---- launch shapes: how much a CU keeps in flight --------------------------------------------------
+// A streaming kernel is fastest when the loads in flight cover bandwidth x latency and little more.  Measured on
+// MI355X with an Adam-shaped update (4 streams read, 3 written) on shards too large for the 256 MB memory-side
+// cache to help: 40 to 48 KB of loads in flight per CU (10 to 12 wavefronts with one 128-bit load per stream)
+// sustain 6.2 to 6.4 TB/s, while the 128 KB that full occupancy keeps in flight (8 workgroups of 256 threads)
+// sustain 5.4 to 5.6: in-flight lines beyond what the memory system needs only crowd the L2 (4 MB per XCD for 32
+// CUs).  Fewer, smaller workgroups do better still (128 threads, 5 per CU: +2.5 % over 256 threads, 2 per CU).
+// Shards whose state fits the memory-side cache or nearly so behave the other way (full occupancy is up to 4 %
+// faster), so the launchers choose by shard size.
+// The cap on resident workgroups is LDS that the launch reserves and the kernel never touches: a CU has 160 KB,
+// so workgroups that each ask for 160/k KB, less a margin for the kernel's own few bytes, fit k to a CU.
+constexpr unsigned lds_for(int workgroups_per_cu) { return (unsigned)(160 * 1024 / workgroups_per_cu - 1024); }
+constexpr unsigned kNoCap = 0;
+// Shards from this many slots on are "large" for the table-driven kernels: a single float32 stream of the shard
+// (256 MB) no longer fits the memory-side cache.  Measured on the 340 M-parameter list: 84 M slots gain 4 % from
+// the large shape, 42 M slots lose 4 % on the whole step.
+constexpr int64_t kLargeShard = (int64_t)1 << 26;
+// The flat kernels (Adam, momentum) switch earlier: from 2^25 slots their three or four streams of state are
+// several times the cache (42 M slots: +10 %; 13 M and 25 M slots, which fit: -2 to -4 %).
+constexpr int64_t kLargeFlatShard = (int64_t)1 << 25;
+constexpr int kFlatBlockSmall = 256, kFlatBlockLarge = 128;
+constexpr unsigned kLdsFlatLarge = lds_for(5);
+// Table-driven kernels (256 threads, two accesses per thread and stream: 32 KB of loads per workgroup in LAMB's
+// phase 1).  Their workgroups start with two dependent table look-ups, so they need more of them resident than
+// the flat kernels to hide that; three per CU is the measured optimum on large shards (LAMB on 336 M slots
+// 2350 -> 2180 us, LARS 1650 -> 1580), no cap on shards that the memory-side cache helps (42 M slots: within 1 %).
+// Phase 1 of LARS only reads and is fastest uncapped.  The updates that read full gradient tensors gain 2 to 5 %
+// from the cap at every size measured (13 M to 336 M slots).
+constexpr unsigned kLdsLambP1Large = lds_for(3);
+constexpr unsigned kLdsLambP2Large = lds_for(3);
+constexpr unsigned kLdsLarsP2Large = lds_for(3);
+constexpr unsigned kLdsLambP1 = kNoCap;
+constexpr unsigned kLdsLambP2 = kNoCap;
+constexpr unsigned kLdsLarsP1 = kNoCap;
+constexpr unsigned kLdsLarsP2 = kNoCap;
+constexpr unsigned kLdsAdamChunk = lds_for(3);
+constexpr unsigned kLdsMomentumChunk = lds_for(3);
+
+inline unsigned flat_grid(int64_t n4, int block, int unroll) {
+  const int64_t tile = (int64_t)block * unroll;
   int64_t tiles = (n4 + tile - 1) / tile;
   if (tiles < 1) tiles = 1;
-#if SU_GRID_CAP > 0
-  if (tiles > SU_GRID_CAP) tiles = SU_GRID_CAP;
-#endif
-  if (tiles > 0x7FFFFFFF) tiles = 0x7FFFFFFF;
+  if (tiles > 0x7FFFFFFF) tiles = 0x7FFFFFFF;      // the kernels loop over tiles
   return (unsigned)tiles;
 }
 
@@ -853,12 +854,16 @@ hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, floa
   ProfScope ps(p, SHARD_K_ADAM, stream);
   const int64_t n4 = p->S >> 2;
   const int tail = (int)(p->S & 3);
-  if (w16)
-    hipLaunchKernelGGL((adam_kernel<true>), dim3(flat_grid(n4, kAdamUnroll)), dim3(kBlock), 0, stream, w, g, m, v, (uint16_t*)w16,
-                       n4, tail, k);
-  else
-    hipLaunchKernelGGL((adam_kernel<false>), dim3(flat_grid(n4, kAdamUnroll)), dim3(kBlock), 0, stream, w, g, m, v,
-                       (uint16_t*)nullptr, n4, tail, k);
+  uint16_t* o = (uint16_t*)w16;
+#define SU_LAUNCH_ADAM(BLOCK, BF16, LDS)                                                                      \
+  hipLaunchKernelGGL((adam_kernel<BLOCK, BF16>), dim3(flat_grid(n4, BLOCK, kAdamUnroll)), dim3(BLOCK), LDS, stream, \
+                     w, g, m, v, o, n4, tail, k)
+  if (p->S >= kLargeFlatShard) {
+    if (o) SU_LAUNCH_ADAM(kFlatBlockLarge, true, kLdsFlatLarge); else SU_LAUNCH_ADAM(kFlatBlockLarge, false, kLdsFlatLarge);
+  } else {
+    if (o) SU_LAUNCH_ADAM(kFlatBlockSmall, true, kNoCap); else SU_LAUNCH_ADAM(kFlatBlockSmall, false, kNoCap);
+  }
+#undef SU_LAUNCH_ADAM
   return hipGetLastError();
 }
 
@@ -868,12 +873,16 @@ hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, 
   ProfScope ps(p, SHARD_K_MOMENTUM, stream);
   const int64_t n4 = p->S >> 2;
   const int tail = (int)(p->S & 3);
-  if (w16)
-    hipLaunchKernelGGL((momentum_kernel<true>), dim3(flat_grid(n4, kMomentumUnroll)), dim3(kBlock), 0, stream, w, g, m, (uint16_t*)w16,
-                       n4, tail, k);
-  else
-    hipLaunchKernelGGL((momentum_kernel<false>), dim3(flat_grid(n4, kMomentumUnroll)), dim3(kBlock), 0, stream, w, g, m,
-                       (uint16_t*)nullptr, n4, tail, k);
+  uint16_t* o = (uint16_t*)w16;
+#define SU_LAUNCH_MOM(BLOCK, BF16, LDS)                                                                              \
+  hipLaunchKernelGGL((momentum_kernel<BLOCK, BF16>), dim3(flat_grid(n4, BLOCK, kMomentumUnroll)), dim3(BLOCK), LDS, \
+                     stream, w, g, m, o, n4, tail, k)
+  if (p->S >= kLargeFlatShard) {
+    if (o) SU_LAUNCH_MOM(kFlatBlockLarge, true, kLdsFlatLarge); else SU_LAUNCH_MOM(kFlatBlockLarge, false, kLdsFlatLarge);
+  } else {
+    if (o) SU_LAUNCH_MOM(kFlatBlockSmall, true, kNoCap); else SU_LAUNCH_MOM(kFlatBlockSmall, false, kNoCap);
+  }
+#undef SU_LAUNCH_MOM
   return hipGetLastError();
 }
 
@@ -887,8 +896,18 @@ hipError_t launch_lamb_p1(shard_plan_t* p, int r, const float* w, const float* g
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   float* cs = chunk_sums ? chunk_sums : ws_at<float>(p, p->ws.chunk_sums);
   const bool vec = p->align % 4 == 0;
-#define SU_LAUNCH_P1(VEC, GS) \
-  hipLaunchKernelGGL((lamb_p1_kernel<VEC, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, m, v, cs, r, k)
+  // Large shards: m and v are stored past the caches as well (nothing the next kernel reads of them would still
+  // be cached by then) and three workgroups stay resident per CU.
+  const bool large = p->S >= kLargeShard;
+#define SU_LAUNCH_P1(VEC, GS)                                                                                       \
+  do {                                                                                                              \
+    if (large)                                                                                                      \
+      hipLaunchKernelGGL((lamb_p1_kernel<PolLambLarge, VEC, GS>), grid, dim3(kUpdBlock), kLdsLambP1Large, stream, vars, \
+                         chunks, w, g, g_full, m, v, cs, r, k);                                                     \
+    else                                                                                                            \
+      hipLaunchKernelGGL((lamb_p1_kernel<PolLamb, VEC, GS>), grid, dim3(kUpdBlock), kLdsLambP1, stream, vars, chunks, w, \
+                         g, g_full, m, v, cs, r, k);                                                                \
+  } while (0)
   if (g_source == 0) {
     if (vec) SU_LAUNCH_P1(true, 0); else SU_LAUNCH_P1(false, 0);
   } else if (g_source == 1) {
@@ -920,10 +939,11 @@ hipError_t launch_lamb_p2(shard_plan_t* p, int r, float* w, const float* m, cons
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   const bool vec = p->align % 4 == 0;
   uint16_t* o = (uint16_t*)w16;
-  if (vec && o) hipLaunchKernelGGL((lamb_p2_kernel<true, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
-  else if (vec) hipLaunchKernelGGL((lamb_p2_kernel<true, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
-  else if (o) hipLaunchKernelGGL((lamb_p2_kernel<false, true>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
-  else hipLaunchKernelGGL((lamb_p2_kernel<false, false>), grid, dim3(kBlock), 0, stream, vars, chunks, w, m, v, o, sums, k);
+  const unsigned lds = p->S >= kLargeShard ? kLdsLambP2Large : kLdsLambP2;
+  if (vec && o) hipLaunchKernelGGL((lamb_p2_kernel<true, true>), grid, dim3(kUpdBlock), lds, stream, vars, chunks, w, m, v, o, sums, k);
+  else if (vec) hipLaunchKernelGGL((lamb_p2_kernel<true, false>), grid, dim3(kUpdBlock), lds, stream, vars, chunks, w, m, v, o, sums, k);
+  else if (o) hipLaunchKernelGGL((lamb_p2_kernel<false, true>), grid, dim3(kUpdBlock), lds, stream, vars, chunks, w, m, v, o, sums, k);
+  else hipLaunchKernelGGL((lamb_p2_kernel<false, false>), grid, dim3(kUpdBlock), lds, stream, vars, chunks, w, m, v, o, sums, k);
   return hipGetLastError();
 }
 
@@ -937,7 +957,7 @@ hipError_t launch_lars_p1(shard_plan_t* p, int r, const float* w, const float* g
   float* cs = ws_at<float>(p, p->ws.chunk_sums);
   const bool vec = p->align % 4 == 0;
 #define SU_LAUNCH(VEC, GS) \
-  hipLaunchKernelGGL((lars_p1_kernel<VEC, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, cs, r)
+  hipLaunchKernelGGL((lars_p1_kernel<VEC, GS>), grid, dim3(kUpdBlock), kLdsLarsP1, stream, vars, chunks, w, g, g_full, cs, r)
   if (g_source == 0) { if (vec) SU_LAUNCH(true, 0); else SU_LAUNCH(false, 0); }
   else if (g_source == 1) { if (vec) SU_LAUNCH(true, 1); else SU_LAUNCH(false, 1); }
   else { if (vec) SU_LAUNCH(true, 2); else SU_LAUNCH(false, 2); }
@@ -954,8 +974,9 @@ hipError_t launch_lars_p2(shard_plan_t* p, int r, float* w, const float* g, int 
   const ChunkDesc* chunks = ws_at<ChunkDesc>(p, p->ws.chunks);
   const bool vec = p->align % 4 == 0;
   uint16_t* o = (uint16_t*)w16;
+  const unsigned lds = p->S >= kLargeShard ? kLdsLarsP2Large : kLdsLarsP2;
 #define SU_LAUNCH(VEC, BF16, GS)                                                                                     \
-  hipLaunchKernelGGL((lars_p2_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g, g_full, m, o, \
+  hipLaunchKernelGGL((lars_p2_kernel<VEC, BF16, GS>), grid, dim3(kUpdBlock), lds, stream, vars, chunks, w, g, g_full, m, o, \
                      sums, r, k)
 #define SU_LAUNCH_GS(GS)                     \
   do {                                       \
@@ -981,7 +1002,7 @@ hipError_t launch_adam_full_grads(shard_plan_t* p, int r, float* w, int g_source
   const bool vec = p->align % 4 == 0;
   uint16_t* o = (uint16_t*)w16;
 #define SU_LAUNCH(VEC, BF16, GS)                                                                                       \
-  hipLaunchKernelGGL((adam_chunk_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g_full, m, v, \
+  hipLaunchKernelGGL((adam_chunk_kernel<VEC, BF16, GS>), grid, dim3(kUpdBlock), kLdsAdamChunk, stream, vars, chunks, w, g_full, m, v, \
                      o, r, k)
   if (g_source == 1) SU_LAUNCH_GS(1);
   else SU_LAUNCH_GS(2);
@@ -999,7 +1020,7 @@ hipError_t launch_momentum_full_grads(shard_plan_t* p, int r, float* w, int g_so
   const bool vec = p->align % 4 == 0;
   uint16_t* o = (uint16_t*)w16;
 #define SU_LAUNCH(VEC, BF16, GS)                                                                                        \
-  hipLaunchKernelGGL((momentum_chunk_kernel<VEC, BF16, GS>), grid, dim3(kBlock), 0, stream, vars, chunks, w, g_full, m, \
+  hipLaunchKernelGGL((momentum_chunk_kernel<VEC, BF16, GS>), grid, dim3(kUpdBlock), kLdsMomentumChunk, stream, vars, chunks, w, g_full, m, \
                      o, r, k)
   if (g_source == 1) SU_LAUNCH_GS(1);
   else SU_LAUNCH_GS(2);

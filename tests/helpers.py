@@ -82,3 +82,25 @@ def pads_are_zero(plan: oracle.Plan, r: int, shard: np.ndarray) -> bool:
         if bits[plan.off[i] + real: plan.off[i] + plan.L[i]].any():
             return False
     return True
+
+
+# ---- guard bands -----------------------------------------------------------------------------------
+CANARY = 0x5A
+BAND = 256           # bytes before and after the payload; keeps the payload 16-byte aligned
+
+
+class Guarded:
+    """A device tensor of `n` elements of `dtype` carved out of a byte buffer with canary bands on both
+    sides: a kernel that stores outside its output shows up in `intact()`."""
+
+    def __init__(self, n: int, dtype=torch.float32, init=None):
+        self.nbytes = n * torch.empty((), dtype=dtype).element_size()
+        self.buf = torch.full((self.nbytes + 2 * BAND,), CANARY, dtype=torch.uint8, device=DEV)
+        self.t = self.buf[BAND:BAND + self.nbytes].view(dtype)
+        if init is None:
+            self.t.zero_()
+        else:
+            self.t.copy_(init if isinstance(init, torch.Tensor) else to_dev(np.ascontiguousarray(init)))
+
+    def intact(self) -> bool:
+        return bool((self.buf[:BAND] == CANARY).all()) and bool((self.buf[BAND + self.nbytes:] == CANARY).all())

@@ -458,10 +458,11 @@ def test_both_orders_of_the_whole_model_copies_write_the_same_bytes(numel, N, al
 
 
 @pytest.mark.gpu
-def test_measured_order_settles_and_every_call_on_the_way_is_right():
-    """With large pieces the order is found by timing the first calls: each of them, whichever order it takes,
-    restores the same bytes; after at most 6 timed calls the order is fixed, and another list of tensors starts
-    a measurement of its own."""
+def test_tuned_order_is_explicit_deterministic_and_every_copy_is_right():
+    """With large pieces the copies go by replica until the caller has the two orders measured for a list of
+    tensors: plain calls never time anything and never change order by themselves; the tuning call runs the copy
+    for real in both orders, reports what it chose with both times, and later calls with that list keep the choice
+    whatever else runs on the stream in between; another list, element type or row stride is untuned again."""
     numel, N = [262144, 100, 131072, 70000, 262144], 4
     oplan = oracle.make_plan(numel, N, 8)
     plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
@@ -470,34 +471,57 @@ def test_measured_order_settles_and_every_call_on_the_way_is_right():
     gathered = su.gathered_empty(plan)
     gathered.copy_(to_dev(ref))
     outs = [torch.zeros(n, device=DEV) for n in numel]
-    assert su.shard_plan_copy_walk(plan, "unshard_format", outs) == "auto"
-    seen = []
-    for _ in range(8):
+    noise = torch.zeros(1 << 24, device=DEV)
+    for k in range(8):                       # untuned calls under a varying load: the order never moves
         for o in outs:
             o.fill_(3.0)
+        if k & 1:
+            noise.add_(1.0)                  # other work on the stream
         su.unshard_format(plan, gathered, outs)
         torch.cuda.synchronize()
         for o, f in zip(outs, flats):
             assert same_bits(to_host(o), f)
-        seen.append(su.shard_plan_copy_walk(plan, "unshard_format", outs, with_times=True))
-    assert seen[5][0] == "auto" and seen[6][0] in ("by_replica", "by_variable"), seen
-    assert seen[6][1][0] > 0.0 and seen[6][1][1] > 0.0
-    assert seen[7] == seen[6]
-    # the other copy and another list of tensors have not been measured yet
-    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs) == "auto"
-    others = [torch.zeros(n, device=DEV) for n in numel]
-    assert su.shard_plan_copy_walk(plan, "unshard_format", others) == "auto"
-    rows = torch.zeros_like(gathered)
-    for _ in range(8):
-        rows.fill_(5.0)
-        su.shard_format_all(plan, outs, rows)
-        torch.cuda.synchronize()
-        assert same_bits(to_host(rows), ref)
-    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs) != "auto"
-    # calls that do not wait for one another settle as well, only later; all of them are right
-    for _ in range(40):
-        su.unshard_format(plan, gathered, others)
+        assert su.shard_plan_copy_walk(plan, "unshard_format", outs, with_times=True) == ("by_replica", (0.0, 0.0))
+    for o in outs:
+        o.fill_(3.0)
+    walk, (ms_rep, ms_var) = su.shard_plan_tune_copy_walk(plan, "unshard_format", gathered, outs)
     torch.cuda.synchronize()
-    for o, f in zip(others, flats):
+    assert walk in ("by_replica", "by_variable") and ms_rep > 0.0 and ms_var > 0.0
+    assert walk == ("by_variable" if ms_var < 0.98 * ms_rep else "by_replica")
+    for o, f in zip(outs, flats):            # the tuning call ran the copy for real
         assert same_bits(to_host(o), f)
+    assert su.shard_plan_copy_walk(plan, "unshard_format", outs, with_times=True) == (walk, (ms_rep, ms_var))
+    for k in range(6):                       # the choice stays, under load or not
+        if k & 1:
+            noise.add_(1.0)
+        su.unshard_format(plan, gathered, outs)
+        assert su.shard_plan_copy_walk(plan, "unshard_format", outs) == walk
+    torch.cuda.synchronize()
+    for o, f in zip(outs, flats):
+        assert same_bits(to_host(o), f)
+    # the other copy and another list of tensors have not been measured
+    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs, with_times=True) == ("by_replica", (0.0, 0.0))
+    others = [torch.zeros(n, device=DEV) for n in numel]
+    assert su.shard_plan_copy_walk(plan, "unshard_format", others, with_times=True) == ("by_replica", (0.0, 0.0))
+    rows = torch.zeros_like(gathered)
+    rows.fill_(5.0)
+    walk2, times2 = su.shard_plan_tune_copy_walk(plan, "shard_format_all", rows, outs)
+    torch.cuda.synchronize()
+    assert same_bits(to_host(rows), ref)
+    assert su.shard_plan_copy_walk(plan, "shard_format_all", outs, with_times=True) == (walk2, times2)
+    # a forced order wins over a tuned one, and tuning then launches nothing
+    su.shard_plan_set_copy_walk(plan, "by_variable")
+    assert su.shard_plan_tune_copy_walk(plan, "unshard_format", gathered, outs) == ("by_variable", (0.0, 0.0))
+    su.shard_plan_set_copy_walk(plan, "auto")
+    assert su.shard_plan_copy_walk(plan, "unshard_format", outs) == walk
+    # refused while the stream is being captured (it waits for its launches)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        with pytest.raises(su.ShardError) as err:
+            su.shard_plan_tune_copy_walk(plan, "unshard_format", gathered, outs)
+        su.unshard_format(plan, gathered, outs)
+    assert err.value.status == -5
+    torch.cuda.synchronize()
     plan.free()

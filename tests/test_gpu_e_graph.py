@@ -250,3 +250,53 @@ def test_tables_a_recorded_graph_reads_are_never_overwritten():
     torch.cuda.synchronize()
     assert bool((scratch[: 8] == 0.0).all())                 # others[0] is all zeros
     plan.free(); ref_plan.free()
+
+
+def test_a_list_first_seen_during_capture_is_safe_for_eager_calls_and_replays():
+    """No eager warm-up: the plan sees the lists of full tensors for the first time while the stream is being
+    captured, so their pointer tables are uploaded by kernels that were only recorded.  Eager calls with the
+    same lists before the first replay must not trust those tables (they upload their own), and the graph must
+    carry its uploads: every replay equals the eager step."""
+    cfg = [c for c in CONFIGS if c.name == "tiny"][0]
+    N, r = 4, 1
+    plan, ref_plan = su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8)), su.shard_plan_bind(su.shard_plan(cfg.numel, N, 8))
+    # poison the plan's pointer-table slots with other tensors, so that a stale table would not go unnoticed
+    decoys = [[torch.full((n,), 9.0, device=DEV) for n in cfg.numel] for _ in range(4)]
+    tmp = torch.zeros(plan.S, device=DEV)
+    for lst in decoys:
+        su.shard_format(plan, r, lst, tmp)
+    graphed, eager = State(plan, cfg, r, 99), State(ref_plan, cfg, r, 99)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        graphed.step(plan)                      # first sight of graphed.full_g and graphed.full_w
+    torch.cuda.synchronize()
+    # eager calls with the same two lists, before any replay
+    want = torch.zeros(plan.S, device=DEV)
+    su.shard_format(ref_plan, r, graphed.full_g, want)
+    su.shard_format(plan, r, graphed.full_g, tmp)
+    torch.cuda.synchronize()
+    assert torch.equal(tmp, want)
+    su.unshard_format(plan, graphed.gathered, graphed.full_w)
+    su.unshard_format(ref_plan, eager.gathered, eager.full_w)
+    torch.cuda.synchronize()
+    assert same_bits(to_host(torch.cat(graphed.full_w)), to_host(torch.cat(eager.full_w)))
+    for a in graphed.full_w + eager.full_w:
+        a.zero_()
+    torch.cuda.synchronize()
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        eager.step(ref_plan)
+        torch.cuda.synchronize()
+        assert all(same_bits(x, y) for x, y in zip(graphed.snapshot(), eager.snapshot())), "replay %d" % k
+    # every slot is now taken (two reserved by the graph, two by the eager uploads of the same lists): once the
+    # graph is gone and its tables are released, other lists fit again
+    del graph
+    su.shard_plan_release_captured_tables(plan)
+    for lst in decoys:
+        su.shard_format(plan, r, lst, tmp)
+    torch.cuda.synchronize()
+    assert bool((tmp[:8] == 9.0).all())
+    plan.free(); ref_plan.free()

@@ -336,15 +336,15 @@ def test_header_is_valid_c99_and_the_c_client_builds():
 
 def test_copy_order_api_on_the_host():
     """Setting and reading the order of the whole-model copies needs no GPU: what a plan fixes by itself (small
-    pieces by variable; one replica and row plans by replica), what is left to measurement, and bad arguments."""
+    pieces by variable; one replica and row plans by replica), what the explicit measurement may change, and bad arguments."""
     import ctypes as C
     lib = su.lib()
     large = su.shard_plan([1 << 20, 100, 1 << 18], 4, 8)
-    assert su.shard_plan_copy_walk(large, "unshard_format") == "auto"
-    assert su.shard_plan_copy_walk(large, "shard_format_all") == "auto"
+    assert su.shard_plan_copy_walk(large, "unshard_format") == "by_replica"      # large pieces, nothing measured
+    assert su.shard_plan_copy_walk(large, "shard_format_all", with_times=True) == ("by_replica", (0.0, 0.0))
     for walk in ("by_replica", "by_variable", "auto"):
         su.shard_plan_set_copy_walk(large, walk)
-        assert su.shard_plan_copy_walk(large, "unshard_format") == walk
+        assert su.shard_plan_copy_walk(large, "unshard_format") == ("by_replica" if walk == "auto" else walk)
     small = su.shard_plan([100] * 300, 64, 8)
     assert su.shard_plan_copy_walk(small, "unshard_format") == "by_variable"
     su.shard_plan_set_copy_walk(small, "by_replica")
@@ -362,6 +362,9 @@ def test_copy_order_api_on_the_host():
     assert lib.shard_plan_set_copy_walk(None, 0) == -1
     assert lib.shard_plan_copy_walk(large.handle, 2, None, C.byref(out), None) == -1
     assert lib.shard_plan_copy_walk(large.handle, 0, None, None, None) == -1
+    # tuning needs a bound plan and valid arguments; all of that is checked before anything touches a GPU
+    assert lib.shard_plan_tune_copy_walk(None, 0, None, 0, 0, None, 0, None, None, None) == -1
+    assert lib.shard_plan_tune_copy_walk(large.handle, 0, None, 0, 0, None, 0, None, None, None) == -5    # not bound
     with pytest.raises(ValueError):
         su.shard_plan_set_copy_walk(large, "sideways")
     for p in (large, small, one, rows):
