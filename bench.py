@@ -56,7 +56,8 @@ def parse_args():
                     help="instead of the headline step, run ONE stage of --config at --replicas for --steps launches "
                          "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
                          "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads | "
-                         "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w | unshard_format_bf16) "
+                         "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w | unshard_format_bf16 | "
+                         "unshard_format_f32_to_bf16 | shard_format_bf16_to_f32 | lamb_step_bf16 | lamb_fused_step_bf16) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--separate-tensors", action="store_true",
                     help="with --stage: every full tensor is an allocation of its own from torch's caching allocator "
@@ -82,6 +83,59 @@ def _settle_copy(torch, su, plan, copy, gathered, full):
     walk, (by_replica_ms, by_variable_ms) = su.shard_plan_tune_copy_walk(plan, copy, gathered, full)
     torch.cuda.synchronize()
     return {"walk": walk, "timed_ms_by_replica": round(by_replica_ms, 4), "timed_ms_by_variable": round(by_variable_ms, 4)}
+
+
+def sources_sha16():
+    """First 16 hex digits of the SHA-256 over the library's sources (csrc/ and include/, by name): what a
+    counter summary under profiles/ is tied to, so that a figure measured on other kernels is not reported."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in (os.path.join(ROOT, "paper_2004_13336_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(d)):
+            if name.endswith((".hip", ".cpp", ".hpp", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def _time_stage(torch, su, plan, fn, kernels, warmup, iters):
+    """One stage (one or several kernels), three ways, all on the stream the library launches on:
+      median_us  median over `iters` calls, each bracketed by an event pair of its own;
+      region_us  `iters` calls back to back inside ONE event pair, per call (how the headline step is timed;
+                 for several kernels in a row this is what their sum really takes);
+      kernel_us  per-kernel averages from the library's own event pairs, a breakdown (each pair adds a few
+                 microseconds of its own, so their sum exceeds region_us)."""
+    for t in range(1, 1 + max(warmup, 1)):
+        fn(t)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(pairs):
+        a.record(); fn(100 + i); b.record()
+    torch.cuda.synchronize()
+    median_us = 1e3 * _median([a.elapsed_time(b) for a, b in pairs])
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(iters):
+        fn(1000 + i)
+    b.record()
+    torch.cuda.synchronize()
+    region_us = 1e3 * a.elapsed_time(b) / iters
+    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+    for i in range(iters):
+        fn(2000 + i)
+    torch.cuda.synchronize()
+    per = {}
+    for k in kernels:
+        n, ms = su.shard_profile_read(plan, k)
+        per[k] = round(1e3 * ms / max(n, 1) * (n / iters if n else 0), 2)      # per call of the stage
+    su.shard_profile_enable(plan, False)
+    return {"median_us": round(median_us, 2), "region_us": round(region_us, 2), "kernel_us": per}
 
 
 def _time_region(torch, fn, steps):
@@ -189,6 +243,12 @@ def headline(args, torch, su, cfgs):
     for _ in range(max(args.warmup, 2)):
         one_step()
     ms_step, wall_ms = _time_region(torch, one_step, args.steps)
+    # the same K steps once more, each inside an event pair of its own: the median beside the mean
+    step_pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in step_pairs:
+        a.record(); one_step(); b.record()
+    torch.cuda.synchronize()
+    median_ms_step = _median([a.elapsed_time(b) for a, b in step_pairs])
 
     # instrumented pass: the same K steps with an event pair around every kernel
     su.shard_profile_reset(plan)
@@ -218,22 +278,35 @@ def headline(args, torch, su, cfgs):
                                "frac": round(gbs / HBM_PEAK_GBS, 4), "avg_us": round(kern[name]["avg_us"], 2),
                                "bytes": b}
     dominant = max(rooflines, key=lambda k: rooflines[k]["avg_us"])
-    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate runs of
-    # this same workload; the summary under profiles/ holds "traffic <kernel> <bytes>" lines
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "bench_%s_lamb_n%d_hbm_traffic.txt" % (cfg.name, N))
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            parts = line.split()
-            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == dominant + "_kernel":
-                traffic = int(parts[2])
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command, kept as a summary
+    # under profiles/ ("traffic <kernel> <bytes>" lines) together with the hash of the library sources it was
+    # measured on.  Counters cannot be read inside this run, so the figure is only reported while that hash is the
+    # hash of the sources in this tree; otherwise traffic is null and traffic_source says why.
+    traffic, traffic_source = None, None
     roof = dict(rooflines[dominant])
     roof["kernel"] = dominant + "_kernel"
     if dominant == "unshard" and unshard_walk["walk"] == "by_variable":
-        # the copy settled on its other order (these tensors collide in memory for the usual one): another
-        # kernel, for which the profile under profiles/ holds no traffic figure
-        roof["kernel"], traffic = "unshard_flat_kernel", None
+        roof["kernel"] = "unshard_flat_kernel"       # the copy was tuned onto its other order: another kernel
+    tname = "bench_%s_lamb_n%d_hbm_traffic.txt" % (cfg.name, N)
+    tpath = os.path.join(ROOT, "profiles", tname)
+    if os.path.exists(tpath):
+        measured_on, found = None, None
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic" and parts[1] == roof["kernel"]:
+                found = int(parts[2])
+            if len(parts) == 2 and parts[0] == "sources_sha16":
+                measured_on = parts[1]
+        current = sources_sha16()
+        fresh = measured_on == current
+        traffic = found if fresh else None
+        traffic_source = {"file": "profiles/" + tname, "measured_on_sources_sha16": measured_on,
+                          "this_build_sources_sha16": current,
+                          "note": "measured by rocprofv3 --pmc in a separate run of this command; reported only while "
+                                  "the library sources are the ones it was measured on" +
+                                  ("" if fresh else " (they are not: traffic withheld)")}
     roof["traffic"] = traffic
+    roof["traffic_source"] = traffic_source
     lamb_us = sum(kern[k]["avg_us"] for k in ("lamb_p1", "norm_reduce", "lamb_p2") if k in kern)
     update_only = {
         "kernels_us": round(lamb_us, 2),
@@ -279,7 +352,7 @@ def headline(args, torch, su, cfgs):
                              w_bf16_out=g16[r])
         su.unshard_format(plan, g16, full16)
 
-    _settle_copy(torch, su, plan, "unshard_format", full16, lambda: su.unshard_format(plan, g16, full16))
+    _settle_copy(torch, su, plan, "unshard_format", g16, full16)
     for _ in range(3):
         one_step_bf16()
     ms16, _ = _time_region(torch, one_step_bf16, args.steps)
@@ -322,6 +395,7 @@ def headline(args, torch, su, cfgs):
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5),
+        "median_ms_per_step": round(median_ms_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s fp32 LAMB N=%d r=%d: shard_format(g) + shard_update_lamb + unshard_format(w)"
@@ -424,7 +498,9 @@ def cpu_baseline_all_cores(cfg, N, r, workers):
 
 
 def table(args, torch, su, cfgs, path):
-    """Every config x stage, kernel time from the library's event pairs; written as JSON."""
+    """Every config x stage; written as JSON.  "us" is the time of one call of the stage with 50 calls back to back
+    inside one event pair after 10 warm-up calls (several kernels in a row are timed together, as they run);
+    "median_us" the median of 50 calls timed one by one; "kernel_us" the per-kernel breakdown."""
     rows = []
     for cfg in cfgs:
         # N = 1 is the replicated update the paper compares against (every replica updates the whole
@@ -490,24 +566,13 @@ def table(args, torch, su, cfgs, path):
                                8 * S + opt_bytes + 4 * N * S + 4 * cfg.total))
             copy_orders = wb.settle_copies(format_all=True)
             for name, fn, kernels, nbytes in stages:
-                for t in range(1, 6):
-                    fn(t)
-                su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
-                iters = 50
-                for t in range(6, 6 + iters):
-                    fn(t)
-                torch.cuda.synchronize()
-                us = 0.0
-                for k in kernels:
-                    n, ms = su.shard_profile_read(plan, k)
-                    us += 1e3 * ms / max(n, 1)
-                su.shard_profile_enable(plan, False)
-                state_bytes = nbytes
+                tm = _time_stage(torch, su, plan, fn, kernels, 10, 50)
+                us = tm["region_us"]
                 rows.append({"config": cfg.name, "N": N, "stage": name + (" (replicated)" if extra else ""), "S": S,
-                             "kernel_us": round(us, 2),
+                             "us": us, "median_us": tm["median_us"], "kernel_us": tm["kernel_us"],
                              "params_per_s": wb.real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                              "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                             "cache_resident": state_bytes < 256e6})
+                             "cache_resident": nbytes < 256e6})
                 if name in copy_orders:
                     rows[-1]["order"] = copy_orders[name]["walk"]
                 print("table:", rows[-1], file=sys.stderr, flush=True)
@@ -529,7 +594,9 @@ def one_stage(args, torch, su, cfgs):
         row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
         print(json.dumps(row))
         return
-    needs_full = (name in ("shard_format", "unshard_format", "shard_format_all", "unshard_format_bf16")
+    bf16_names = ("unshard_format_bf16", "unshard_format_f32_to_bf16", "shard_format_bf16_to_f32", "lamb_step_bf16",
+                  "lamb_fused_step_bf16")
+    needs_full = (name in ("shard_format", "unshard_format", "shard_format_all") + bf16_names
                   or name.endswith("_full_grads")
                   or name.endswith("_step"))
     wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=needs_full, separate=args.separate_tensors,
@@ -583,45 +650,73 @@ def one_stage(args, torch, su, cfgs):
                                     4 * N * S + 4 * cfg.total)
         stages["shard_format_all"] = (lambda t: su.shard_format_all(plan, wb.full_g, wb.gathered), ["format"],
                                       4 * N * S + 4 * cfg.total)
-        if name == "unshard_format_bf16":                       # the all-gather in bfloat16 (Section 4.2)
+        if name in bf16_names:                                  # the all-gather in bfloat16 (Section 4.2)
             g16 = su.gathered_empty(plan, dtype=torch.bfloat16).normal_(0.0, cfg.weight_std)
-            flat16 = torch.empty(cfg.total, dtype=torch.bfloat16, device="cuda")
+            flat16 = torch.empty(cfg.total, dtype=torch.bfloat16, device="cuda").normal_(0.0, cfg.grad_std)
             full16, pos = [], 0
             for n in cfg.numel:
                 full16.append(flat16[pos:pos + n]); pos += n
             full16 = su.FullTensors(plan, full16)
-            stages[name] = (lambda t: su.unshard_format(plan, g16, full16), ["unshard"], 2 * N * S + 2 * cfg.total)
+            model16 = 2 * N * S + 2 * cfg.total
+            stages["unshard_format_bf16"] = (lambda t: su.unshard_format(plan, g16, full16), ["unshard"], model16)
+            # the converting copies: float32 gathered rows -> bfloat16 tensors, bfloat16 gradients -> float32 shard
+            stages["unshard_format_f32_to_bf16"] = (lambda t: su.unshard_format(plan, wb.gathered, full16), ["unshard"],
+                                                    4 * N * S + 2 * cfg.total)
+            stages["shard_format_bf16_to_f32"] = (lambda t: su.shard_format(plan, r, full16, wb.g), ["format"], 6 * S)
+
+            # the step as the paper runs it: float32 update that also emits bf16(w'), bfloat16 gather buffer and tensors
+            def lamb_step_bf16(t):
+                su.shard_format(plan, r, wb.full_g, wb.g)
+                su.shard_update_lamb(plan, r, wb.w, wb.g, wb.m, wb.v, lamb_hp, t, other_replicas_sumsq=wb.other,
+                                     w_bf16_out=g16[r])
+                su.unshard_format(plan, g16, full16)
+
+            def lamb_fused_step_bf16(t):
+                su.shard_update_lamb_full_grads(plan, r, wb.w, wb.full_g, wb.m, wb.v, lamb_hp, t,
+                                                other_replicas_sumsq=wb.other, w_bf16_out=g16[r])
+                su.unshard_format(plan, g16, full16)
+            stages["lamb_step_bf16"] = (lamb_step_bf16, ["format", "lamb_p1", "norm_reduce", "lamb_p2", "unshard"],
+                                        8 * S + 42 * S + model16)
+            stages["lamb_fused_step_bf16"] = (lamb_fused_step_bf16, ["lamb_p1", "norm_reduce", "lamb_p2", "unshard"],
+                                              42 * S + model16)
     if name not in stages:
         raise SystemExit("unknown --stage %s" % name)
     fn, kernels, nbytes = stages[name]
     copy_orders = wb.settle_copies(format_all=name == "shard_format_all") if needs_full else {}
-    if name == "unshard_format_bf16":
-        copy_orders = {"unshard_format": _settle_copy(torch, su, plan, "unshard_format", g16, full16)}
+    if name in bf16_names and name != "shard_format_bf16_to_f32":
+        src = wb.gathered if name == "unshard_format_f32_to_bf16" else g16
+        copy_orders = {"unshard_format": _settle_copy(torch, su, plan, "unshard_format", src, full16)}
     # --cold: a 1 GiB device copy between launches of the stage, so that nothing of the previous launch is
     # left in the 256 MB memory-side cache (between two real steps a forward and a backward pass run); the
     # event pairs time the library's kernels only
     spill = torch.empty((2, 1 << 28), dtype=torch.float32, device="cuda") if args.cold else None
-    for t in range(1, 1 + max(args.warmup, 1)):
-        fn(t)
-    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
-    for t in range(100, 100 + args.steps):
-        if spill is not None:
+    if spill is None:
+        tm = _time_stage(torch, su, plan, fn, kernels, args.warmup, args.steps)
+        per, us, median_us = tm["kernel_us"], tm["region_us"], tm["median_us"]
+    else:
+        # cold: only the library's own event pairs see the kernels without the spill
+        for t in range(1, 1 + max(args.warmup, 1)):
+            fn(t)
+        su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
+        for t in range(100, 100 + args.steps):
             spill[1].copy_(spill[0])
-        fn(t)
-    torch.cuda.synchronize()
-    per = {}
-    for k in kernels:
-        n, ms = su.shard_profile_read(plan, k)
-        per[k] = round(1e3 * ms / max(n, 1), 2)
-    us = sum(per.values())
+            fn(t)
+        torch.cuda.synchronize()
+        per = {}
+        for k in kernels:
+            n, ms = su.shard_profile_read(plan, k)
+            per[k] = round(1e3 * ms / args.steps, 2)
+        us, median_us = sum(per.values()), None
     print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
-                      "total_us": round(us, 2), "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                      "total_us": round(us, 2), "median_us": median_us,
+                      "timing": "sum of per-kernel event pairs" if args.cold else "region: calls back to back in one event pair",
+                      "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                       "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold),
                       "separate_tensors": bool(args.separate_tensors), "copy_orders": copy_orders}))
     wb.free()
 
 
-def _adafactor_row(cfg, N, torch, su, warmup=5, iters=50):
+def _adafactor_row(cfg, N, torch, su, warmup=10, iters=50):
     """Adafactor on the row plan of the same variables (matrices by rows, vectors as n x 1): 24 B/slot
     (g and w read by the reductions, g by the clipping sum, g and w read and w written by the update)."""
     shapes = [(s[0], s[1]) if len(s) == 2 else (s[0], 1) for s in cfg.shapes]
@@ -635,20 +730,14 @@ def _adafactor_row(cfg, N, torch, su, warmup=5, iters=50):
     R = torch.zeros(max(total_rows, 1), dtype=torch.float32, device="cuda")
     C = torch.zeros(max(total_cols, 1), dtype=torch.float32, device="cuda")
     hp = {"eps1": 1e-30, "eps2": 1e-3, "clip_threshold": 1.0, "decay_exponent": 0.8, "max_rho": 1e-2}
-    for t in range(1, 1 + max(warmup, 1)):
-        su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
-    su.shard_profile_reset(plan); su.shard_profile_enable(plan, True)
-    for t in range(100, 100 + iters):
-        su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t)
-    torch.cuda.synchronize()
-    us = 0.0
-    for k in ("rowcol_p1", "rowcol_p2", "adafactor_state", "adafactor_usq", "adafactor_apply"):
-        n, ms = su.shard_profile_read(plan, k)
-        us += 1e3 * ms / iters
-    su.shard_profile_enable(plan, False)
+    tm = _time_stage(torch, su, plan, lambda t: su.shard_update_adafactor(plan, 0, w, g, R, C, hp, t),
+                     ("rowcol_p1", "rowcol_p2", "adafactor_state", "adafactor_usq", "item_total", "adafactor_apply"),
+                     warmup, iters)
+    us = tm["region_us"]
     real = sum(plan.real_count(0))
     nbytes = 24 * S
-    row = {"config": cfg.name, "N": N, "stage": "adafactor (row plan)", "S": S, "kernel_us": round(us, 2),
+    row = {"config": cfg.name, "N": N, "stage": "adafactor (row plan)", "S": S, "us": us, "total_us": us,
+           "median_us": tm["median_us"], "kernel_us": tm["kernel_us"],
            "params_per_s": real / (us * 1e-6), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
            "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cache_resident": nbytes < 256e6}
     plan.free()

@@ -95,8 +95,8 @@ enum {
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
   SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9, SHARD_K_ROWCOL_P1 = 10, SHARD_K_ROWCOL_P2 = 11,
   SHARD_K_ADAFACTOR_STATE = 12, SHARD_K_ADAFACTOR_USQ = 13, SHARD_K_ADAFACTOR_APPLY = 14,
-  SHARD_K_PLAIN_COPY = 15,
-  SHARD_K_COUNT = 16
+  SHARD_K_PLAIN_COPY = 15, SHARD_K_ITEM_TOTAL = 16,
+  SHARD_K_COUNT = 17
 };
 
 const char* shard_strerror(int status);

@@ -17,7 +17,7 @@ SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
               "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11,
-              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14, "plain_copy": 15}
+              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14, "plain_copy": 15, "item_total": 16}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -251,7 +251,17 @@ def shard_plan_tune_copy_walk(plan: Plan, copy: str, gathered: torch.Tensor, ful
 
 
 def _hp(cls, hp: Dict[str, float]):
-    return cls(**{name: float(hp.get(name, 0.0)) for name, _ in cls._fields_})
+    """The C struct of an optimizer's hyper-parameters.  Every field must be given except weight_decay
+    (0 if absent); a key the struct does not have is an error, so that a misspelt name cannot silently
+    become a zero."""
+    fields = [name for name, _ in cls._fields_]
+    unknown = sorted(set(hp) - set(fields))
+    if unknown:
+        raise ValueError("%s: unknown hyper-parameter(s) %s (expected %s)" % (cls.__name__, unknown, fields))
+    missing = [name for name in fields if name not in hp and name != "weight_decay"]
+    if missing:
+        raise ValueError("%s: missing hyper-parameter(s) %s" % (cls.__name__, missing))
+    return cls(**{name: float(hp.get(name, 0.0)) for name in fields})
 
 
 def shard_update_adam(plan: Plan, r: int, w, g, m, v, hp: Dict[str, float], step: int, w_bf16_out=None, stream=None):
@@ -448,6 +458,10 @@ ADAFACTOR_DEFAULTS = {"eps1": 1e-30, "eps2": 1e-3, "clip_threshold": 1.0, "decay
 
 
 def _adafactor_hp(hp: Dict[str, float]):
+    """Every field has the published default (ADAFACTOR_DEFAULTS); unknown keys are an error."""
+    unknown = sorted(set(hp) - set(ADAFACTOR_DEFAULTS))
+    if unknown:
+        raise ValueError("AdafactorHP: unknown hyper-parameter(s) %s (expected %s)" % (unknown, sorted(ADAFACTOR_DEFAULTS)))
     return AdafactorHP(**{name: float(hp.get(name, ADAFACTOR_DEFAULTS[name])) for name, _ in AdafactorHP._fields_})
 
 

@@ -138,6 +138,7 @@ const char* const kKernelNames[SHARD_K_COUNT] = {
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
     "lars_p1_kernel", "lars_p2_kernel", "rowcol_p1_kernel", "rowcol_p2_kernel",
     "adafactor_state_kernel", "adafactor_usq_kernel", "adafactor_apply_kernel", "plain_copy_kernel",
+    "item_total_kernel",
 };
 
 // Step-dependent constants of Adafactor, taken in double and rounded once.

@@ -43,10 +43,11 @@ __global__ __launch_bounds__(kCopyBlock) void plain_copy_kernel(const u4* __rest
 }
 
 // ---- shard_format / unshard_format ----------------------------------------------------------------
-// A unit is what one lane moves per access: 4 elements whenever float32 is involved (one 128-bit
-// access on the float32 side, 64 bits on the bfloat16 side), 8 elements for bfloat16 -> bfloat16
-// (128 bits on both sides).  Consecutive lanes take consecutive units, so every wavefront access
-// covers one contiguous span of memory.
+// A unit is what one lane moves at a time: 8 elements when the destination is bfloat16, so that every store is
+// a 128-bit access (from float32 that is two 128-bit loads; with 4-element units and 64-bit stores the
+// float32 -> bfloat16 unshard of the 340 M-parameter model ran at 5.2 instead of 5.8 TB/s), 4 elements when it is
+// float32 (bfloat16 -> float32 then loads 64 bits per lane, which measured 4 % faster than 8-element units).
+// Consecutive lanes take consecutive units, so the accesses of a wavefront cover one contiguous span of memory.
 
 template <int DT> struct ElemOf;
 template <> struct ElemOf<SHARD_F32> { typedef uint32_t type; };
@@ -54,41 +55,56 @@ template <> struct ElemOf<SHARD_BF16> { typedef uint16_t type; };
 
 template <int SRC, int DST>
 struct UnitOf {
-  static constexpr int n = (SRC == SHARD_BF16 && DST == SHARD_BF16) ? 8 : 4;
+  static constexpr int n = DST == SHARD_BF16 ? 8 : 4;
 };
 
 template <typename Pol, int DT, int UNIT>
 __device__ __forceinline__ void load_unit(const typename ElemOf<DT>::type* p, uint32_t (&x)[UNIT]) {
-  if constexpr (DT == SHARD_F32) {
-    static_assert(UNIT == 4, "float32 units are 4 elements");
+  if constexpr (DT == SHARD_F32 && UNIT == 4) {
     const u4 a = ld<Pol::RO>((const u4*)p);
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-  } else if constexpr (UNIT == 8) {
+  } else if constexpr (DT == SHARD_F32) {
+    static_assert(UNIT == 8, "float32 units are 4 or 8 elements");
     const u4 a = ld<Pol::RO>((const u4*)p);
-    x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
-    x[4] = a.z & 0xFFFFu; x[5] = a.z >> 16; x[6] = a.w & 0xFFFFu; x[7] = a.w >> 16;
+    const u4 b = ld<Pol::RO>((const u4*)p + 1);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
   } else {
-    const u2 a = ld<Pol::RO>((const u2*)p);
-    x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
+    if constexpr (UNIT == 8) {
+      const u4 a = ld<Pol::RO>((const u4*)p);
+      x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
+      x[4] = a.z & 0xFFFFu; x[5] = a.z >> 16; x[6] = a.w & 0xFFFFu; x[7] = a.w >> 16;
+    } else {
+      const u2 a = ld<Pol::RO>((const u2*)p);
+      x[0] = a.x & 0xFFFFu; x[1] = a.x >> 16; x[2] = a.y & 0xFFFFu; x[3] = a.y >> 16;
+    }
   }
 }
 template <typename Pol, int DT, int UNIT>
 __device__ __forceinline__ void store_unit(typename ElemOf<DT>::type* p, const uint32_t (&x)[UNIT]) {
-  if constexpr (DT == SHARD_F32) {
-    static_assert(UNIT == 4, "float32 units are 4 elements");
+  if constexpr (DT == SHARD_F32 && UNIT == 4) {
     u4 a;
     a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
     st<Pol::ST>((u4*)p, a);
-  } else if constexpr (UNIT == 8) {
+  } else if constexpr (DT == SHARD_F32) {
+    static_assert(UNIT == 8, "float32 units are 4 or 8 elements");
+    u4 a, b;
+    a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
+    b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
+    st<Pol::ST>((u4*)p, a);
+    st<Pol::ST>((u4*)p + 1, b);
+  } else {
+    static_assert(UNIT == 8, "bfloat16 units are 8 elements");
     u4 a;
     a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16); a.z = x[4] | (x[5] << 16); a.w = x[6] | (x[7] << 16);
     st<Pol::ST>((u4*)p, a);
-  } else {
-    u2 a;
-    a.x = x[0] | (x[1] << 16); a.y = x[2] | (x[3] << 16);
-    st<Pol::ST>((u2*)p, a);
   }
 }
+// One replica's formatting takes two units per thread only where the tile then still is the default chunk
+// (2048 slots): with 8-element units a second one would send every chunk down the predicated path.
+template <int SRC, int DST>
+constexpr int format_unroll() { return UnitOf<SRC, DST>::n == 8 ? 1 : kFormatUnroll; }
+
 template <int SRC, int DST>
 __device__ __forceinline__ uint32_t convert(uint32_t b) {
   if constexpr (SRC == DST) return b;
@@ -339,7 +355,7 @@ __global__ __launch_bounds__(kCopyBlock) void format_kernel(const VarDesc* __res
                                                         const void* const* __restrict__ ptrs, void* out, int r0,
                                                         int64_t row_stride, int n_chunks, int tiles_per_chunk,
                                                         int wg_per_replica) {
-  reformat_body<PolFormat, SRC, DST, kFormatUnroll, VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
+  reformat_body<PolFormat, SRC, DST, format_unroll<SRC, DST>(), VEC, false>(vars, chunks, ptrs, out, r0, row_stride, n_chunks, tiles_per_chunk, wg_per_replica);
 }
 
 template <int SRC, int DST, bool VEC>
@@ -395,7 +411,7 @@ template <int SRC, int DST, int MODE>
 void reformat_dispatch(shard_plan_t* p, int r0, int replicas, const void* const* tab, void* packed, int64_t stride,
                        bool vec, bool by_variable, hipStream_t stream) {
   const int n_chunks = (int)p->chunks.size();
-  constexpr int U = MODE == 0 ? kFormatUnroll : (MODE == 1 ? kUnshardUnroll : kFormatAllUnroll);
+  constexpr int U = MODE == 0 ? format_unroll<SRC, DST>() : (MODE == 1 ? kUnshardUnroll : kFormatAllUnroll);
   constexpr int TILE = kCopyBlock * U * UnitOf<SRC, DST>::n;
   const int tiles_per_chunk = (p->chunk + TILE - 1) / TILE;
   // plan_build keeps n_chunks * N * (chunk / 1024) below 2^31, and a tile is at least 1024 slots

@@ -56,6 +56,7 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       }
       const int64_t len = (per + align - 1) / align * align;
       if (len > kMax / N || pos > kMax - len) return SHARD_EINVAL;
+      if (n > kMax - total) return SHARD_EINVAL;           // the model itself must be countable
       p->n[i] = n;
       p->L[i] = len;
       p->stride[i] = cols ? per : len;
@@ -71,7 +72,15 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
     p->S = pos;
     p->total = total;
 
+    // the formatting kernels launch one workgroup per (replica, chunk, 1024-slot tile): the whole table must fit a
+    // launch, which is checked before anything of it is built
+    int64_t n_chunks = 0;
+    for (int i = 0; i < V; ++i) {
+      n_chunks += (p->L[i] + chunk - 1) / chunk;
+      if (n_chunks * (chunk / 1024) > (int64_t)std::numeric_limits<int32_t>::max() / N) return SHARD_EINVAL;
+    }
     p->chunks.clear();
+    p->chunks.reserve((size_t)n_chunks);
     for (int i = 0; i < V; ++i) {
       VarDesc& vd = p->vars[i];
       vd.n = p->n[i];
@@ -80,12 +89,8 @@ int plan_build(shard_plan_t* p, int V, const int64_t* numel, const int64_t* cols
       vd.stride = p->stride[i];
       vd.flags = p->flags[i];
       vd.reserved = 0;
-      const int64_t count = (p->L[i] + chunk - 1) / chunk;
-      // the formatting kernels launch one workgroup per (replica, chunk, 1024-slot tile)
-      if (((int64_t)p->chunks.size() + count) * (chunk / 1024) > (int64_t)std::numeric_limits<int32_t>::max() / N)
-        return SHARD_EINVAL;
       vd.first_chunk = (int32_t)p->chunks.size();
-      vd.n_chunks = (int32_t)count;
+      vd.n_chunks = (int32_t)((p->L[i] + chunk - 1) / chunk);
       for (int64_t k0 = 0; k0 < p->L[i]; k0 += chunk) {
         ChunkDesc cd;
         cd.k0 = k0;

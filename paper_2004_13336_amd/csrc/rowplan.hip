@@ -615,7 +615,7 @@ hipError_t launch_adafactor_moments(shard_plan_t* p, int r, const float* g, floa
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  ProfScope ps(p, SHARD_K_ADAFACTOR_STATE, stream);
+  ProfScope ps(p, SHARD_K_ITEM_TOTAL, stream);
   hipLaunchKernelGGL(item_total_kernel, dim3((unsigned)p->V), dim3(kBlock), 0, stream, vars, (const float*)upart, other_usq,
                      usq_local, usq_total);
   return hipGetLastError();

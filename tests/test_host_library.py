@@ -380,3 +380,22 @@ def test_bench_refuses_more_than_one_gpu():
                           timeout=120)
     assert proc.returncode != 0
     assert "ONE GPU" in (proc.stdout + proc.stderr)
+
+
+def test_hyper_parameter_dicts_are_checked_strictly():
+    """A missing or misspelt hyper-parameter is an error, not a silent zero; only weight_decay has a default."""
+    from paper_2004_13336_amd import api
+    from paper_2004_13336_amd._lib import AdamHP, LarsHP, MomentumHP
+    ok = api._hp(AdamHP, {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8})
+    assert ok.weight_decay == 0.0 and abs(ok.beta2 - 0.999) < 1e-6
+    with pytest.raises(ValueError, match="missing"):
+        api._hp(AdamHP, {"lr": 1e-3, "beta1": 0.9, "eps": 1e-8})
+    with pytest.raises(ValueError, match="unknown"):
+        api._hp(AdamHP, {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8, "weight_decya": 0.01})
+    with pytest.raises(ValueError, match="missing"):
+        api._hp(MomentumHP, {"lr": 0.1})
+    with pytest.raises(ValueError, match="missing"):
+        api._hp(LarsHP, {"lr": 0.1, "mu": 0.9, "weight_decay": 0.0, "eps": 0.0})
+    with pytest.raises(ValueError, match="unknown"):
+        api._adafactor_hp({"clip": 1.0})
+    assert api._adafactor_hp({}).clip_threshold == 1.0
