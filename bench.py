@@ -57,7 +57,9 @@ def parse_args():
                          "(adam | momentum | lars | lamb | adafactor | shard_format | unshard_format | shard_format_all | "
                          "adam_full_grads | momentum_full_grads | lamb_full_grads | lars_full_grads | "
                          "adam_step | momentum_step | lars_step | lamb_step = format g + update + unshard w | unshard_format_bf16 | "
-                         "unshard_format_f32_to_bf16 | shard_format_bf16_to_f32 | lamb_step_bf16 | lamb_fused_step_bf16) "
+                         "unshard_format_f32_to_bf16 | shard_format_bf16_to_f32 | lamb_step_bf16 | lamb_fused_step_bf16 | "
+                         "adam_shape_probe = the flat Adam update in every launch shape | copy_order_probe = both orders of the "
+                         "whole-model copies on tensors placed at several distances) "
                          "and print its HIP-event timing: the command to put under rocprofv3 for that kernel")
     ap.add_argument("--separate-tensors", action="store_true",
                     help="with --stage: every full tensor is an allocation of its own from torch's caching allocator "
@@ -65,6 +67,9 @@ def parse_args():
                          "instead of a slice of one flat buffer")
     ap.add_argument("--copy-order", default="auto", choices=["auto", "by_replica", "by_variable"],
                     help="with --stage: shard_plan_set_copy_walk before anything runs")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --stage: also record the stage in a HIP graph (stream capture) and time its replays "
+                         "beside the eager launches")
     ap.add_argument("--cold", action="store_true",
                     help="with --stage: flush the memory-side cache (a 1 GiB copy) before every launch of the stage")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -594,6 +599,12 @@ def one_stage(args, torch, su, cfgs):
         row = _adafactor_row(cfg, N, torch, su, warmup=args.warmup, iters=args.steps)
         print(json.dumps(row))
         return
+    if name == "adam_shape_probe":
+        _adam_shape_probe(args, cfg, N, r, torch, su)
+        return
+    if name == "copy_order_probe":
+        _copy_order_probe(args, N, torch, su)
+        return
     bf16_names = ("unshard_format_bf16", "unshard_format_f32_to_bf16", "shard_format_bf16_to_f32", "lamb_step_bf16",
                   "lamb_fused_step_bf16")
     needs_full = (name in ("shard_format", "unshard_format", "shard_format_all") + bf16_names
@@ -707,12 +718,111 @@ def one_stage(args, torch, su, cfgs):
             n, ms = su.shard_profile_read(plan, k)
             per[k] = round(1e3 * ms / args.steps, 2)
         us, median_us = sum(per.values()), None
+    extra = {}
+    if args.graph and spill is None:
+        # the same stage recorded once with stream capture and replayed: what launching costs beyond the kernels
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            fn(5000)                              # the lists of tensors become resident on this stream's device
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fn(5001)
+        torch.cuda.synchronize()
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(); a.record()
+        for _ in range(args.steps):
+            graph.replay()
+        b.record(); torch.cuda.synchronize()
+        extra["graph_replay_us"] = round(1e3 * a.elapsed_time(b) / args.steps, 2)
+        del graph
+    if name.startswith(("unshard_format", "shard_format_all")) and spill is None:
+        # the practical ceiling for this copy: a plain device copy of the same number of bytes, same run
+        half = nbytes // 2 // 16 * 16
+        ca = torch.empty(half, dtype=torch.uint8, device="cuda").zero_(); cb = torch.empty(half, dtype=torch.uint8, device="cuda")
+        tm_copy = _time_stage(torch, su, plan, lambda t: su.shard_profile_plain_copy(plan, cb, ca), ["plain_copy"],
+                              args.warmup, args.steps)
+        extra["plain_copy_same_bytes_us"] = tm_copy["region_us"]
     print(json.dumps({"config": cfg.name, "N": N, "stage": name, "S": S, "launches": args.steps, "kernel_us": per,
-                      "total_us": round(us, 2), "median_us": median_us,
+                      "total_us": round(us, 2), "median_us": median_us, **extra,
                       "timing": "sum of per-kernel event pairs" if args.cold else "region: calls back to back in one event pair",
                       "bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
                       "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "cold": bool(args.cold),
                       "separate_tensors": bool(args.separate_tensors), "copy_orders": copy_orders}))
+    wb.free()
+
+
+def _copy_order_probe(args, N, torch, su):
+    """Where the caller's tensors lie decides which order of a whole-model copy is faster.  A uniform model of 320
+    float32 matrices of 1024 x 1024 (2.69 GB moved per copy at N = 8), each tensor a fixed distance after the
+    previous one; for four distances: unshard_format and shard_format_all with the order forced either way, and
+    what shard_plan_tune_copy_walk settles on.  --config is ignored."""
+    V, n = 320, 1024 * 1024
+    rows = []
+    for skew_bytes in (0, 256, 4096, 16384):
+        skew = skew_bytes // 4
+        flat = torch.empty(V * (n + skew) + 64, dtype=torch.float32, device="cuda").normal_(0, 1e-3)
+        row = {"distance": "4 MiB + %d B" % skew_bytes}
+        for order in ("by_replica", "by_variable", "auto"):
+            plan = su.shard_plan_bind(su.shard_plan([n] * V, N, 8))
+            su.shard_plan_set_copy_walk(plan, order)
+            full = su.FullTensors(plan, [flat[i * (n + skew): i * (n + skew) + n] for i in range(V)])
+            gathered = su.gathered_empty(plan).normal_(0, 0.02)
+            for copy, fn, k in (("unshard_format", lambda t: su.unshard_format(plan, gathered, full), "unshard"),
+                                ("shard_format_all", lambda t: su.shard_format_all(plan, full, gathered), "format")):
+                picked = None
+                if order == "auto":
+                    picked = su.shard_plan_tune_copy_walk(plan, copy, gathered, full)[0]
+                tm = _time_stage(torch, su, plan, fn, [k], args.warmup, args.steps)
+                row["%s %s" % (copy, "tuned" if order == "auto" else order)] = tm["region_us"]
+                if picked:
+                    row["%s tuned picks" % copy] = picked
+            plan.free()
+            del full, gathered
+        rows.append(row)
+        print("spacing:", row, file=sys.stderr, flush=True)
+        del flat
+        torch.cuda.empty_cache()
+    print(json.dumps({"stage": "copy_order_probe", "N": N, "model": "320 float32 matrices of 1024 x 1024", "launches": args.steps,
+                      "rows": rows}))
+
+
+def _adam_shape_probe(args, cfg, N, r, torch, su):
+    """The measurement behind the library's choice of launch shape: the flat Adam update of this shard in every
+    shape shard_profile_adam_shape offers (threads per workgroup x workgroups resident per CU), each timed as
+    --steps launches back to back, then the shape the library itself picks and a plain copy of the same bytes."""
+    wb = Workbench(cfg, N, r, args.chunk, torch, su, want_full=False)
+    plan, S = wb.plan, wb.S
+    hp = {"lr": 1e-3, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8, "weight_decay": 0.0}
+    nbytes = 28 * S
+    rows = []
+
+    def region(fn):
+        for t in range(1, 4):
+            fn(t)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(); a.record()
+        for t in range(10, 10 + args.steps):
+            fn(t)
+        b.record(); torch.cuda.synchronize()
+        return 1e3 * a.elapsed_time(b) / args.steps
+    for block in (256, 128):
+        for k in (0, 8, 6, 5, 4, 3):
+            us = region(lambda t: su.shard_profile_adam_shape(plan, wb.w, wb.g, wb.m, wb.v, hp, t, block, k))
+            rows.append({"threads": block, "workgroups_per_cu": k, "lds_bytes": 0 if k == 0 else 160 * 1024 // k - 1024,
+                         "us": round(us, 1), "GBps": round(nbytes / us / 1e3, 1)})
+            print("shape:", rows[-1], file=sys.stderr, flush=True)
+    us_lib = region(lambda t: su.shard_update_adam(plan, r, wb.w, wb.g, wb.m, wb.v, hp, t))
+    half = nbytes // 2 // 16 * 16
+    ca = torch.empty(half, dtype=torch.uint8, device="cuda").zero_(); cb = torch.empty(half, dtype=torch.uint8, device="cuda")
+    us_copy = region(lambda t: su.shard_profile_plain_copy(plan, cb, ca))
+    print(json.dumps({"config": cfg.name, "N": N, "stage": "adam_shape_probe", "S": S, "launches": args.steps,
+                      "bytes": nbytes, "shapes": rows,
+                      "library_choice": {"us": round(us_lib, 1), "GBps": round(nbytes / us_lib / 1e3, 1)},
+                      "plain_copy_same_bytes": {"us": round(us_copy, 1), "GBps": round(2 * half / us_copy / 1e3, 1)}}))
     wb.free()
 
 

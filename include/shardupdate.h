@@ -95,8 +95,8 @@ enum {
   SHARD_K_LAMB_P1 = 4, SHARD_K_NORM_REDUCE = 5, SHARD_K_LAMB_P2 = 6, SHARD_K_PTR_TABLE = 7,
   SHARD_K_LARS_P1 = 8, SHARD_K_LARS_P2 = 9, SHARD_K_ROWCOL_P1 = 10, SHARD_K_ROWCOL_P2 = 11,
   SHARD_K_ADAFACTOR_STATE = 12, SHARD_K_ADAFACTOR_USQ = 13, SHARD_K_ADAFACTOR_APPLY = 14,
-  SHARD_K_PLAIN_COPY = 15, SHARD_K_ITEM_TOTAL = 16,
-  SHARD_K_COUNT = 17
+  SHARD_K_PLAIN_COPY = 15, SHARD_K_ITEM_TOTAL = 16, SHARD_K_ADAM_SHAPE = 17,
+  SHARD_K_COUNT = 18
 };
 
 const char* shard_strerror(int status);
@@ -490,6 +490,18 @@ int shard_profile_reset(shard_plan_t* plan);
  * dst, src: device pointers, 16-byte aligned, not overlapping; bytes: a positive multiple of 16.
  * Errors: SHARD_EINVAL, SHARD_EALIGN, SHARD_EHIP. */
 int shard_profile_plain_copy(shard_plan_t* plan, void* dst, const void* src, size_t bytes, shard_stream_t stream);
+
+/* A second measurement aid: shard_update_adam (without the bf16 output) in a launch shape the caller names instead
+ * of the one the library chooses by shard size, timed under the kernel id SHARD_K_ADAM_SHAPE.  It exists so that
+ * the measurement behind the library's choice can be repeated: how fast an update of 4 streams read and 3 written
+ * runs depends on how many bytes a CU keeps in flight, i.e. on threads per workgroup and on how many workgroups stay
+ * resident (capped by reserving LDS the kernel never touches).  The same kernels run, so the state ends up
+ * bit for bit as after shard_update_adam.
+ *   block_threads      128 or 256
+ *   workgroups_per_cu  0 = no cap (what the hardware fits), else 3 .. 16
+ * Other arguments and errors as shard_update_adam; SHARD_EINVAL for a shape outside the above. */
+int shard_profile_adam_shape(shard_plan_t* plan, float* w, const float* g, float* m, float* v, const shard_adam_hp* hp,
+                             int64_t step, int block_threads, int workgroups_per_cu, shard_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -100,6 +100,7 @@ SIGNATURES = {
     "shard_profile_read": (C.c_int, [_P, C.c_int, _I64P, C.POINTER(C.c_double)]),
     "shard_profile_reset": (C.c_int, [_P]),
     "shard_profile_plain_copy": (C.c_int, [_P, _P, _P, C.c_size_t, _P]),
+    "shard_profile_adam_shape": (C.c_int, [_P, _P, _P, _P, _P, C.POINTER(AdamHP), C.c_int64, C.c_int, C.c_int, _P]),
     "shard_plan_release_captured_tables": (C.c_int, [_P]),
     "shard_plan_set_copy_walk": (C.c_int, [_P, C.c_int]),
     "shard_plan_copy_walk": (C.c_int, [_P, C.c_int, _P, C.POINTER(C.c_int), C.POINTER(C.c_float)]),

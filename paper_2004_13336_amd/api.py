@@ -17,7 +17,7 @@ SHARD_F32, SHARD_BF16 = 0, 1
 SHARD_VAR_NO_DECAY, SHARD_VAR_NO_ADAPT = 1, 2
 KERNEL_IDS = {"format": 0, "unshard": 1, "adam": 2, "momentum": 3, "lamb_p1": 4, "norm_reduce": 5,
               "lamb_p2": 6, "ptr_table": 7, "lars_p1": 8, "lars_p2": 9, "rowcol_p1": 10, "rowcol_p2": 11,
-              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14, "plain_copy": 15, "item_total": 16}
+              "adafactor_state": 12, "adafactor_usq": 13, "adafactor_apply": 14, "plain_copy": 15, "item_total": 16, "adam_shape": 17}
 
 _DTYPES = {torch.float32: SHARD_F32, torch.bfloat16: SHARD_BF16}
 
@@ -536,6 +536,16 @@ def shard_profile_plain_copy(plan: Plan, dst: torch.Tensor, src: torch.Tensor, s
         raise ValueError("dst and src must be contiguous CUDA tensors of equal size")
     _check(lib().shard_profile_plain_copy(plan.handle, C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes,
                                           _stream(stream)), "shard_profile_plain_copy")
+
+
+def shard_profile_adam_shape(plan: Plan, w, g, m, v, hp, step: int, block_threads: int, workgroups_per_cu: int,
+                             stream=None) -> None:
+    """shard_update_adam in a named launch shape (measurement aid): 128 or 256 threads, 0 or 3..16 workgroups per CU."""
+    f = torch.float32
+    _check(lib().shard_profile_adam_shape(plan.handle, _dev(w, plan.S, f, "w"), _dev(g, plan.S, f, "g"),
+                                          _dev(m, plan.S, f, "m"), _dev(v, plan.S, f, "v"), C.byref(_hp(AdamHP, hp)),
+                                          int(step), int(block_threads), int(workgroups_per_cu), _stream(stream)),
+           "shard_profile_adam_shape")
 
 
 # ---- replica arrays (host only) ---------------------------------------------------------------------

@@ -138,7 +138,7 @@ const char* const kKernelNames[SHARD_K_COUNT] = {
     "lamb_p1_kernel", "norm_reduce_kernel", "lamb_p2_kernel", "ptr_table_kernel",
     "lars_p1_kernel", "lars_p2_kernel", "rowcol_p1_kernel", "rowcol_p2_kernel",
     "adafactor_state_kernel", "adafactor_usq_kernel", "adafactor_apply_kernel", "plain_copy_kernel",
-    "item_total_kernel",
+    "item_total_kernel", "adam_kernel (named shape)",
 };
 
 // Step-dependent constants of Adafactor, taken in double and rounded once.
@@ -912,6 +912,21 @@ int shard_profile_reset(shard_plan_t* p) {
     p->prof_ms[i] = 0.0;
   }
   return SHARD_OK;
+}
+
+int shard_profile_adam_shape(shard_plan_t* p, float* w, const float* g, float* m, float* v, const shard_adam_hp* hp,
+                             int64_t step, int block_threads, int workgroups_per_cu, shard_stream_t stream) {
+  if (p == nullptr || hp == nullptr) return SHARD_EINVAL;
+  if (block_threads != 128 && block_threads != 256) return SHARD_EINVAL;
+  if (workgroups_per_cu != 0 && (workgroups_per_cu < 3 || workgroups_per_cu > 16)) return SHARD_EINVAL;
+  AdamK k;
+  int rc = fold_adam(hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, step, &k);
+  if (rc != SHARD_OK) return rc;
+  if (p->S == 0) return SHARD_OK;
+  if ((rc = check_shard_ptr(w)) != SHARD_OK || (rc = check_shard_ptr(g)) != SHARD_OK ||
+      (rc = check_shard_ptr(m)) != SHARD_OK || (rc = check_shard_ptr(v)) != SHARD_OK)
+    return rc;
+  return hip_status(launch_adam_shape(p, w, g, m, v, k, block_threads, workgroups_per_cu, as_stream(stream)));
 }
 
 int shard_profile_plain_copy(shard_plan_t* p, void* dst, const void* src, size_t bytes, shard_stream_t stream) {

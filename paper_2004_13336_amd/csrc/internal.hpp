@@ -231,6 +231,9 @@ hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, floa
                        hipStream_t stream);
 hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, void* w16, const MomentumK& k,
                            hipStream_t stream);
+// block: 128 or 256 threads; workgroups_per_cu: 0 = no cap, else 3..16 resident workgroups per CU
+hipError_t launch_adam_shape(shard_plan_t* p, float* w, const float* g, float* m, float* v, const AdamK& k, int block,
+                             int workgroups_per_cu, hipStream_t stream);
 
 // g_source 0: g is the packed shard gradient; 1 / 2: g_full is the device table of full float32 /
 // bfloat16 gradient tensors and g is unused.

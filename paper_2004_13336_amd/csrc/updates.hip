@@ -867,6 +867,25 @@ hipError_t launch_adam(shard_plan_t* p, float* w, const float* g, float* m, floa
   return hipGetLastError();
 }
 
+// The flat Adam update in a launch shape the caller names (shard_profile_adam_shape, a measurement aid): the same
+// kernels as launch_adam, so the results are the same bits; only the time differs.
+hipError_t launch_adam_shape(shard_plan_t* p, float* w, const float* g, float* m, float* v, const AdamK& k,
+                             int block, int workgroups_per_cu, hipStream_t stream) {
+  if (p->S == 0) return hipSuccess;
+  ProfScope ps(p, SHARD_K_ADAM_SHAPE, stream);
+  const int64_t n4 = p->S >> 2;
+  const int tail = (int)(p->S & 3);
+  const unsigned lds = workgroups_per_cu > 0 ? (unsigned)(160 * 1024 / workgroups_per_cu - 1024) : 0u;
+  uint16_t* none = nullptr;
+  if (block == 128)
+    hipLaunchKernelGGL((adam_kernel<128, false>), dim3(flat_grid(n4, 128, kAdamUnroll)), dim3(128), lds, stream, w, g, m,
+                       v, none, n4, tail, k);
+  else
+    hipLaunchKernelGGL((adam_kernel<256, false>), dim3(flat_grid(n4, 256, kAdamUnroll)), dim3(256), lds, stream, w, g, m,
+                       v, none, n4, tail, k);
+  return hipGetLastError();
+}
+
 hipError_t launch_momentum(shard_plan_t* p, float* w, const float* g, float* m, void* w16, const MomentumK& k,
                            hipStream_t stream) {
   if (p->S == 0) return hipSuccess;

@@ -260,3 +260,27 @@ def test_lamb_and_lars_on_a_shard_past_the_large_switch():
     for a, b in zip(lm, oracle.unshard_format(oplan, to_host(M)[None, :])):
         assert_first_moment_close(b, a, LARS["lr"] * 1e-3, 10)
     plan.free()
+
+
+def test_every_named_launch_shape_of_adam_gives_the_same_bits():
+    """shard_profile_adam_shape runs the update's own kernels in the shape the caller names; whatever the shape, the
+    state must come out bit for bit as from shard_update_adam (same arithmetic per element), outputs guarded."""
+    n = 3 * 1024 * 1024 + 1027
+    plan = su.shard_plan([n], 1, 1)
+    ws, gs = gen_weights_grads(311, [n], 0.02, 1e-3)
+    W, G = ws[0], gs[0]
+    ref = [Guarded(n, init=W), Guarded(n, init=np.zeros(n, np.float32)), Guarded(n, init=np.zeros(n, np.float32))]
+    g = Guarded(n, init=G)
+    su.shard_update_adam(plan, 0, ref[0].t, g.t, ref[1].t, ref[2].t, ADAM, 1)
+    for block in (128, 256):
+        for k in (0, 3, 5, 8, 16):
+            w, m, v = Guarded(n, init=W), Guarded(n), Guarded(n)
+            su.shard_profile_adam_shape(plan, w.t, g.t, m.t, v.t, ADAM, 1, block, k)
+            torch.cuda.synchronize()
+            assert w.intact() and m.intact() and v.intact() and g.intact(), (block, k)
+            assert torch.equal(w.t, ref[0].t) and torch.equal(m.t, ref[1].t) and torch.equal(v.t, ref[2].t), (block, k)
+    for block, k in ((64, 0), (256, 2), (128, 17), (256, -1)):
+        with pytest.raises(su.ShardError) as err:
+            su.shard_profile_adam_shape(plan, ref[0].t, g.t, ref[1].t, ref[2].t, ADAM, 1, block, k)
+        assert err.value.status == -1
+    plan.free()
