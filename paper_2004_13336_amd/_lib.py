@@ -113,10 +113,9 @@ def lib() -> C.CDLL:
     """The loaded library; built in-tree first if no built library is there."""
     global _lib
     if _lib is None:
-        path = os.environ.get("SHARDUPDATE_LIB", LIB_PATH)      # another build of the same library, e.g. a tuning variant
-        if path == LIB_PATH and not os.path.exists(LIB_PATH):
+        if not os.path.exists(LIB_PATH):
             build_library()
-        handle = C.CDLL(path)
+        handle = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(handle, name)          # AttributeError if the library lacks a declared symbol
             fn.restype = res

@@ -276,19 +276,21 @@ def test_full_gradient_updates_check_arguments_without_touching_the_gpu():
 
 
 def test_without_the_library_every_call_fails_loudly():
-    """There is no fallback: with no loadable libshardupdate.so the first call raises (a fresh interpreter,
-    pointed at a file that does not exist)."""
+    """There is no fallback: with no loadable libshardupdate.so the first call raises (a fresh interpreter whose
+    binding is pointed at a file that does not exist and cannot build one)."""
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    code = ("import paper_2004_13336_amd as su\n"
+    code = ("import paper_2004_13336_amd as su, paper_2004_13336_amd._lib as L\n"
+            "L.LIB_PATH = %r\n"
+            "L.build_library = lambda: None\n"
             "try:\n"
             "    su.shard_plan([8, 8], 2)\n"
             "except OSError as e:\n"
             "    print('raised', type(e).__name__)\n"
             "else:\n"
-            "    print('no error')\n")
-    env = dict(os.environ, SHARDUPDATE_LIB=os.path.join(root, "no_such_dir", "libshardupdate.so"), PYTHONPATH=root)
+            "    print('no error')\n") % os.path.join(root, "no_such_dir", "libshardupdate.so")
+    env = dict(os.environ, PYTHONPATH=root)
     proc = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, cwd=root)
     assert proc.stdout.strip() == "raised OSError", proc.stdout + proc.stderr
 
