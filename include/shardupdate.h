@@ -211,7 +211,7 @@ int unshard_format(shard_plan_t* plan, const void* gathered, int64_t row_stride,
  *   list stays among the plan's 4 cached ones.  It RUNS the copy 8 times (the destination is overwritten with what
  *   the copy writes), one untimed and three timed launches back to back in each order, and WAITS for them
  *   (hipEventSynchronize): a set-up call, not for the training loop, and refused on a capturing stream
- *   (SHARD_ESTATE).  By variable is taken if it is at least 2 % faster per launch, else by replica.  Where the
+ *   (SHARD_ESTATE).  By variable is taken if it is at least 5 % faster per launch, else by replica.  Where the
  *   order is already fixed (small pieces, a row plan, N = 1, shard_plan_set_copy_walk) nothing is launched.
  *   walk_out (may be NULL) receives the order, best_ms_out (host, 2 floats, may be NULL) the milliseconds per
  *   launch by replica and by variable.  Arguments and errors otherwise as the copy itself.

@@ -621,9 +621,11 @@ int shard_plan_tune_copy_walk(shard_plan_t* p, int copy, void* gathered, int64_t
   t.row_stride = row_stride;
   t.best_ms[0] = ms[0];
   t.best_ms[1] = ms[1];
-  // Well-placed tensors go 2 to 6 % faster by replica; colliding ones 8 to 25 % faster by variable.  A lead
-  // within the run-to-run noise of either leaves the default.
-  t.chosen = ms[1] < 0.98f * ms[0] ? SHARD_WALK_BY_VARIABLE : SHARD_WALK_BY_REPLICA;
+  // Well-placed tensors go 2 to 6 % faster by replica inside a training step; colliding ones 8 to 25 % faster by
+  // variable.  Launches of the same copy back to back flatter going by variable by up to 4 % (part of what the
+  // copy reads is still in the memory-side cache, which other kernels of a real step would have displaced), so only
+  // a lead beyond that changes the order.
+  t.chosen = ms[1] < 0.95f * ms[0] ? SHARD_WALK_BY_VARIABLE : SHARD_WALK_BY_REPLICA;
   if (walk_out) *walk_out = t.chosen;
   if (best_ms_out) {
     best_ms_out[0] = ms[0];

@@ -2,7 +2,8 @@
  * from C with nothing but the HIP runtime for device memory, and checks one pass of the path
  * (plan -> bind -> format -> momentum update with mu = 0 -> unshard) against the closed form
  * w' = w - lr (g + wd w), evaluated here in double, then repeats the update with the gradient read in place
- * from the full tensors and compares the shards bit for bit.  Exit status 0 = pass.
+ * from the full tensors and compares the shards bit for bit, runs the copy-order set-up call, and compares LAMB with its sums
+ * in the library's static array against LAMB with its sums in the workspace.  Exit status 0 = pass.
  *
  * Built by __graft_entry__.build() with gcc; run by tests/test_gpu_f_c_client.py on a GPU machine. */
 #include <hip/hip_runtime_api.h>
@@ -137,6 +138,35 @@ int main(void) {
     }
     CHECK_SU(shard_plan_set_copy_walk(plan, SHARD_WALK_AUTO));
     if (shard_plan_set_copy_walk(plan, 7) != SHARD_EINVAL) ++failures;
+  }
+  /* the set-up call that measures both orders (or reports the fixed one) leaves the full tensors as the copy does */
+  {
+    int walk = -1;
+    float ms[2] = {-1.0f, -1.0f};
+    CHECK_SU(shard_plan_tune_copy_walk(plan, SHARD_COPY_UNSHARD, gathered, 0, SHARD_F32, full_out, SHARD_F32, NULL, &walk, ms));
+    if (walk != SHARD_WALK_BY_REPLICA && walk != SHARD_WALK_BY_VARIABLE) { fprintf(stderr, "tuned order %d\n", walk); ++failures; }
+    if (shard_plan_tune_copy_walk(plan, 5, gathered, 0, SHARD_F32, full_out, SHARD_F32, NULL, &walk, ms) != SHARD_EINVAL) ++failures;
+  }
+  /* LAMB with its intermediate sums in the library's static device array: the bits of shard_update_lamb */
+  {
+    void *wa = NULL, *wb = NULL, *ma = NULL, *mb = NULL, *va = NULL, *vb = NULL;
+    float *a = (float*)malloc(sizeof(float) * (size_t)S), *b = (float*)malloc(sizeof(float) * (size_t)S);
+    shard_lamb_hp hp;
+    hp.lr = 1e-3f; hp.beta1 = 0.9f; hp.beta2 = 0.999f; hp.eps = 1e-6f; hp.weight_decay = 0.01f;
+    CHECK_HIP(hipMalloc(&wa, sizeof(float) * (size_t)S)); CHECK_HIP(hipMalloc(&wb, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMalloc(&ma, sizeof(float) * (size_t)S)); CHECK_HIP(hipMalloc(&mb, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMalloc(&va, sizeof(float) * (size_t)S)); CHECK_HIP(hipMalloc(&vb, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMemset(ma, 0, sizeof(float) * (size_t)S)); CHECK_HIP(hipMemset(mb, 0, sizeof(float) * (size_t)S));
+    CHECK_HIP(hipMemset(va, 0, sizeof(float) * (size_t)S)); CHECK_HIP(hipMemset(vb, 0, sizeof(float) * (size_t)S));
+    CHECK_SU(shard_format(plan, R, (const void* const*)full_w, SHARD_F32, wa, SHARD_F32, NULL));
+    CHECK_SU(shard_format(plan, R, (const void* const*)full_w, SHARD_F32, wb, SHARD_F32, NULL));
+    CHECK_SU(shard_update_lamb(plan, R, (float*)wa, (const float*)g, (float*)ma, (float*)va, NULL, &hp, 1, NULL, NULL, NULL));
+    CHECK_SU(shard_update_lamb_noalloc(plan, R, (float*)wb, (const float*)g, (float*)mb, (float*)vb, NULL, &hp, 1, NULL, NULL, NULL));
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_HIP(hipMemcpy(a, wa, sizeof(float) * (size_t)S, hipMemcpyDeviceToHost));
+    CHECK_HIP(hipMemcpy(b, wb, sizeof(float) * (size_t)S, hipMemcpyDeviceToHost));
+    if (memcmp(a, b, sizeof(float) * (size_t)S) != 0) { fprintf(stderr, "shard_update_lamb_noalloc differs from shard_update_lamb\n"); ++failures; }
+    free(a); free(b); hipFree(wa); hipFree(wb); hipFree(ma); hipFree(mb); hipFree(va); hipFree(vb);
   }
   /* an error path: replica id out of range */
   if (shard_format(plan, N, (const void* const*)full_w, SHARD_F32, w, SHARD_F32, NULL) != SHARD_EINVAL) ++failures;

@@ -487,7 +487,7 @@ def test_tuned_order_is_explicit_deterministic_and_every_copy_is_right():
     walk, (ms_rep, ms_var) = su.shard_plan_tune_copy_walk(plan, "unshard_format", gathered, outs)
     torch.cuda.synchronize()
     assert walk in ("by_replica", "by_variable") and ms_rep > 0.0 and ms_var > 0.0
-    assert walk == ("by_variable" if ms_var < 0.98 * ms_rep else "by_replica")
+    assert walk == ("by_variable" if ms_var < 0.95 * ms_rep else "by_replica")
     for o, f in zip(outs, flats):            # the tuning call ran the copy for real
         assert same_bits(to_host(o), f)
     assert su.shard_plan_copy_walk(plan, "unshard_format", outs, with_times=True) == (walk, (ms_rep, ms_var))
