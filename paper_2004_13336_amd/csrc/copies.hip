@@ -45,7 +45,8 @@ __global__ __launch_bounds__(kCopyBlock) void plain_copy_kernel(const u4* __rest
 // ---- shard_format / unshard_format ----------------------------------------------------------------
 // A unit is what one lane moves at a time: 8 elements when the destination is bfloat16, so that every store is
 // a 128-bit access (from float32 that is two 128-bit loads; with 4-element units and 64-bit stores the
-// float32 -> bfloat16 unshard of the 340 M-parameter model ran at 5.2 instead of 5.8 TB/s), 4 elements when it is
+// float32 -> bfloat16 unshard of the 340 M-parameter model ran at 5.2 instead of 5.8 TB/s; full tiles of that pair
+// take the lane-pair exchange in copy_units, which keeps the loads coalesced as well: 6.0 TB/s), 4 elements when it is
 // float32 (bfloat16 -> float32 then loads 64 bits per lane, which measured 4 % faster than 8-element units).
 // Consecutive lanes take consecutive units, so the accesses of a wavefront cover one contiguous span of memory.
 
@@ -129,6 +130,33 @@ template <typename Pol, int SRC, int DST, int U, bool ALL, bool UNSHARD>
 __device__ __forceinline__ void copy_units(const typename ElemOf<SRC>::type* src, typename ElemOf<DST>::type* dst,
                                            int whole, int zero_from, int len) {
   constexpr int UNIT = UnitOf<SRC, DST>::n;
+  if constexpr (ALL && U == 1 && SRC == SHARD_F32 && DST == SHARD_BF16) {
+    // A full tile of float32 -> bfloat16 (2048 elements).  Loading a thread's 8 consecutive floats takes two
+    // 128-bit loads 32 bytes apart, which leaves every load instruction of a wavefront half-used.  Instead thread
+    // t loads the 4 floats at 4t and the 4 floats at 1024 + 4t (both instructions fully coalesced), converts them,
+    // and neighbouring lanes swap halves so that the even lane holds 8 consecutive bfloat16 of the tile's first
+    // half and the odd lane 8 of its second half: every store is 128 bits.  Same bytes as the generic path.
+    constexpr int HALF = kCopyBlock * 4;
+    const int t = (int)threadIdx.x;
+    const u4 a = ld<Pol::RO>((const u4*)(src + 4 * t));
+    const u4 b = ld<Pol::RO>((const u4*)(src + HALF + 4 * t));
+    const uint32_t a0 = bf16_from_f32_bits(a.x) | (bf16_from_f32_bits(a.y) << 16);
+    const uint32_t a1 = bf16_from_f32_bits(a.z) | (bf16_from_f32_bits(a.w) << 16);
+    const uint32_t b0 = bf16_from_f32_bits(b.x) | (bf16_from_f32_bits(b.y) << 16);
+    const uint32_t b1 = bf16_from_f32_bits(b.z) | (bf16_from_f32_bits(b.w) << 16);
+    const bool odd = (t & 1) != 0;
+    // what the neighbour needs: the even lane's second-half pair goes to the odd lane, the odd lane's first-half pair
+    // to the even one (quad_perm [1,0,3,2] = lane ^ 1)
+    const uint32_t s0 = odd ? a0 : b0, s1 = odd ? a1 : b1;
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s0, 0xB1, 0xF, 0xF, false);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s1, 0xB1, 0xF, 0xF, false);
+    u4 o;
+    if (odd) { o.x = r0; o.y = r1; o.z = b0; o.w = b1; }      // elements 1024 + 4(t-1) .. 1024 + 4t + 3
+    else     { o.x = a0; o.y = a1; o.z = r0; o.w = r1; }      // elements 4t .. 4t + 7
+    uint16_t* out = (uint16_t*)dst + (odd ? HALF + 4 * (t - 1) : 4 * t);
+    st<Pol::ST>((u4*)out, o);
+    return;
+  }
   uint32_t x[U][UNIT];
 #pragma unroll
   for (int i = 0; i < U; ++i) {
