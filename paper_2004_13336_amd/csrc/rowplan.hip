@@ -199,20 +199,43 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
   }
 }
 
-// p[first * stride] + p[(first + step) * stride] + ... over the indices below n, added in exactly that order,
-// with eight loads in flight (the order is what makes results reproducible; the loads do not depend on each
-// other, only the additions do).
+// The small kernels below are all latency: a loop that loads, waits and adds once per iteration pays a trip to
+// memory for every element.  Both helpers issue kInFlight independent loads per batch (a last, partial batch is
+// predicated) and then add them in index order, so the order of the additions, and with it every result, is that
+// of the plain loop.
+constexpr int kInFlight = 8;
+
+// p[first * stride] + p[(first + step) * stride] + ... over the indices below n, added in exactly that order.
 __device__ __forceinline__ float ordered_sum(const float* __restrict__ p, int64_t stride, int first, int step, int n) {
   float s = 0.0f;
-  int i = first;
-  for (; i + 7 * step < n; i += 8 * step) {
-    float a[8];
+  for (int i = first; i < n; i += kInFlight * step) {
+    float a[kInFlight];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a[j] = p[(int64_t)(i + j * step) * stride];
+    for (int j = 0; j < kInFlight; ++j) {
+      const int ij = i + j * step;
+      a[j] = ij < n ? p[(int64_t)ij * stride] : 0.0f;
+    }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) s += a[j];
+    for (int j = 0; j < kInFlight; ++j)
+      if (i + j * step < n) s += a[j];
   }
-  for (; i < n; i += step) s += p[(int64_t)i * stride];
+  return s;
+}
+
+// This thread's share of p[0 .. n): p[t] + p[t + kBlock] + ..., t = threadIdx.x, accumulated in float64 in that order.
+__device__ __forceinline__ double thread_share_f64(const float* __restrict__ p, int64_t n) {
+  double s = 0.0;
+  for (int64_t k = threadIdx.x; k < n; k += (int64_t)kInFlight * kBlock) {
+    float a[kInFlight];
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j) {
+      const int64_t kj = k + (int64_t)j * kBlock;
+      a[j] = kj < n ? p[kj] : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < kInFlight; ++j)
+      if (k + (int64_t)j * kBlock < n) s += (double)a[j];
+  }
   return s;
 }
 
@@ -304,10 +327,8 @@ __global__ __launch_bounds__(kBlock) void rowcol_p2_kernel(const RowColVar* __re
   const int i = b - n_row_items;
   const RowColVar v = vars[i];
   const int64_t n_items = (int64_t)v.n_rb * v.n_ct;
-  double ya = 0.0, ra = 0.0;
-  for (int64_t k = threadIdx.x; k < n_items; k += kBlock) ya += (double)ypart[v.first_item + k];
-  const int64_t real_rows = real_rows_of(v, r);
-  for (int64_t k = threadIdx.x; k < real_rows; k += kBlock) ra += (double)row_state[v.row_off + k];
+  double ya = thread_share_f64(ypart + v.first_item, n_items);
+  double ra = thread_share_f64(row_state + v.row_off, real_rows_of(v, r));
   ya = block_sum_f64(ya);
   __syncthreads();
   ra = block_sum_f64(ra);
@@ -361,9 +382,7 @@ __global__ __launch_bounds__(kBlock) void adafactor_state_kernel(const RowColVar
     const ColItem it = col_items[b];
     const RowColVar v = vars[it.var];
     __shared__ float sum_r;
-    double s = 0.0;
-    for (int q = threadIdx.x; q < v.n_col_items; q += kBlock) s += (double)colitem_part[v.first_col_item + q];
-    s = block_sum_f64(s);
+    double s = block_sum_f64(thread_share_f64(colitem_part + v.first_col_item, v.n_col_items));
     if (threadIdx.x == 0) {
       const double n = (double)v.rows * (double)v.cols;
       sum_r = (float)((double)k.beta2 * (double)table_global[2 * it.var + 1] + (double)k.omb2 * (s + n * (double)k.eps1));
@@ -454,9 +473,7 @@ __global__ __launch_bounds__(kBlock) void item_total_kernel(const RowColVar* __r
   const int i = blockIdx.x;
   const RowColVar v = vars[i];
   const int64_t n_items = (int64_t)v.n_rb * v.n_ct;
-  double a = 0.0;
-  for (int64_t q = threadIdx.x; q < n_items; q += kBlock) a += (double)part[v.first_item + q];
-  a = block_sum_f64(a);
+  double a = block_sum_f64(thread_share_f64(part + v.first_item, n_items));
   if (threadIdx.x == 0) {
     const float fa = (float)a;
     if (local_out) local_out[i] = fa;

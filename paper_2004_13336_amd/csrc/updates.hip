@@ -396,23 +396,23 @@ __global__ __launch_bounds__(kBlock) void norm_reduce_kernel(const VarDesc* __re
   const int i = blockIdx.x;
   const VarDesc vd = vars[i];
   double a = 0.0, b = 0.0;
-  // the pair of a chunk in one 8-byte load, four loads in flight; each thread still adds its chunks in rising order
+  // the pair of a chunk in one 8-byte load, eight loads in flight (a last, partial batch is predicated rather than
+  // taken one dependent load at a time: this kernel is all latency); each thread still adds its chunks in rising order
   const float2* pairs = reinterpret_cast<const float2*>(chunk_sums) + vd.first_chunk;
-  int c = threadIdx.x;
-  for (; c + 3 * kBlock < vd.n_chunks; c += 4 * kBlock) {
-    float2 x[4];
+  for (int c = threadIdx.x; c < vd.n_chunks; c += 8 * kBlock) {
+    float2 x[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) x[j] = pairs[c + j * kBlock];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      a += (double)x[j].x;
-      b += (double)x[j].y;
+    for (int j = 0; j < 8; ++j) {
+      const int cj = c + j * kBlock;
+      x[j] = cj < vd.n_chunks ? pairs[cj] : float2{0.0f, 0.0f};
     }
-  }
-  for (; c < vd.n_chunks; c += kBlock) {
-    const float2 x = pairs[c];
-    a += (double)x.x;
-    b += (double)x.y;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (c + j * kBlock < vd.n_chunks) {
+        a += (double)x[j].x;
+        b += (double)x[j].y;
+      }
+    }
   }
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) {
