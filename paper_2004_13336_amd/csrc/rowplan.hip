@@ -200,9 +200,10 @@ __global__ __launch_bounds__(kBlock) void rowcol_p1_kernel(const RowColVar* __re
 }
 
 // The small kernels below are all latency: a loop that loads, waits and adds once per iteration pays a trip to
-// memory for every element.  Both helpers issue kInFlight independent loads per batch (a last, partial batch is
-// predicated) and then add them in index order, so the order of the additions, and with it every result, is that
-// of the plain loop.
+// memory for every element.  Both helpers issue kInFlight independent, unconditional loads per batch (in a last,
+// partial batch the indices past the end are redirected to the batch's first element and only the additions are
+// predicated: a conditional load makes the compiler wait for each one) and then add them in index order, so the
+// order of the additions, and with it every result, is that of the plain loop.
 constexpr int kInFlight = 8;
 
 // p[first * stride] + p[(first + step) * stride] + ... over the indices below n, added in exactly that order.
@@ -213,7 +214,7 @@ __device__ __forceinline__ float ordered_sum(const float* __restrict__ p, int64_
 #pragma unroll
     for (int j = 0; j < kInFlight; ++j) {
       const int ij = i + j * step;
-      a[j] = ij < n ? p[(int64_t)ij * stride] : 0.0f;
+      a[j] = p[(int64_t)(ij < n ? ij : i) * stride];
     }
 #pragma unroll
     for (int j = 0; j < kInFlight; ++j)
@@ -230,7 +231,7 @@ __device__ __forceinline__ double thread_share_f64(const float* __restrict__ p, 
 #pragma unroll
     for (int j = 0; j < kInFlight; ++j) {
       const int64_t kj = k + (int64_t)j * kBlock;
-      a[j] = kj < n ? p[kj] : 0.0f;
+      a[j] = p[kj < n ? kj : k];
     }
 #pragma unroll
     for (int j = 0; j < kInFlight; ++j)

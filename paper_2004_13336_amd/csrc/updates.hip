@@ -396,15 +396,16 @@ __global__ __launch_bounds__(kBlock) void norm_reduce_kernel(const VarDesc* __re
   const int i = blockIdx.x;
   const VarDesc vd = vars[i];
   double a = 0.0, b = 0.0;
-  // the pair of a chunk in one 8-byte load, eight loads in flight (a last, partial batch is predicated rather than
-  // taken one dependent load at a time: this kernel is all latency); each thread still adds its chunks in rising order
+  // the pair of a chunk in one 8-byte load, eight unconditional loads in flight (in a last, partial batch the
+  // indices past the end are redirected, and only the additions are predicated: a conditional load would make the
+  // compiler wait for each one, and this kernel is all latency); each thread still adds its chunks in rising order
   const float2* pairs = reinterpret_cast<const float2*>(chunk_sums) + vd.first_chunk;
   for (int c = threadIdx.x; c < vd.n_chunks; c += 8 * kBlock) {
     float2 x[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int cj = c + j * kBlock;
-      x[j] = cj < vd.n_chunks ? pairs[cj] : float2{0.0f, 0.0f};
+      x[j] = pairs[cj < vd.n_chunks ? cj : c];       // past the end: a pair that is loaded anyway, not added
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
