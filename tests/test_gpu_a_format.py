@@ -252,6 +252,52 @@ def test_full_size_format_round_trip(name, N, replicas):
     plan.free()
 
 
+def test_full_size_converting_copies_bert_large_8_replicas():
+    """The converting copies at the benchmark's size (340 M parameters, 8 replicas: the stages
+    unshard_format_f32_to_bf16 and shard_format_bf16_to_f32 time exactly these launches): float32 shards restored
+    as bfloat16 tensors, bfloat16 tensors formatted into float32 shards, float32 tensors into a bfloat16
+    gathered buffer; every element against the oracle's conversion of the same bits."""
+    cfg = [c for c in CONFIGS if c.name == "bert_large"][0]
+    N, numel = 8, cfg.numel
+    print("full-size converting copies", cfg.name, N, flush=True)
+    oplan = oracle.make_plan(numel, N, 8)
+    plan = su.shard_plan_bind(su.shard_plan(numel, N, 8))
+    flats = _bit_tensors(cfg.seed + 1, numel, "f32")              # NaN payloads, infinities, denormals included
+    dev_full = [to_dev(f) for f in flats]
+    gathered = su.gathered_empty(plan)
+    su.shard_format_all(plan, dev_full, gathered)
+    # float32 gathered buffer -> bfloat16 full tensors, in both orders of the work items
+    want16 = [oracle.f32_to_bf16_bits(f) for f in flats]
+    outs16 = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in numel]
+    for walk in ("by_replica", "by_variable"):
+        su.shard_plan_set_copy_walk(plan, walk)
+        for o in outs16:
+            o.view(torch.int16).fill_(0x5A5A)
+        su.unshard_format(plan, gathered, outs16)
+        for i, (o, w) in enumerate(zip(outs16, want16)):
+            assert same_bits(to_host(o), w), (walk, i)
+    # float32 full tensors -> bfloat16 gathered buffer: row r is the oracle's shard r, converted
+    rows16 = torch.empty((N, oplan.S), dtype=torch.bfloat16, device=DEV)
+    for walk in ("by_replica", "by_variable"):
+        su.shard_plan_set_copy_walk(plan, walk)
+        rows16.view(torch.int16).fill_(0x5A5A)
+        su.shard_format_all(plan, dev_full, rows16)
+        for r in (0, 3, 7):
+            assert same_bits(to_host(rows16[r]), oracle.shard_format(oplan, r, flats, dst="bf16")), (walk, r)
+    # one replica at a time gives the same rows
+    one = torch.empty(oplan.S, dtype=torch.bfloat16, device=DEV)
+    for r in (0, 7):
+        su.shard_format(plan, r, dev_full, one)
+        assert torch.equal(one.view(torch.int16), rows16[r].view(torch.int16)), r
+    # bfloat16 full tensors -> float32 shard
+    su.shard_plan_set_copy_walk(plan, "auto")
+    out32 = torch.empty(oplan.S, dtype=torch.float32, device=DEV)
+    for r in (0, 7):
+        su.shard_format(plan, r, outs16, out32)
+        assert same_bits(to_host(out32), oracle.shard_format(oplan, r, want16, dst="f32")), r
+    plan.free()
+
+
 def test_formatting_stress_1p5b_128_replicas_bf16():
     """771 variables, 128 replicas: [1600]-element variables leave 13 real + 3 padded slots per
     replica and hundreds of all-padding pieces on the last replicas."""
