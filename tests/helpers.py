@@ -74,6 +74,25 @@ def assert_second_moment_close(got, ref, steps: int = 1, what: str = "v"):
     assert np.all(d <= bound), "%s: max excess %.3g" % (what, float(np.max(d / bound)))
 
 
+def assert_sumsq_close(got, ref, numel: Sequence[int], what: str = "sums"):
+    """Per-variable [sum w^2, sum u^2] tables.  Sums of squares have no cancellation of their own: relative 3e-6
+    against the float64 sums.  An element of u can be the small difference of larger terms, though (LAMB's first
+    moment beta1 m + (1 - beta1) g, LARS's g + wd w), and float32 then leaves it an absolute error of a few 1e-7 of
+    its uncancelled size (at most about 1 for these optimizers' normalised updates) however small u itself is; by
+    Cauchy-Schwarz the sum over n elements moves by at most 2 sqrt(n sum u^2) x that.  Only variables of a handful
+    of elements can have this term exceed the relative one."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1, 2)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1, 2)
+    n = np.asarray(numel, dtype=np.float64)
+    assert got.shape == ref.shape == (n.size, 2), (got.shape, ref.shape, n.size)
+    tol_w = 3e-6 * ref[:, 0] + 1e-30
+    tol_u = 3e-6 * ref[:, 1] + 2.0 * np.sqrt(n * ref[:, 1]) * 5e-7 + 1e-30
+    bad_w = np.abs(got[:, 0] - ref[:, 0]) > tol_w
+    bad_u = np.abs(got[:, 1] - ref[:, 1]) > tol_u
+    assert not bad_w.any(), (what, "sum w^2", np.nonzero(bad_w)[0], got[bad_w, 0], ref[bad_w, 0])
+    assert not bad_u.any(), (what, "sum u^2", np.nonzero(bad_u)[0], got[bad_u, 1], ref[bad_u, 1])
+
+
 def pads_are_zero(plan: oracle.Plan, r: int, shard: np.ndarray) -> bool:
     # real_count counts from the piece start in both plan kinds (row plans pad inside the piece too)
     bits = shard.view(np.uint32 if shard.dtype == np.float32 else np.uint16)

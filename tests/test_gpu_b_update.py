@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_2004_13336_amd as su
-from helpers import (DEV, assert_first_moment_close, assert_second_moment_close, assert_weights_close, f32_hp,
+from helpers import (DEV, assert_first_moment_close, assert_second_moment_close, assert_sumsq_close, assert_weights_close, f32_hp,
                      gen_weights_grads, pads_are_zero, same_bits, shards_of, to_dev, to_host)
 from workloads import CONFIGS, normal_f32
 
@@ -503,7 +503,8 @@ def _random_plan_case(seed):
     return numel, N, align, chunk, flags
 
 
-@pytest.mark.parametrize("seed", range(10))
+# seed 101: a one-element variable whose first moment cancels to a fiftieth of its terms at the second step
+@pytest.mark.parametrize("seed", list(range(16)) + [101])
 def test_random_plans_every_update_against_the_unsharded_oracle(seed):
     """Two steps of each optimizer on all replicas of a random plan, put back together and compared
     with the unsharded oracle; padding stays +0.0 throughout."""
@@ -551,7 +552,7 @@ def test_random_plans_every_update_against_the_unsharded_oracle(seed):
         gs, G = grads(t)
         uw, um, uv, usums = oracle.lamb_unsharded_step(uw, gs, um, uv, LAMB, t, flags)
         _, total = _lamb_all_replicas(plan, oplan, W, G, M, V, LAMB, t)
-        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        assert_sumsq_close(to_host(total), usums, numel, "lamb t=%d" % t)
         check(uw, W, "lamb", t)
     uw = [w.copy() for w in ws]; um = [np.zeros_like(w) for w in ws]
     W = dev_rows(W0); M = zeros_like_rows(W)
@@ -559,7 +560,7 @@ def test_random_plans_every_update_against_the_unsharded_oracle(seed):
         gs, G = grads(t)
         uw, um, usums = oracle.lars_unsharded_step(uw, gs, um, LARS, flags)
         _, total = _lars_all_replicas(plan, oplan, W, G, M, LARS)
-        np.testing.assert_allclose(to_host(total).astype(np.float64), usums, rtol=3e-6, atol=1e-30)
+        assert_sumsq_close(to_host(total), usums, numel, "lars t=%d" % t)
         check(uw, W, "lars", t)
     plan.free()
 
